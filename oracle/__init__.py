@@ -1,0 +1,179 @@
+"""CPU oracle for the Based sequence mixer (arXiv 2402.18668) -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end over ``based_oracle.c`` (plain C, fp64).  It shares no code
+with the HIP library; only the tests, the smoke check and the benchmark's CPU-baseline
+leg may import it.  The product path never does.
+
+Array conventions: ``q, k`` are ``[U, N, d']``, ``v, y`` are ``[U, N, d_v]`` float64,
+``S`` is ``[U, D, d_v]`` and ``z`` is ``[U, D]`` with ``D = 1 + d' + d'^2`` (Sec. 4) in the
+feature order ``[1, x_a, x_a x_b / sqrt(2) at 1 + d' + a d' + b]`` (Eq. 4).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "based_oracle.c")
+_LIB = os.path.join(_HERE, "libbased_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (``-O2 -fopenmp``); returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-std=c99", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        i = ctypes.c_int
+        lib.oracle_threads.restype = i
+        lib.oracle_feature_dim.restype = i
+        lib.oracle_feature_dim.argtypes = [i]
+        lib.oracle_state_size_symmetric.restype = ctypes.c_long
+        lib.oracle_state_size_symmetric.argtypes = [i, i]
+        lib.oracle_feature_map.argtypes = [dp, i, dp]
+        lib.oracle_linattn_quadratic.argtypes = [dp, dp, dp, dp, i, i, i, i]
+        lib.oracle_linattn_rows.argtypes = [dp, dp, dp, ip, i, dp, i, i, i, i]
+        lib.oracle_linattn_state.argtypes = [dp, dp, dp, dp, i, i, i, i]
+        lib.oracle_linattn_recurrent.argtypes = [dp, dp, dp, dp, dp, dp, i, i, i, i]
+        lib.oracle_swa.argtypes = [dp, dp, dp, dp, i, i, i, i, ctypes.c_double]
+        lib.oracle_swa_rows.argtypes = [dp, dp, dp, ip, i, dp, i, i, i, i, ctypes.c_double]
+        for name in ("oracle_feature_map", "oracle_linattn_quadratic", "oracle_linattn_rows",
+                     "oracle_linattn_state", "oracle_linattn_recurrent", "oracle_swa",
+                     "oracle_swa_rows"):
+            getattr(lib, name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _d(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def threads() -> int:
+    """OpenMP threads the oracle will use."""
+    return int(_load().oracle_threads())
+
+
+def feature_dim(dp: int) -> int:
+    """D = 1 + d' + d'^2 (Sec. 4)."""
+    return int(_load().oracle_feature_dim(int(dp)))
+
+
+def state_size_symmetric(dp: int, dv: int) -> int:
+    """(d + 1)(1 + 3d'/2 + d'^2/2): the recurrent-state size of the state-size appendix."""
+    return int(_load().oracle_state_size_symmetric(int(dp), int(dv)))
+
+
+def feature_map(x) -> np.ndarray:
+    """phi(x) of Eq. 4 applied along the last axis."""
+    x = np.asarray(x, dtype=np.float64)
+    dp = x.shape[-1]
+    D = feature_dim(dp)
+    flat = np.ascontiguousarray(x.reshape(-1, dp))
+    out = np.empty((flat.shape[0], D), dtype=np.float64)
+    lib = _load()
+    for r in range(flat.shape[0]):
+        _, pin = _d(flat[r])
+        lib.oracle_feature_map(pin, dp, out[r].ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    return out.reshape(x.shape[:-1] + (D,))
+
+
+def _shapes(q, k, v):
+    assert q.ndim == 3 and k.shape == q.shape and v.ndim == 3 and v.shape[:2] == q.shape[:2]
+    return q.shape[0], q.shape[1], q.shape[2], v.shape[2]
+
+
+def linattn_quadratic(q, k, v) -> np.ndarray:
+    """Eq. 2 with the kernel of Eq. 4, every row, zero initial state."""
+    q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)
+    U, N, dp, dv = _shapes(q, k, v)
+    y = np.empty((U, N, dv), dtype=np.float64)
+    _load().oracle_linattn_quadratic(pq, pk, pv, y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                     U, N, dp, dv)
+    return y
+
+
+def linattn_rows(q, k, v, rows) -> np.ndarray:
+    """Eq. 2 at the listed token indices only; returns ``[U, len(rows), d_v]``."""
+    q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)
+    U, N, dp, dv = _shapes(q, k, v)
+    rows, pr = _i64(rows)
+    assert rows.ndim == 1 and (rows >= 0).all() and (rows < N).all()
+    y = np.empty((U, rows.shape[0], dv), dtype=np.float64)
+    _load().oracle_linattn_rows(pq, pk, pv, pr, rows.shape[0],
+                                y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), U, N, dp, dv)
+    return y
+
+
+def linattn_state(k, v, S=None, z=None):
+    """S = S0 + sum_j phi(k_j) v_j^T and z = z0 + sum_j phi(k_j) (Sec. 3.1); returns copies."""
+    k, pk = _d(k); v, pv = _d(v)
+    U, N, dp = k.shape
+    dv = v.shape[2]
+    D = feature_dim(dp)
+    S = np.zeros((U, D, dv)) if S is None else np.array(S, dtype=np.float64, order="C")
+    z = np.zeros((U, D)) if z is None else np.array(z, dtype=np.float64, order="C")
+    assert S.shape == (U, D, dv) and z.shape == (U, D)
+    p = ctypes.POINTER(ctypes.c_double)
+    _load().oracle_linattn_state(pk, pv, S.ctypes.data_as(p), z.ctypes.data_as(p), U, N, dp, dv)
+    return S, z
+
+
+def linattn_recurrent(q, k, v, S=None, z=None):
+    """Eq. 3 from a given state (zero if omitted); returns ``(y, S_final, z_final)``."""
+    q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)
+    U, N, dp, dv = _shapes(q, k, v)
+    D = feature_dim(dp)
+    S = np.zeros((U, D, dv)) if S is None else np.array(S, dtype=np.float64, order="C")
+    z = np.zeros((U, D)) if z is None else np.array(z, dtype=np.float64, order="C")
+    assert S.shape == (U, D, dv) and z.shape == (U, D)
+    y = np.empty((U, N, dv), dtype=np.float64)
+    p = ctypes.POINTER(ctypes.c_double)
+    _load().oracle_linattn_recurrent(pq, pk, pv, y.ctypes.data_as(p), S.ctypes.data_as(p),
+                                     z.ctypes.data_as(p), U, N, dp, dv)
+    return y, S, z
+
+
+def swa(q, k, v, w: int, scale: float) -> np.ndarray:
+    """Causal sliding-window softmax attention (Sec. 3.2 on Eq. 1), every row."""
+    q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)
+    U, N, dh = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and w >= 1
+    y = np.empty((U, N, dh), dtype=np.float64)
+    _load().oracle_swa(pq, pk, pv, y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), U, N, dh,
+                       int(w), float(scale))
+    return y
+
+
+def swa_rows(q, k, v, w: int, scale: float, rows) -> np.ndarray:
+    """The same at the listed token indices only; returns ``[U, len(rows), d_h]``."""
+    q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)
+    U, N, dh = q.shape
+    rows, pr = _i64(rows)
+    assert rows.ndim == 1 and (rows >= 0).all() and (rows < N).all()
+    y = np.empty((U, rows.shape[0], dh), dtype=np.float64)
+    _load().oracle_swa_rows(pq, pk, pv, pr, rows.shape[0],
+                            y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), U, N, dh, int(w),
+                            float(scale))
+    return y

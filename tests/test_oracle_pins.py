@@ -1,0 +1,336 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something other than itself
+(closed forms, equivalent forms written independently in numpy, a pure-Python brute force,
+textbook special cases, a library attention routine, and the dimension facts the paper prints).
+CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# --------------------------------------------------------------------------------------------
+# pure-Python brute force (independent authoring path; tiny sizes only)
+# --------------------------------------------------------------------------------------------
+def brute_linattn(q, k, v):
+    U, N, dp = len(q), len(q[0]), len(q[0][0])
+    dv = len(v[0][0])
+    out = [[[0.0] * dv for _ in range(N)] for _ in range(U)]
+    for u in range(U):
+        for i in range(N):
+            den = 0.0
+            num = [0.0] * dv
+            for j in range(i + 1):
+                x = 0.0
+                for a in range(dp):
+                    x += q[u][i][a] * k[u][j][a]
+                w = 1.0 + x + x * x / 2.0
+                den += w
+                for c in range(dv):
+                    num[c] += w * v[u][j][c]
+            out[u][i] = [n / den for n in num]
+    return out
+
+
+def brute_swa(q, k, v, w, scale):
+    U, N, dh = len(q), len(q[0]), len(q[0][0])
+    out = [[[0.0] * dh for _ in range(N)] for _ in range(U)]
+    for u in range(U):
+        for i in range(N):
+            js = [j for j in range(N) if j <= i and j > i - w]
+            logits = [scale * sum(q[u][i][a] * k[u][j][a] for a in range(dh)) for j in js]
+            m = max(logits)
+            e = [math.exp(l - m) for l in logits]
+            s = sum(e)
+            for c in range(dh):
+                out[u][i][c] = sum(e[t] * v[u][j][c] for t, j in enumerate(js)) / s
+    return out
+
+
+# --------------------------------------------------------------------------------------------
+# dimension facts printed in the paper
+# --------------------------------------------------------------------------------------------
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "state_sizes.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, a, b = line.split()
+            rows.append((key, int(a), int(b)))
+    return rows
+
+
+def test_dimension_facts_from_the_paper():
+    rows = _golden_rows()
+    assert len(rows) >= 7
+    for key, arg, expected in rows:
+        if key == "D":
+            assert oracle.feature_dim(arg) == expected
+        elif key == "SYM":
+            # per-column count: (d + 1) * (...) with d = 0
+            assert oracle.state_size_symmetric(arg, 0) == expected
+        elif key == "TILES":
+            assert arg // 16 == expected
+        elif key == "BLOCKS":
+            assert arg // 16 // 8 == expected
+    # the full formula with its (d + 1) factor, d = 64, d' = 16
+    assert oracle.state_size_symmetric(16, 64) == 65 * 153
+    assert oracle.feature_dim(32) == 1057
+
+
+# --------------------------------------------------------------------------------------------
+# Eq. 4: phi(q).phi(k) = 1 + q.k + (q.k)^2 / 2, and the feature order
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dp", [1, 2, 4, 16, 32])
+def test_feature_map_closed_form(dp):
+    g = rng(dp)
+    for scale in (1e-3, 1.0, 30.0):
+        q = g.standard_normal((64, dp)) * scale
+        k = g.standard_normal((64, dp)) * scale
+        pq, pk = oracle.feature_map(q), oracle.feature_map(k)
+        assert pq.shape == (64, 1 + dp + dp * dp)
+        lhs = (pq * pk).sum(-1)
+        x = (q * k).sum(-1)
+        rhs = 1.0 + x + 0.5 * x * x
+        assert np.allclose(lhs, rhs, rtol=1e-12, atol=1e-12 * max(1.0, scale ** 4))
+
+
+def test_feature_map_order_and_scaling():
+    x = np.array([2.0, 3.0, 5.0])
+    phi = oracle.feature_map(x)
+    assert phi[0] == 1.0
+    assert list(phi[1:4]) == [2.0, 3.0, 5.0]
+    # row-major (a, b) block: index 1 + d' + a d' + b holds x_a x_b / sqrt(2)
+    blk = phi[4:].reshape(3, 3)
+    assert np.allclose(blk, np.outer(x, x) / math.sqrt(2.0), rtol=0, atol=1e-15)
+    assert blk[0, 2] == blk[2, 0]
+    # adversarial: orthogonal q, k => kernel is exactly 1
+    q = np.array([1.0, 0.0, 0.0]); k = np.array([0.0, 7.0, 0.0])
+    assert (oracle.feature_map(q) * oracle.feature_map(k)).sum() == 1.0
+
+
+# --------------------------------------------------------------------------------------------
+# brute force
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("U,N,dp,dv", [(1, 1, 1, 1), (2, 7, 3, 2), (1, 32, 4, 4), (3, 13, 2, 5)])
+def test_linattn_vs_pure_python(U, N, dp, dv):
+    g = rng(100 + N)
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp)); v = g.standard_normal((U, N, dv))
+    want = np.array(brute_linattn(q.tolist(), k.tolist(), v.tolist()))
+    assert np.allclose(oracle.linattn_quadratic(q, k, v), want, rtol=1e-12, atol=1e-13)
+    rows = np.array(sorted({0, N // 2, N - 1}))
+    assert np.allclose(oracle.linattn_rows(q, k, v, rows), want[:, rows], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("U,N,dh,w", [(1, 1, 1, 1), (2, 9, 3, 4), (1, 20, 4, 64), (2, 17, 2, 1), (1, 12, 3, 12)])
+def test_swa_vs_pure_python(U, N, dh, w):
+    g = rng(200 + N)
+    q = g.standard_normal((U, N, dh)); k = g.standard_normal((U, N, dh)); v = g.standard_normal((U, N, dh))
+    want = np.array(brute_swa(q.tolist(), k.tolist(), v.tolist(), w, 0.7))
+    assert np.allclose(oracle.swa(q, k, v, w, 0.7), want, rtol=1e-12, atol=1e-13)
+    rows = np.array(sorted({0, N // 3, N - 1}))
+    assert np.allclose(oracle.swa_rows(q, k, v, w, 0.7, rows), want[:, rows], rtol=1e-12, atol=1e-13)
+
+
+# --------------------------------------------------------------------------------------------
+# equality of forms: parallel (Eq. 2) == recurrent (Eq. 3) == tile split (Sec. 4) == cumsum form
+# --------------------------------------------------------------------------------------------
+def np_phi(x):
+    """numpy feature map written separately from the oracle (explicit outer product)."""
+    dp = x.shape[-1]
+    second = (x[..., :, None] * x[..., None, :]).reshape(x.shape[:-1] + (dp * dp,)) / np.sqrt(2.0)
+    return np.concatenate([np.ones(x.shape[:-1] + (1,)), x, second], axis=-1)
+
+
+def np_cumsum_form(q, k, v):
+    """Materialised-feature cumsum form of the appendix listing (no epsilon)."""
+    pq, pk = np_phi(q), np_phi(k)
+    kv = np.cumsum(pk[..., :, None] * v[..., None, :], axis=1)      # [U, N, D, dv]
+    num = np.einsum("unf,unfc->unc", pq, kv)
+    den = np.einsum("unf,unf->un", pq, np.cumsum(pk, axis=1))
+    return num / den[..., None]
+
+
+def np_chunked(q, k, v, C):
+    """Tile split of Sec. 4: on-diagonal quadratic block + off-diagonal readout of the running state."""
+    U, N, dp = q.shape
+    dv = v.shape[-1]
+    D = 1 + dp + dp * dp
+    S = np.zeros((U, D, dv)); z = np.zeros((U, D))
+    y = np.empty((U, N, dv))
+    for c0 in range(0, N, C):
+        c1 = min(N, c0 + C)
+        qc, kc, vc = q[:, c0:c1], k[:, c0:c1], v[:, c0:c1]
+        A = np.einsum("uia,uja->uij", qc, kc)
+        P = np.tril(np.ones((c1 - c0, c1 - c0)))[None] * (1.0 + A + 0.5 * A * A)
+        pq, pk = np_phi(qc), np_phi(kc)
+        num = np.einsum("uij,ujc->uic", P, vc) + np.einsum("uif,ufc->uic", pq, S)
+        den = P.sum(-1) + np.einsum("uif,uf->ui", pq, z)
+        y[:, c0:c1] = num / den[..., None]
+        S += np.einsum("ujf,ujc->ufc", pk, vc)
+        z += pk.sum(1)
+    return y, S, z
+
+
+@pytest.mark.parametrize("U,N,dp,dv", [(2, 50, 4, 6), (1, 100, 16, 8), (1, 37, 8, 3)])
+def test_forms_agree(U, N, dp, dv):
+    g = rng(300 + N)
+    q = g.standard_normal((U, N, dp)) * 0.7; k = g.standard_normal((U, N, dp)) * 0.7
+    v = g.standard_normal((U, N, dv))
+    yq = oracle.linattn_quadratic(q, k, v)
+    yr, Sr, zr = oracle.linattn_recurrent(q, k, v)
+    assert np.allclose(yq, yr, rtol=1e-10, atol=1e-12)
+    assert np.allclose(yq, np_cumsum_form(q, k, v), rtol=1e-10, atol=1e-12)
+    for C in (1, 16, 7, N, N + 5):
+        yc, Sc, zc = np_chunked(q, k, v, C)
+        assert np.allclose(yq, yc, rtol=1e-10, atol=1e-12), C
+        assert np.allclose(Sr, Sc, rtol=1e-10, atol=1e-12)
+        assert np.allclose(zr, zc, rtol=1e-10, atol=1e-12)
+    S, z = oracle.linattn_state(k, v)
+    assert np.allclose(S, Sr, rtol=1e-12, atol=1e-12) and np.allclose(z, zr, rtol=1e-12, atol=1e-12)
+    # state against the independent numpy feature map
+    assert np.allclose(S, np.einsum("ujf,ujc->ufc", np_phi(k), v), rtol=1e-12, atol=1e-12)
+    assert np.allclose(z, np_phi(k).sum(1), rtol=1e-12, atol=1e-12)
+
+
+def test_recurrent_continuation_equals_one_pass():
+    """Split prefill: running the recurrent view on a suffix from the prefix's state gives the
+    quadratic view's rows for that suffix; a single decode step is the N = 1 case."""
+    g = rng(7)
+    U, N, dp, dv, N1 = 2, 60, 4, 5, 23
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp)); v = g.standard_normal((U, N, dv))
+    yq = oracle.linattn_quadratic(q, k, v)
+    S1, z1 = oracle.linattn_state(k[:, :N1], v[:, :N1])
+    y2, S2, z2 = oracle.linattn_recurrent(q[:, N1:], k[:, N1:], v[:, N1:], S1, z1)
+    assert np.allclose(y2, yq[:, N1:], rtol=1e-10, atol=1e-12)
+    Sf, zf = oracle.linattn_state(k, v)
+    assert np.allclose(S2, Sf, rtol=1e-12, atol=1e-12) and np.allclose(z2, zf, rtol=1e-12, atol=1e-12)
+    # adding to a given state
+    S3, z3 = oracle.linattn_state(k[:, N1:], v[:, N1:], S1, z1)
+    assert np.allclose(S3, Sf, rtol=1e-12, atol=1e-12) and np.allclose(z3, zf, rtol=1e-12, atol=1e-12)
+    # one token at a time
+    S, z = S1, z1
+    for t in range(N1, N1 + 4):
+        yt, S, z = oracle.linattn_recurrent(q[:, t:t + 1], k[:, t:t + 1], v[:, t:t + 1], S, z)
+        assert np.allclose(yt[:, 0], yq[:, t], rtol=1e-10, atol=1e-12)
+
+
+# --------------------------------------------------------------------------------------------
+# special cases with known answers
+# --------------------------------------------------------------------------------------------
+def test_linattn_special_cases():
+    g = rng(11)
+    U, N, dp, dv = 2, 40, 4, 3
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp)); v = g.standard_normal((U, N, dv))
+    running_mean = np.cumsum(v, axis=1) / np.arange(1, N + 1)[None, :, None]
+    # q == 0 or k == 0: kernel is 1, output is the running mean of v (0th-order term)
+    assert np.allclose(oracle.linattn_quadratic(np.zeros_like(q), k, v), running_mean, rtol=1e-12, atol=1e-13)
+    assert np.allclose(oracle.linattn_quadratic(q, np.zeros_like(k), v), running_mean, rtol=1e-12, atol=1e-13)
+    assert np.allclose(oracle.linattn_recurrent(np.zeros_like(q), k, v)[0], running_mean, rtol=1e-12, atol=1e-13)
+    # first row is v_0
+    y = oracle.linattn_quadratic(q, k, v)
+    assert np.allclose(y[:, 0], v[:, 0], rtol=1e-14, atol=0)
+    # constant v passes through; outputs are convex combinations (kernel is positive)
+    c = np.broadcast_to(np.array([1.5, -2.0, 0.25]), v.shape).copy()
+    assert np.allclose(oracle.linattn_quadratic(q, k, c), c, rtol=1e-12, atol=1e-13)
+    lo = np.minimum.accumulate(v, axis=1); hi = np.maximum.accumulate(v, axis=1)
+    assert (y >= lo - 1e-12).all() and (y <= hi + 1e-12).all()
+    # state: row 0 is sum of v, z[0] counts tokens, (a,b) and (b,a) rows are identical
+    S, z = oracle.linattn_state(k, v)
+    assert np.allclose(S[:, 0], v.sum(1), rtol=1e-13, atol=1e-13)
+    assert np.allclose(z[:, 0], N)
+    assert np.allclose(S[:, 1:1 + dp], np.einsum("uja,ujc->uac", k, v), rtol=1e-12, atol=1e-13)
+    blk = S[:, 1 + dp:].reshape(U, dp, dp, dv)
+    assert np.array_equal(blk, blk.transpose(0, 2, 1, 3))
+    zb = z[:, 1 + dp:].reshape(U, dp, dp)
+    assert np.allclose(zb, np.einsum("uja,ujb->uab", k, k) / np.sqrt(2.0), rtol=1e-12, atol=1e-13)
+
+
+def test_linattn_tracks_softmax_for_small_logits():
+    """For |q.k| <= 0.1 the Taylor kernel is within |x|^3 e^|x| / 6 of exp(x), so the output agrees
+    with unscaled causal softmax attention to that order (library routine, fp64)."""
+    g = rng(13)
+    U, N, dp, dv = 2, 48, 8, 4
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp))
+    q *= 0.3 / np.abs(q).max() / np.sqrt(dp); k *= 0.3 / np.abs(k).max() / np.sqrt(dp)
+    v = g.standard_normal((U, N, dv))
+    x = np.abs(np.einsum("uia,uja->uij", q, k)).max()
+    assert x <= 0.1
+    tq, tk, tv = (torch.from_numpy(a)[None] for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=1.0)[0].numpy()
+    bound = 2.5 * (x ** 3 * math.exp(x) / 6.0) * np.abs(v).max()
+    assert np.abs(oracle.linattn_quadratic(q, k, v) - ref).max() <= bound
+    # sign/term check: dropping the quadratic term would exceed this bound
+    first_order_gap = 0.25 * x * x * np.abs(v).max()
+    assert bound < first_order_gap
+
+
+# --------------------------------------------------------------------------------------------
+# sliding-window attention
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,dh,w", [(33, 8, 33), (40, 16, 64), (17, 4, 1000)])
+def test_swa_full_window_equals_library_causal_attention(N, dh, w):
+    g = rng(400 + N)
+    U = 3
+    q = g.standard_normal((U, N, dh)); k = g.standard_normal((U, N, dh)); v = g.standard_normal((U, N, dh))
+    scale = 1.0 / math.sqrt(dh)
+    tq, tk, tv = (torch.from_numpy(a)[None] for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale)[0].numpy()
+    assert np.allclose(oracle.swa(q, k, v, w, scale), ref, rtol=1e-11, atol=1e-12)
+
+
+def test_swa_banded_equals_library_attention_with_band_mask():
+    g = rng(17)
+    U, N, dh, w = 2, 50, 8, 7
+    q = g.standard_normal((U, N, dh)); k = g.standard_normal((U, N, dh)); v = g.standard_normal((U, N, dh))
+    i = np.arange(N)[:, None]; j = np.arange(N)[None, :]
+    mask = torch.from_numpy((j <= i) & (j > i - w))
+    tq, tk, tv = (torch.from_numpy(a)[None] for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=0.5)[0].numpy()
+    assert np.allclose(oracle.swa(q, k, v, w, 0.5), ref, rtol=1e-11, atol=1e-12)
+
+
+def test_swa_special_cases():
+    g = rng(19)
+    U, N, dh, w = 2, 30, 4, 5
+    q = g.standard_normal((U, N, dh)); k = g.standard_normal((U, N, dh)); v = g.standard_normal((U, N, dh))
+    # w = 1: every token sees only itself
+    assert np.allclose(oracle.swa(q, k, v, 1, 0.5), v, rtol=1e-14, atol=0)
+    # q = 0: mean of the last min(i + 1, w) values
+    want = np.stack([v[:, max(0, i - w + 1):i + 1].mean(1) for i in range(N)], axis=1)
+    assert np.allclose(oracle.swa(np.zeros_like(q), k, v, w, 0.5), want, rtol=1e-12, atol=1e-13)
+    # adding a constant to every logit of a row changes nothing: shift k by a vector c with q.c constant
+    # is not available in general, so use scale = 0 against q = 0 instead, and the shift via an extra
+    # coordinate that is 1 in q and constant in k
+    q1 = np.concatenate([q, np.ones((U, N, 1))], -1)
+    k1 = np.concatenate([k, np.full((U, N, 1), 3.7)], -1)
+    v1 = np.concatenate([v, np.zeros((U, N, 1))], -1)
+    assert np.allclose(oracle.swa(q1, k1, v1, w, 0.5)[..., :dh], oracle.swa(q, k, v, w, 0.5), rtol=1e-11, atol=1e-12)
+    # large logits do not overflow
+    big = oracle.swa(q * 1e3, k * 1e3, v, w, 1.0)
+    assert np.isfinite(big).all()
+    # a decode step (one query against the last min(pos, w) cached rows, any cache order) is the prefill row
+    y = oracle.swa(q, k, v, w, 0.5)
+    for pos in (1, 3, w, w + 1, N):
+        lo = max(0, pos - w)
+        perm = g.permutation(pos - lo)
+        kc, vc = k[:, lo:pos][:, perm], v[:, lo:pos][:, perm]
+        # put the query last in a fresh sequence whose other rows are the permuted cache; window covers all
+        qs = np.zeros((U, pos - lo, dh)); qs[:, -1] = q[:, pos - 1]
+        row = oracle.swa_rows(qs, kc, vc, w, 0.5, np.array([pos - lo - 1]))[:, 0]
+        assert np.allclose(row, y[:, pos - 1], rtol=1e-12, atol=1e-13)
+
+
+def test_oracle_threads_reported():
+    assert oracle.threads() >= 1
