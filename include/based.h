@@ -1,0 +1,154 @@
+/*
+ * based.h -- C ABI of the MI355X (gfx950) hot path of the Based sequence mixer
+ * (arXiv 2402.18668): causal linear attention with the 2nd-order Taylor feature map,
+ * and small-window causal softmax attention, for prefill and for per-token decode.
+ *
+ * General contract (all entry points)
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps device memory, and keeps no global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it and never synchronise; buffers must stay alive until the work
+ *     has run.
+ *   - Return value: BASED_OK or an error code; on any error nothing has been launched.
+ *     Nothing aborts or throws.
+ *   - Tensors are contiguous, last index fastest, base pointers 16-byte aligned.
+ *     A "unit" is one (batch, head) pair; units are independent, u = b * H + h.
+ *   - dtype selects the element type of q, k, v, y (and of the window ring):
+ *     BASED_F32 or BASED_BF16.  All accumulation and the recurrent state are fp32.
+ *     Outputs are rounded to dtype with round-to-nearest-even.
+ *   - Supported sizes: d_feat in {16, 32}; d_v, d_h in {64, 128}; w in {64, 128};
+ *     any B, H, N >= 1 with B * H * N < 2^31.  Anything else: BASED_ERR_UNSUPPORTED.
+ *
+ * Notation follows the paper: d' = d_feat is the projected feature dimension of q and k,
+ * D = 1 + d' + d'^2 the expanded feature dimension (Sec. 4), d_v the value dimension.
+ * Feature order (Eq. 4): phi(x) = [1, x_0..x_{d'-1}, x_a x_b / sqrt(2) at 1 + d' + a d' + b].
+ * No temperature is applied inside the linear-attention calls: the kernel evaluated is
+ * exactly 1 + q.k + (q.k)^2 / 2; a caller who wants exp(q.k / sqrt(d')) approximated
+ * scales q and k by d'^(-1/4) beforehand.
+ */
+#ifndef BASED_H
+#define BASED_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    BASED_OK = 0,
+    BASED_ERR_INVALID_ARG = 1, /* null / misaligned pointer, non-positive size, bad pos */
+    BASED_ERR_UNSUPPORTED = 2, /* size or dtype outside the supported set               */
+    BASED_ERR_LAUNCH = 3       /* the HIP runtime refused the launch                    */
+};
+
+enum { BASED_F32 = 0, BASED_BF16 = 1 };
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char *based_strerror(int status);
+
+/* Library version, major * 100 + minor. */
+int based_version(void);
+
+/* D = 1 + d' + d'^2 (Sec. 4), or 0 if d_feat < 1. */
+int based_feature_dim(int d_feat);
+
+/*
+ * Recurrent state of linear attention (Sec. 3.1, Eq. 3): the KV-state s = sum_j phi(k_j) v_j^T
+ * and the K-state z = sum_j phi(k_j), fp32.
+ *
+ * Device layout of a state buffer: for each unit u, at float offset u * stride,
+ *   S[D][d_v] (row f = feature, in the feature order above) followed by z[D];
+ *   stride = D * d_v + D rounded up to a multiple of 64 floats (the tail is padding).
+ * based_state_bytes returns B * H * stride * 4, or 0 for unsupported sizes.
+ * based_state_stride_floats returns stride.
+ */
+size_t based_state_bytes(int B, int H, int d_feat, int d_v);
+size_t based_state_stride_floats(int d_feat, int d_v);
+
+/*
+ * Copy between a state buffer and the canonical dense arrays S [B][H][D][d_v] and
+ * z [B][H][D] (fp32, device).  Either of S, z may be NULL to skip it.
+ */
+int based_state_export(const void *state, float *S, float *z, int B, int H, int d_feat, int d_v,
+                       void *stream);
+int based_state_import(void *state, const float *S, const float *z, int B, int H, int d_feat,
+                       int d_v, void *stream);
+
+/*
+ * based_prefill -- causal Taylor linear attention over whole sequences (Eq. 2 with the feature
+ * map of Eq. 4), computed in the chunked form of Sec. 4: inside a chunk of tokens the masked
+ * quadratic product, across chunks the running state (Eq. 3).
+ *
+ *   y_i = sum_{j<=i} kappa(q_i, k_j) v_j / sum_{j<=i} kappa(q_i, k_j),
+ *   kappa(q, k) = phi(q).phi(k) = 1 + q.k + (q.k)^2 / 2,
+ * plus, with an initial state (S0, z0): numerator + phi(q_i) S0, denominator + phi(q_i).z0.
+ *
+ *   q, k   [B][H][N][d_feat]   in,  dtype
+ *   v      [B][H][N][d_v]      in,  dtype
+ *   y      [B][H][N][d_v]      out, dtype
+ *   state  state buffer (layout above) or NULL.  has_init != 0: read as (S0, z0) (must be
+ *          non-NULL).  If non-NULL it receives the state after the last token.
+ *   workspace  scratch of at least based_prefill_workspace_bytes(...) bytes, 256-byte aligned;
+ *          may be NULL when that size is 0.  Contents on return are unspecified.
+ *
+ * Calls sharing a workspace or a state buffer must be ordered on one stream.
+ */
+size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype);
+int based_prefill(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                  void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                  void *stream);
+
+/*
+ * based_decode_step -- one token of the recurrent view (Eq. 3), state update fused with
+ * readout (the operation of Alg. 2, here including the K-state and the division):
+ *   z += phi(k);  S += phi(k) v^T;  y = phi(q) S / (phi(q).z)
+ * The token is added to the state before it is read (it attends to itself).
+ *
+ *   q, k   [B][H][d_feat]  in, dtype        v  [B][H][d_v]  in, dtype
+ *   y      [B][H][d_v]     out, dtype       state  in-out (layout above)
+ */
+int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,
+                      int H, int d_feat, int d_v, int dtype, void *stream);
+
+/*
+ * Sliding-window attention (Sec. 3.2): causal softmax attention (Eq. 1) in which query i sees
+ * the w keys i-w+1 .. i (fewer at the start of the sequence), logits scale * q_i.k_j.
+ *
+ * Ring buffer (the w-sized KV cache): for each unit, K[w][d_h] then V[w][d_h] in dtype;
+ * token j (0-based position in the sequence) lives in slot j mod w.
+ * based_swa_ring_bytes returns B * H * 2 * w * d_h * sizeof(dtype), or 0 if unsupported.
+ */
+size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype);
+
+/*
+ * based_swa_prefill -- all rows of a sequence.
+ *   q, k, v [B][H][N][d_h] in;  y [B][H][N][d_h] out;  ring: NULL or ring buffer that receives
+ *   the last min(N, w) rows of k and v (other slots are left untouched).
+ */
+int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void *ring, int B,
+                      int H, int N, int d_h, int w, float scale, int dtype, void *stream);
+
+/*
+ * based_swa_decode -- one token (the operation of Alg. 3, with the cache update included):
+ * writes (k, v) into slot (pos - 1) mod w, then attends q over the last min(pos, w) tokens.
+ *   q, k, v [B][H][d_h] in;  y [B][H][d_h] out;  ring in-out;
+ *   pos = number of tokens seen including this one, >= 1 (same for every unit).
+ */
+int based_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring, int pos,
+                     int B, int H, int d_h, int w, float scale, int dtype, void *stream);
+
+/*
+ * based_decode_fused -- based_decode_step and based_swa_decode for the same token in ONE
+ * kernel launch.  The two mixers belong to different layers of the model, so their outputs
+ * stay separate (y_lin, y_swa).  Arguments as in the two calls above.
+ */
+int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                       int d_feat, int d_v, const void *swa_q, const void *swa_k,
+                       const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
+                       float scale, int B, int H, int dtype, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BASED_H */

@@ -1,0 +1,267 @@
+"""ctypes binding of the C-ABI HIP library (``include/based.h``): argument marshalling only.
+
+Every function takes torch CUDA tensors (used purely as device memory), checks their shapes and
+dtypes on the host, and forwards raw pointers plus the current HIP stream to the library.  No
+step of the method runs in Python or in torch; if the built library is missing the import
+fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libbased_hip.so")
+
+F32, BF16 = 0, 1
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH = 0, 1, 2, 3
+
+EXPORTS = [
+    "based_strerror", "based_version", "based_feature_dim", "based_state_bytes",
+    "based_state_stride_floats", "based_state_export", "based_state_import",
+    "based_prefill_workspace_bytes", "based_prefill", "based_decode_step", "based_swa_ring_bytes",
+    "based_swa_prefill", "based_swa_decode", "based_decode_fused",
+]
+
+
+class BasedError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {strerror(status)} (status {status})")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -m paper_2402_18668_amd.build` (there is no fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.based_strerror.restype = ctypes.c_char_p
+    lib.based_strerror.argtypes = [i]
+    lib.based_version.restype = i
+    lib.based_feature_dim.restype = i
+    lib.based_feature_dim.argtypes = [i]
+    lib.based_state_bytes.restype = sz
+    lib.based_state_bytes.argtypes = [i, i, i, i]
+    lib.based_state_stride_floats.restype = sz
+    lib.based_state_stride_floats.argtypes = [i, i]
+    lib.based_state_export.restype = i
+    lib.based_state_export.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.based_state_import.restype = i
+    lib.based_state_import.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.based_prefill_workspace_bytes.restype = sz
+    lib.based_prefill_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.based_prefill.restype = i
+    lib.based_prefill.argtypes = [vp, vp, vp, vp, vp, i, vp, i, i, i, i, i, i, vp]
+    lib.based_decode_step.restype = i
+    lib.based_decode_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+    lib.based_swa_ring_bytes.restype = sz
+    lib.based_swa_ring_bytes.argtypes = [i, i, i, i, i]
+    lib.based_swa_prefill.restype = i
+    lib.based_swa_prefill.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
+    lib.based_swa_decode.restype = i
+    lib.based_swa_decode.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
+    lib.based_decode_fused.restype = i
+    lib.based_decode_fused.argtypes = [vp, vp, vp, vp, vp, i, i, vp, vp, vp, vp, vp, i, i, i, f, i, i, i, vp]
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.based_strerror(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise BasedError(status, what)
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None:
+            if not t.is_cuda:
+                raise ValueError("tensors must live on the GPU")
+            if not t.is_contiguous():
+                raise ValueError("tensors must be contiguous")
+
+
+def feature_dim(d_feat: int) -> int:
+    return int(lib.based_feature_dim(int(d_feat)))
+
+
+def state_bytes(B: int, H: int, d_feat: int, d_v: int) -> int:
+    return int(lib.based_state_bytes(B, H, d_feat, d_v))
+
+
+def state_stride_floats(d_feat: int, d_v: int) -> int:
+    return int(lib.based_state_stride_floats(d_feat, d_v))
+
+
+def alloc_state(B: int, H: int, d_feat: int, d_v: int, device="cuda") -> torch.Tensor:
+    """Zero-filled state buffer (an opaque fp32 tensor of the size the library asks for)."""
+    n = state_bytes(B, H, d_feat, d_v)
+    if n == 0:
+        raise BasedError(ERR_UNSUPPORTED, "based_state_bytes")
+    return torch.zeros(n // 4, dtype=torch.float32, device=device)
+
+
+def state_export(state: torch.Tensor, B: int, H: int, d_feat: int, d_v: int):
+    """Returns canonical ``S [B, H, D, d_v]`` and ``z [B, H, D]`` (fp32 device tensors)."""
+    _dev(state)
+    D = feature_dim(d_feat)
+    S = torch.empty((B, H, D, d_v), dtype=torch.float32, device=state.device)
+    z = torch.empty((B, H, D), dtype=torch.float32, device=state.device)
+    _check(lib.based_state_export(_ptr(state), _ptr(S), _ptr(z), B, H, d_feat, d_v, _stream()),
+           "based_state_export")
+    return S, z
+
+
+def state_import(state: torch.Tensor, S: torch.Tensor, z: torch.Tensor, d_feat: int):
+    _dev(state, S, z)
+    B, H, D, d_v = S.shape
+    if S.dtype != torch.float32 or z.dtype != torch.float32 or tuple(z.shape) != (B, H, D) or D != feature_dim(d_feat):
+        raise ValueError("S must be [B,H,D,d_v] fp32 and z [B,H,D] fp32")
+    _check(lib.based_state_import(_ptr(state), _ptr(S), _ptr(z), B, H, d_feat, d_v, _stream()),
+           "based_state_import")
+
+
+def prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype_code) -> int:
+    return int(lib.based_prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype_code))
+
+
+def alloc_prefill_workspace(B, H, N, d_feat, d_v, dtype_code, device="cuda"):
+    n = prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype_code)
+    if n == 0:
+        return None
+    return torch.empty((n + 3) // 4, dtype=torch.float32, device=device)
+
+
+def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None):
+    """based_prefill.  q, k ``[B,H,N,d']``; v ``[B,H,N,d_v]``; returns y (allocated if not given)."""
+    _dev(q, k, v, y, state, workspace)
+    B, H, N, dp = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:3]) != (B, H, N) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    code = _dtype_code(q)
+    if y is None:
+        y = torch.empty_like(v)
+    elif y.shape != v.shape or y.dtype != v.dtype:
+        raise ValueError("y must match v")
+    if state is not None and (state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv)):
+        raise ValueError("state buffer too small or not fp32")
+    need = prefill_workspace_bytes(B, H, N, dp, dv, code)
+    if need and workspace is None:
+        workspace = alloc_prefill_workspace(B, H, N, dp, dv, code, q.device)
+    if need and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace too small")
+    _check(lib.based_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
+                             _ptr(workspace), B, H, N, dp, dv, code, _stream()), "based_prefill")
+    return y
+
+
+def decode_step(q, k, v, state, y=None):
+    """based_decode_step.  q, k ``[B,H,d']``; v ``[B,H,d_v]``; state updated in place."""
+    _dev(q, k, v, y, state)
+    B, H, dp = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:2]) != (B, H) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv):
+        raise ValueError("state buffer too small or not fp32")
+    if y is None:
+        y = torch.empty_like(v)
+    _check(lib.based_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), B, H, dp, dv,
+                                 _dtype_code(q), _stream()), "based_decode_step")
+    return y
+
+
+def swa_ring_bytes(B, H, w, d_h, dtype_code) -> int:
+    return int(lib.based_swa_ring_bytes(B, H, w, d_h, dtype_code))
+
+
+def alloc_swa_ring(B, H, w, d_h, dtype, device="cuda") -> torch.Tensor:
+    code = F32 if dtype == torch.float32 else BF16
+    n = swa_ring_bytes(B, H, w, d_h, code)
+    if n == 0:
+        raise BasedError(ERR_UNSUPPORTED, "based_swa_ring_bytes")
+    return torch.zeros((B, H, 2, w, d_h), dtype=dtype, device=device)
+
+
+def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
+    """based_swa_prefill.  q, k, v ``[B,H,N,d_h]``."""
+    _dev(q, k, v, y, ring)
+    B, H, N, dh = q.shape
+    if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if y is None:
+        y = torch.empty_like(v)
+    if ring is not None and (ring.dtype != q.dtype or ring.numel() != B * H * 2 * w * dh):
+        raise ValueError("ring must be [B,H,2,w,d_h] of the input dtype")
+    _check(lib.based_swa_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), B, H, N, dh, int(w),
+                                 float(scale), _dtype_code(q), _stream()), "based_swa_prefill")
+    return y
+
+
+def swa_decode(q, k, v, ring, pos: int, w: int, scale: float, y=None):
+    """based_swa_decode.  q, k, v ``[B,H,d_h]``; ring updated in place."""
+    _dev(q, k, v, y, ring)
+    B, H, dh = q.shape
+    if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if ring.dtype != q.dtype or ring.numel() != B * H * 2 * w * dh:
+        raise ValueError("ring must be [B,H,2,w,d_h] of the input dtype")
+    if y is None:
+        y = torch.empty_like(v)
+    _check(lib.based_swa_decode(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), int(pos), B, H, dh,
+                                int(w), float(scale), _dtype_code(q), _stream()), "based_swa_decode")
+    return y
+
+
+def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, scale: float,
+                 y_lin=None, y_swa=None):
+    """based_decode_fused: both decode steps in one launch; returns ``(y_lin, y_swa)``."""
+    _dev(q, k, v, state, swa_q, swa_k, swa_v, ring, y_lin, y_swa)
+    B, H, dp = q.shape
+    dv = v.shape[-1]
+    dh = swa_q.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:2]) != (B, H) or tuple(swa_q.shape[:2]) != (B, H):
+        raise ValueError("shapes disagree")
+    if swa_k.shape != swa_q.shape or swa_v.shape != swa_q.shape:
+        raise ValueError("window attention shapes disagree")
+    for t in (k, v, swa_q, swa_k, swa_v, ring):
+        if t.dtype != q.dtype:
+            raise ValueError("dtypes disagree")
+    if state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv):
+        raise ValueError("state buffer too small or not fp32")
+    if ring.numel() != B * H * 2 * w * dh:
+        raise ValueError("ring must be [B,H,2,w,d_h]")
+    if y_lin is None:
+        y_lin = torch.empty_like(v)
+    if y_swa is None:
+        y_swa = torch.empty_like(swa_v)
+    _check(lib.based_decode_fused(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), dp, dv,
+                                  _ptr(swa_q), _ptr(swa_k), _ptr(swa_v), _ptr(y_swa), _ptr(ring),
+                                  int(pos), dh, int(w), float(scale), B, H, _dtype_code(q), _stream()),
+           "based_decode_fused")
+    return y_lin, y_swa

@@ -1,0 +1,163 @@
+// C ABI of the library: argument validation and dispatch only; see include/based.h for the
+// contract of every entry point.
+#include "common.h"
+
+using namespace based;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool ok_ptr(const void *p) { return p != nullptr && aligned16(p); }
+bool ok_dtype(int dtype) { return dtype == BASED_F32 || dtype == BASED_BF16; }
+bool ok_lin_dims(int dp, int dv) { return (dp == 16 || dp == 32) && (dv == 64 || dv == 128); }
+bool ok_swa_dims(int dh, int w) { return (dh == 64 || dh == 128) && (w == 64 || w == 128); }
+bool ok_counts(int B, int H, int N)
+{
+    if (B < 1 || H < 1 || N < 1) return false;
+    const unsigned long long t = (unsigned long long)B * (unsigned long long)H * (unsigned long long)N;
+    return t < (1ull << 31);
+}
+int status_of(hipError_t e) { return e == hipSuccess ? BASED_OK : BASED_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+const char *based_strerror(int status)
+{
+    switch (status) {
+    case BASED_OK: return "ok";
+    case BASED_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, non-positive size, bad pos)";
+    case BASED_ERR_UNSUPPORTED: return "unsupported size or dtype";
+    case BASED_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int based_version(void) { return 100; }
+
+int based_feature_dim(int d_feat) { return d_feat < 1 ? 0 : feature_dim(d_feat); }
+
+size_t based_state_stride_floats(int d_feat, int d_v)
+{
+    return ok_lin_dims(d_feat, d_v) ? state_stride(d_feat, d_v) : 0;
+}
+
+size_t based_state_bytes(int B, int H, int d_feat, int d_v)
+{
+    if (!ok_lin_dims(d_feat, d_v) || !ok_counts(B, H, 1)) return 0;
+    return (size_t)B * H * state_stride(d_feat, d_v) * sizeof(float);
+}
+
+int based_state_export(const void *state, float *S, float *z, int B, int H, int d_feat, int d_v,
+                       void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(state) || (S && !aligned16(S)) || (z && !aligned16(z))) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_state_copy(const_cast<float *>(static_cast<const float *>(state)), S, z,
+                                       B * H, d_feat, d_v, 0, (hipStream_t)stream));
+}
+
+int based_state_import(void *state, const float *S, const float *z, int B, int H, int d_feat,
+                       int d_v, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(state) || (S && !aligned16(S)) || (z && !aligned16(z))) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_state_copy(static_cast<float *>(state), const_cast<float *>(S),
+                                       const_cast<float *>(z), B * H, d_feat, d_v, 1,
+                                       (hipStream_t)stream));
+}
+
+size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype)
+{
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype) || !ok_counts(B, H, N)) return 0;
+    if (!prefill_mfma_supported(d_feat, d_v, dtype)) return 0;
+    return prefill_mfma_workspace_bytes(B * H, N, d_feat, d_v);
+}
+
+int based_prefill(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                  void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
+    if (has_init && !state) return BASED_ERR_INVALID_ARG;
+    const int U = B * H;
+    if (prefill_mfma_supported(d_feat, d_v, dtype)) {
+        const size_t need = prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
+        if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
+            return BASED_ERR_INVALID_ARG;
+        return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0,
+                                             workspace, U, N, d_feat, d_v, (hipStream_t)stream));
+    }
+    return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, U, N,
+                                        d_feat, d_v, dtype, (hipStream_t)stream));
+}
+
+int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,
+                      int H, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
+        return BASED_ERR_INVALID_ARG;
+    return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
+                                        dtype, (hipStream_t)stream));
+}
+
+size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype)
+{
+    if (!ok_swa_dims(d_h, w) || !ok_dtype(dtype) || !ok_counts(B, H, 1)) return 0;
+    return (size_t)B * H * 2 * w * d_h * (dtype == BASED_F32 ? 4 : 2);
+}
+
+int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void *ring, int B, int H,
+                      int N, int d_h, int w, float scale, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_swa_dims(d_h, w) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (ring && !aligned16(ring)) return BASED_ERR_INVALID_ARG;
+    const int U = B * H;
+    hipError_t e;
+    if (swa_prefill_mfma_supported(d_h, w, dtype))
+        e = launch_swa_prefill_mfma(q, k, v, y, U, N, d_h, w, scale, (hipStream_t)stream);
+    else
+        e = launch_swa_prefill_ref(q, k, v, y, U, N, d_h, w, scale, dtype, (hipStream_t)stream);
+    if (e == hipSuccess && ring)
+        e = launch_swa_ring_fill(k, v, ring, U, N, d_h, w, dtype, (hipStream_t)stream);
+    return status_of(e);
+}
+
+int based_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring, int pos, int B,
+                     int H, int d_h, int w, float scale, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1) || pos < 1) return BASED_ERR_INVALID_ARG;
+    if (!ok_swa_dims(d_h, w) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(ring))
+        return BASED_ERR_INVALID_ARG;
+    return status_of(launch_swa_decode(q, k, v, y, ring, pos, B * H, d_h, w, scale, dtype,
+                                       (hipStream_t)stream));
+}
+
+int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                       int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
+                       void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
+                       int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1) || pos < 1) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_swa_dims(d_h, w) || !ok_dtype(dtype))
+        return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y_lin) || !ok_ptr(state) || !ok_ptr(swa_q) ||
+        !ok_ptr(swa_k) || !ok_ptr(swa_v) || !ok_ptr(y_swa) || !ok_ptr(ring))
+        return BASED_ERR_INVALID_ARG;
+    if ((unsigned long long)B * H * 2ull >= (1ull << 31)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_decode_fused(q, k, v, y_lin, static_cast<float *>(state), d_feat, d_v,
+                                         swa_q, swa_k, swa_v, y_swa, ring, pos, d_h, w, scale, B * H,
+                                         dtype, (hipStream_t)stream));
+}
+
+}  // extern "C"

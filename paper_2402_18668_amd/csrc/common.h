@@ -1,0 +1,85 @@
+// Shared device helpers for the Based HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/based.h"
+
+namespace based {
+
+constexpr float kRsqrt2 = 0.70710678118654752440f;
+
+// Element types of q/k/v/y.  bf16 is carried as raw 16-bit patterns.
+struct bf16_t {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x)
+{
+    bf16_t r;
+    r.bits = f32_to_bf16_bits(x);
+    return r;
+}
+
+__host__ __device__ constexpr int feature_dim(int dp) { return 1 + dp + dp * dp; }
+__host__ __device__ constexpr size_t state_stride(int dp, int dv)
+{
+    return ((size_t)feature_dim(dp) * dv + feature_dim(dp) + 63) / 64 * 64;
+}
+
+// Sum over the 64 lanes of a wave; every lane gets the total.
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// ---- launchers implemented in the kernel translation units ---------------------------------
+// Each returns a hipError_t from the launch (hipGetLastError), never synchronises.
+hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void *y, float *state,
+                              int has_init, int U, int N, int dp, int dv, int dtype, hipStream_t s);
+bool prefill_mfma_supported(int dp, int dv, int dtype);
+size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv);
+hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
+                               int has_init, void *workspace, int U, int N, int dp, int dv,
+                               hipStream_t s);
+hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
+                              int U, int dp, int dv, int dtype, hipStream_t s);
+hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
+                                  int dh, int w, float scale, int dtype, hipStream_t s);
+bool swa_prefill_mfma_supported(int dh, int w, int dtype);
+hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, int U, int N,
+                                   int dh, int w, float scale, hipStream_t s);
+hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, int U, int N, int dh, int w,
+                                int dtype, hipStream_t s);
+hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
+                             int pos, int U, int dh, int w, float scale, int dtype, hipStream_t s);
+hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
+                               float *state, int dp, int dv, const void *sq, const void *sk,
+                               const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
+                               float scale, int U, int dtype, hipStream_t s);
+hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, int dv, int to_state,
+                             hipStream_t s);
+
+}  // namespace based

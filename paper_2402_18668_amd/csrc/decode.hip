@@ -1,0 +1,329 @@
+// Per-token decode kernels: the recurrent Taylor linear-attention step (Eq. 3; the operation of
+// Alg. 2 plus the K-state and the division), the sliding-window attention step over the w-slot
+// ring (the operation of Alg. 3 plus the cache update), and both in one launch.
+//
+// Both steps are HBM-bandwidth bound: every state / ring element is read once (and the state
+// written once) per token, with 16-byte accesses that are contiguous across lanes.  Nothing is
+// reused within a step, so rows go HBM -> registers directly; LDS only carries the expanded
+// features, the softmax scores and the cross-wave partial sums.
+#include "common.h"
+
+namespace based {
+
+constexpr int kDecodeThreads = 256;
+
+// ---------------------------------------------------------------------------------------------
+// Linear attention: z += phi(k); S += phi(k) v^T; y = phi(q) S / (phi(q).z)      one unit / block
+// ---------------------------------------------------------------------------------------------
+template <int DP, int DV, typename T>
+__device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const T *__restrict__ k,
+                                                 const T *__restrict__ v, T *__restrict__ y,
+                                                 float *__restrict__ state, int u)
+{
+    constexpr int D = feature_dim(DP);
+    constexpr int NT = kDecodeThreads;
+    constexpr int LPR = DV / 4;      // lanes per state row (float4 each)
+    constexpr int RPS = NT / LPR;    // rows per sweep step
+    constexpr int STEPS = (D + RPS - 1) / RPS;
+    constexpr int DPAD = STEPS * RPS;
+    constexpr int UNR = 8;           // state rows in flight per lane
+
+    __shared__ float pk[DPAD], pq[DPAD];
+    __shared__ float qs[DP], ks[DP];
+    __shared__ float yred[NT / 64][DV];
+    __shared__ float dred[NT / 64];
+
+    const int tid = threadIdx.x;
+    float *Su = state + (size_t)u * state_stride(DP, DV);
+    float *zu = Su + (size_t)D * DV;
+
+    if (tid < DP) {
+        qs[tid] = to_f32(q[(size_t)u * DP + tid]);
+        ks[tid] = to_f32(k[(size_t)u * DP + tid]);
+    }
+    const int col4 = (tid % LPR) * 4, row = tid / LPR;
+    float4 v4;
+    {
+        const T *vp = v + (size_t)u * DV + col4;
+        v4 = make_float4(to_f32(vp[0]), to_f32(vp[1]), to_f32(vp[2]), to_f32(vp[3]));
+    }
+    __syncthreads();
+    // feature expansion (Eq. 4) in LDS; rows past D are zero so the tail of the sweep is inert
+    for (int f = tid; f < DPAD; f += NT) {
+        float a, b;
+        if (f == 0) { a = 1.f; b = 1.f; }
+        else if (f <= DP) { a = qs[f - 1]; b = ks[f - 1]; }
+        else if (f < D) {
+            const int i = (f - 1 - DP) / DP, j = (f - 1 - DP) % DP;
+            a = qs[i] * qs[j] * kRsqrt2; b = ks[i] * ks[j] * kRsqrt2;
+        } else { a = 0.f; b = 0.f; }
+        pq[f] = a; pk[f] = b;
+    }
+    __syncthreads();
+
+    // K-state: each feature handled by one thread
+    float dpart = 0.f;
+    for (int f = tid; f < D; f += NT) {
+        const float zn = zu[f] + pk[f];
+        zu[f] = zn;
+        dpart = fmaf(pq[f], zn, dpart);
+    }
+
+    // one read-modify-write sweep over the KV-state, readout fused in
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 *Srow = reinterpret_cast<float4 *>(Su + col4);
+#pragma unroll 1
+    for (int st0 = 0; st0 < STEPS; st0 += UNR) {
+        float4 sv[UNR];
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int f = (st0 + j) * RPS + row;
+            if (st0 + j < STEPS && f < D) sv[j] = Srow[(size_t)f * (DV / 4)];
+        }
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int f = (st0 + j) * RPS + row;
+            if (st0 + j < STEPS && f < D) {
+                const float a = pk[f], b = pq[f];
+                sv[j].x = fmaf(a, v4.x, sv[j].x); sv[j].y = fmaf(a, v4.y, sv[j].y);
+                sv[j].z = fmaf(a, v4.z, sv[j].z); sv[j].w = fmaf(a, v4.w, sv[j].w);
+                Srow[(size_t)f * (DV / 4)] = sv[j];
+                acc.x = fmaf(b, sv[j].x, acc.x); acc.y = fmaf(b, sv[j].y, acc.y);
+                acc.z = fmaf(b, sv[j].z, acc.z); acc.w = fmaf(b, sv[j].w, acc.w);
+            }
+        }
+    }
+
+    // rows are spread over the lanes above LPR within a wave, and over the waves
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+        acc.x += __shfl_xor(acc.x, o, 64); acc.y += __shfl_xor(acc.y, o, 64);
+        acc.z += __shfl_xor(acc.z, o, 64); acc.w += __shfl_xor(acc.w, o, 64);
+    }
+    dpart = wave_sum(dpart);
+    const int wv = tid >> 6, lane = tid & 63;
+    if (lane < LPR) {
+        yred[wv][col4 + 0] = acc.x; yred[wv][col4 + 1] = acc.y;
+        yred[wv][col4 + 2] = acc.z; yred[wv][col4 + 3] = acc.w;
+    }
+    if (lane == 0) dred[wv] = dpart;
+    __syncthreads();
+    if (tid < DV) {
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) { num += yred[w][tid]; den += dred[w]; }
+        y[(size_t)u * DV + tid] = from_f32<T>(num / den);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sliding-window attention, one query against the ring                           one unit / block
+// ---------------------------------------------------------------------------------------------
+template <typename T> struct Chunk;  // 16 bytes of elements
+template <> struct Chunk<float> {
+    static constexpr int CE = 4;
+    float4 raw;
+    __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
+};
+template <> struct Chunk<bf16_t> {
+    static constexpr int CE = 8;
+    uint4 raw;
+    __device__ __forceinline__ float get(int i) const
+    {
+        const uint32_t w = (&raw.x)[i >> 1];
+        return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+};
+
+template <int DH, int W, typename T>
+__device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T *__restrict__ k,
+                                                const T *__restrict__ v, T *__restrict__ y,
+                                                T *__restrict__ ring, int pos, float scale, int u)
+{
+    using Ch = Chunk<T>;
+    constexpr int NT = kDecodeThreads;
+    constexpr int CE = Ch::CE;
+    constexpr int LPR = DH / CE;    // lanes per ring row
+    constexpr int RPP = NT / LPR;   // ring rows per pass
+    constexpr int PASSES = W / RPP;
+    static_assert(W % RPP == 0 && PASSES >= 1, "window must be a multiple of the rows per pass");
+
+    __shared__ float sc[W];
+    __shared__ float part[RPP][DH];
+
+    const int tid = threadIdx.x;
+    const int chunk = tid % LPR, rg = tid / LPR;
+    const int slot = (pos - 1) % W;
+    const int valid = pos < W ? pos : W;
+
+    T *Kr = ring + (size_t)u * 2 * W * DH;
+    T *Vr = Kr + (size_t)W * DH;
+
+    Ch qc, kc[PASSES], vc[PASSES];
+    qc.raw = *reinterpret_cast<const decltype(qc.raw) *>(q + (size_t)u * DH + chunk * CE);
+    // all loads are independent of the scores: issue them up front
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int j = p * RPP + rg;
+        if (j == slot) {
+            kc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(k + (size_t)u * DH + chunk * CE);
+            vc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(v + (size_t)u * DH + chunk * CE);
+            *reinterpret_cast<decltype(qc.raw) *>(Kr + (size_t)j * DH + chunk * CE) = kc[p].raw;
+            *reinterpret_cast<decltype(qc.raw) *>(Vr + (size_t)j * DH + chunk * CE) = vc[p].raw;
+        } else if (j < valid) {
+            kc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(Kr + (size_t)j * DH + chunk * CE);
+            vc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(Vr + (size_t)j * DH + chunk * CE);
+        } else {
+            kc[p].raw = decltype(qc.raw){};
+            vc[p].raw = decltype(qc.raw){};
+        }
+    }
+    // scores
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < CE; ++i) d = fmaf(qc.get(i), kc[p].get(i), d);
+#pragma unroll
+        for (int o = 1; o < LPR; o <<= 1) d += __shfl_xor(d, o, 64);
+        if (chunk == 0) sc[p * RPP + rg] = d * scale;
+    }
+    __syncthreads();
+    // softmax statistics (every wave computes the same numbers)
+    const int lane = tid & 63;
+    float m = -INFINITY;
+    for (int j = lane; j < valid; j += 64) m = fmaxf(m, sc[j]);
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int j = lane; j < valid; j += 64) sum += __expf(sc[j] - m);
+    sum = wave_sum(sum);
+    // weighted sum of the value rows
+    float acc[CE];
+#pragma unroll
+    for (int i = 0; i < CE; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int j = p * RPP + rg;
+        const float pj = j < valid ? __expf(sc[j] - m) : 0.f;
+#pragma unroll
+        for (int i = 0; i < CE; ++i) acc[i] = fmaf(pj, vc[p].get(i), acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < CE; ++i) part[rg][chunk * CE + i] = acc[i];
+    __syncthreads();
+    if (tid < DH) {
+        float num = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r) num += part[r][tid];
+        y[(size_t)u * DH + tid] = from_f32<T>(num / sum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------------------------
+template <int DP, int DV, typename T>
+__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q, const T *k,
+                                                                     const T *v, T *y, float *state)
+{
+    decode_step_body<DP, DV, T>(q, k, v, y, state, blockIdx.x);
+}
+
+template <int DH, int W, typename T>
+__global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, const T *k,
+                                                                    const T *v, T *y, T *ring,
+                                                                    int pos, float scale)
+{
+    swa_decode_body<DH, W, T>(q, k, v, y, ring, pos, scale, blockIdx.x);
+}
+
+// Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
+// the window attention step.
+template <int DP, int DV, int DH, int W, typename T>
+__global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
+    const T *q, const T *k, const T *v, T *y_lin, float *state, const T *sq, const T *sk,
+    const T *sv, T *y_swa, T *ring, int pos, float scale, int U)
+{
+    if ((int)blockIdx.x < U)
+        decode_step_body<DP, DV, T>(q, k, v, y_lin, state, blockIdx.x);
+    else
+        swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, blockIdx.x - U);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dispatch
+// ---------------------------------------------------------------------------------------------
+#define BASED_PICK2(A, a0, a1, B, b0, b1, CALL)                  \
+    do {                                                          \
+        if (A == a0 && B == b0) { CALL(a0, b0); }                 \
+        else if (A == a0 && B == b1) { CALL(a0, b1); }            \
+        else if (A == a1 && B == b0) { CALL(a1, b0); }            \
+        else { CALL(a1, b1); }                                    \
+    } while (0)
+
+hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
+                              int U, int dp, int dv, int dtype, hipStream_t s)
+{
+#define CALL_LIN(DP_, DV_)                                                                        \
+    if (dtype == BASED_F32)                                                                       \
+        hipLaunchKernelGGL((decode_step_kernel<DP_, DV_, float>), dim3(U), dim3(kDecodeThreads),  \
+                           0, s, (const float *)q, (const float *)k, (const float *)v,            \
+                           (float *)y, state);                                                    \
+    else                                                                                          \
+        hipLaunchKernelGGL((decode_step_kernel<DP_, DV_, bf16_t>), dim3(U), dim3(kDecodeThreads), \
+                           0, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,         \
+                           (bf16_t *)y, state)
+    BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_LIN);
+#undef CALL_LIN
+    return hipGetLastError();
+}
+
+hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
+                             int pos, int U, int dh, int w, float scale, int dtype, hipStream_t s)
+{
+#define CALL_SWA(DH_, W_)                                                                         \
+    if (dtype == BASED_F32)                                                                       \
+        hipLaunchKernelGGL((swa_decode_kernel<DH_, W_, float>), dim3(U), dim3(kDecodeThreads), 0, \
+                           s, (const float *)q, (const float *)k, (const float *)v, (float *)y,   \
+                           (float *)ring, pos, scale);                                            \
+    else                                                                                          \
+        hipLaunchKernelGGL((swa_decode_kernel<DH_, W_, bf16_t>), dim3(U), dim3(kDecodeThreads),   \
+                           0, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,         \
+                           (bf16_t *)y, (bf16_t *)ring, pos, scale)
+    BASED_PICK2(dh, 64, 128, w, 64, 128, CALL_SWA);
+#undef CALL_SWA
+    return hipGetLastError();
+}
+
+template <int DP, int DV, typename T>
+static void fused_pick(const void *q, const void *k, const void *v, void *y_lin, float *state,
+                       const void *sq, const void *sk, const void *sv, void *y_swa, void *ring,
+                       int pos, int dh, int w, float scale, int U, hipStream_t s)
+{
+#define CALL_F(DH_, W_)                                                                           \
+    hipLaunchKernelGGL((decode_fused_kernel<DP, DV, DH_, W_, T>), dim3(2 * U),                    \
+                       dim3(kDecodeThreads), 0, s, (const T *)q, (const T *)k, (const T *)v,      \
+                       (T *)y_lin, state, (const T *)sq, (const T *)sk, (const T *)sv,            \
+                       (T *)y_swa, (T *)ring, pos, scale, U)
+    BASED_PICK2(dh, 64, 128, w, 64, 128, CALL_F);
+#undef CALL_F
+}
+
+hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
+                               float *state, int dp, int dv, const void *sq, const void *sk,
+                               const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
+                               float scale, int U, int dtype, hipStream_t s)
+{
+#define CALL_L(DP_, DV_)                                                                          \
+    if (dtype == BASED_F32)                                                                       \
+        fused_pick<DP_, DV_, float>(q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w,   \
+                                    scale, U, s);                                                 \
+    else                                                                                          \
+        fused_pick<DP_, DV_, bf16_t>(q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w,  \
+                                     scale, U, s)
+    BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_L);
+#undef CALL_L
+    return hipGetLastError();
+}
+
+}  // namespace based

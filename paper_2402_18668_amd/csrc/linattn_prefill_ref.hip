@@ -1,0 +1,178 @@
+// Causal Taylor linear attention, prefill, all-fp32 vector-ALU kernel.
+//
+// Computes Eq. 2 (with the feature map of Eq. 4) through the recurrent view of Eq. 3, a few
+// tokens at a time: the expanded features phi(q), phi(k) of a small token batch are built in
+// LDS (never in HBM), the KV-state lives in registers spread over the workgroup, and each
+// token's numerator and denominator are reduced across the workgroup through LDS.
+//
+// This is the exact-arithmetic path: it serves fp32 inputs (1e-4 class accuracy) and every
+// supported size; the bf16 MFMA kernel takes over where it applies.
+//
+// Work split: one workgroup per (unit, 64-column slice of d_v).  Thread (c = tid % 64,
+// r = tid / 64) owns column c of the slice and the feature rows [r * FPT, (r + 1) * FPT).
+// The K-state z is spread over all threads by feature (f = tid + NT * i).
+#include "common.h"
+
+namespace based {
+
+template <int DP, int NT> struct RefCfg {
+    static constexpr int D = feature_dim(DP);
+    static constexpr int RG = NT / 64;                          // row groups (= waves)
+    static constexpr int FPT = ((D + RG - 1) / RG + 3) / 4 * 4; // features per thread, mult of 4
+    static constexpr int DPAD = RG * FPT;
+    static constexpr int TB = DP <= 16 ? 8 : 4;                 // tokens per batch
+    static constexpr int ZPT = (DPAD + NT - 1) / NT;
+};
+
+template <int DP, int NT, typename T>
+__global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q,
+                                                         const T *__restrict__ k,
+                                                         const T *__restrict__ v,
+                                                         T *__restrict__ y, float *state,
+                                                         int has_init, int N, int dv)
+{
+    using C = RefCfg<DP, NT>;
+    constexpr int D = C::D, RG = C::RG, FPT = C::FPT, DPAD = C::DPAD, TB = C::TB, ZPT = C::ZPT;
+
+    __shared__ __align__(16) float phiq[TB][DPAD];
+    __shared__ __align__(16) float phik[TB][DPAD];
+    __shared__ float qs[TB][DP], ks[TB][DP], vs[TB][64];
+    __shared__ float red[TB][RG][64];
+    __shared__ float redd[TB][RG];
+
+    const int slices = dv / 64;
+    const int u = blockIdx.x / slices, col0 = (blockIdx.x % slices) * 64;
+    const int tid = threadIdx.x, c = tid & 63, r = tid >> 6;
+
+    const T *qu = q + (size_t)u * N * DP, *ku = k + (size_t)u * N * DP;
+    const T *vu = v + (size_t)u * N * dv + col0;
+    T *yu = y + (size_t)u * N * dv + col0;
+    float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
+    float *zu = Su ? Su + (size_t)D * dv : nullptr;
+
+    float s[FPT], zreg[ZPT];
+#pragma unroll
+    for (int i = 0; i < FPT; ++i) {
+        const int f = r * FPT + i;
+        s[i] = (has_init && f < D) ? Su[(size_t)f * dv + col0 + c] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+        const int f = tid + NT * i;
+        zreg[i] = (has_init && f < D) ? zu[f] : 0.f;
+    }
+
+    for (int tok0 = 0; tok0 < N; tok0 += TB) {
+        // (a) stage the token batch
+        for (int idx = tid; idx < TB * DP; idx += NT) {
+            const int t = idx / DP, a = idx % DP;
+            const bool ok = tok0 + t < N;
+            qs[t][a] = ok ? to_f32(qu[(size_t)(tok0 + t) * DP + a]) : 0.f;
+            ks[t][a] = ok ? to_f32(ku[(size_t)(tok0 + t) * DP + a]) : 0.f;
+        }
+        for (int idx = tid; idx < TB * 64; idx += NT) {
+            const int t = idx >> 6, cc = idx & 63;
+            vs[t][cc] = (tok0 + t < N) ? to_f32(vu[(size_t)(tok0 + t) * dv + cc]) : 0.f;
+        }
+        __syncthreads();
+        // (b) feature expansion, Eq. 4, into LDS
+        for (int idx = tid; idx < TB * DPAD; idx += NT) {
+            const int t = idx / DPAD, f = idx % DPAD;
+            const bool ok = tok0 + t < N;
+            float pq, pk;
+            if (f == 0) {
+                pq = 1.f; pk = 1.f;
+            } else if (f <= DP) {
+                pq = qs[t][f - 1]; pk = ks[t][f - 1];
+            } else if (f < D) {
+                const int a = (f - 1 - DP) / DP, b = (f - 1 - DP) % DP;
+                pq = qs[t][a] * qs[t][b] * kRsqrt2;
+                pk = ks[t][a] * ks[t][b] * kRsqrt2;
+            } else {
+                pq = 0.f; pk = 0.f;
+            }
+            phiq[t][f] = pq;
+            phik[t][f] = ok ? pk : 0.f;  // tokens past the end must not touch the state
+        }
+        __syncthreads();
+        // (c) state update fused with readout, token by token (Eq. 3)
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            const float vt = vs[t][c];
+            float num = 0.f;
+            const float4 *pk4 = reinterpret_cast<const float4 *>(&phik[t][r * FPT]);
+            const float4 *pq4 = reinterpret_cast<const float4 *>(&phiq[t][r * FPT]);
+#pragma unroll
+            for (int i = 0; i < FPT / 4; ++i) {
+                const float4 a = pk4[i], b = pq4[i];
+                s[4 * i + 0] = fmaf(a.x, vt, s[4 * i + 0]); num = fmaf(b.x, s[4 * i + 0], num);
+                s[4 * i + 1] = fmaf(a.y, vt, s[4 * i + 1]); num = fmaf(b.y, s[4 * i + 1], num);
+                s[4 * i + 2] = fmaf(a.z, vt, s[4 * i + 2]); num = fmaf(b.z, s[4 * i + 2], num);
+                s[4 * i + 3] = fmaf(a.w, vt, s[4 * i + 3]); num = fmaf(b.w, s[4 * i + 3], num);
+            }
+            red[t][r][c] = num;
+            float dpart = 0.f;
+#pragma unroll
+            for (int i = 0; i < ZPT; ++i) {
+                const int f = tid + NT * i;
+                if (f < DPAD) {
+                    zreg[i] += phik[t][f];
+                    dpart = fmaf(phiq[t][f], zreg[i], dpart);
+                }
+            }
+            dpart = wave_sum(dpart);
+            if (c == 0) redd[t][r] = dpart;
+        }
+        __syncthreads();
+        // (d) reduce over row groups, normalise, store
+        for (int idx = tid; idx < TB * 64; idx += NT) {
+            const int t = idx >> 6, cc = idx & 63;
+            if (tok0 + t < N) {
+                float num = 0.f, den = 0.f;
+#pragma unroll
+                for (int g = 0; g < RG; ++g) { num += red[t][g][cc]; den += redd[t][g]; }
+                yu[(size_t)(tok0 + t) * dv + cc] = from_f32<T>(num / den);
+            }
+        }
+        __syncthreads();
+    }
+
+    if (Su) {
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) {
+            const int f = r * FPT + i;
+            if (f < D) Su[(size_t)f * dv + col0 + c] = s[i];
+        }
+        if (col0 == 0) {
+#pragma unroll
+            for (int i = 0; i < ZPT; ++i) {
+                const int f = tid + NT * i;
+                if (f < D) zu[f] = zreg[i];
+            }
+        }
+    }
+}
+
+template <int DP, int NT, typename T>
+static hipError_t launch_ref(const void *q, const void *k, const void *v, void *y, float *state,
+                             int has_init, int U, int N, int dv, hipStream_t s)
+{
+    const dim3 grid((unsigned)(U * (dv / 64)));
+    hipLaunchKernelGGL((prefill_ref_kernel<DP, NT, T>), grid, dim3(NT), 0, s, (const T *)q,
+                       (const T *)k, (const T *)v, (T *)y, state, has_init, N, dv);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void *y, float *state,
+                              int has_init, int U, int N, int dp, int dv, int dtype, hipStream_t s)
+{
+    if (dp == 16) {
+        return dtype == BASED_F32
+                   ? launch_ref<16, 256, float>(q, k, v, y, state, has_init, U, N, dv, s)
+                   : launch_ref<16, 256, bf16_t>(q, k, v, y, state, has_init, U, N, dv, s);
+    }
+    return dtype == BASED_F32 ? launch_ref<32, 512, float>(q, k, v, y, state, has_init, U, N, dv, s)
+                              : launch_ref<32, 512, bf16_t>(q, k, v, y, state, has_init, U, N, dv, s);
+}
+
+}  // namespace based

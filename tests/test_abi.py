@@ -1,0 +1,77 @@
+"""The C-ABI library loads, exports every symbol include/based.h declares, and rejects bad
+arguments on the host before anything is launched (no GPU needed: no compute call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "based.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(based_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def based():
+    from paper_2402_18668_amd import based as b
+    return b
+
+
+def test_header_symbols_exported(based):
+    names = declared_symbols()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(based.lib, n), n
+    assert sorted(based.EXPORTS) == names
+
+
+def test_size_queries(based):
+    assert based.feature_dim(16) == 273 and based.feature_dim(32) == 1057 and based.feature_dim(0) == 0
+    stride = based.state_stride_floats(16, 64)
+    assert stride % 64 == 0 and stride >= 273 * 65
+    assert based.state_bytes(2, 3, 16, 64) == 6 * stride * 4
+    assert based.state_bytes(2, 3, 17, 64) == 0 and based.state_bytes(0, 3, 16, 64) == 0
+    assert based.swa_ring_bytes(2, 3, 64, 128, based.BF16) == 6 * 2 * 64 * 128 * 2
+    assert based.swa_ring_bytes(2, 3, 64, 128, based.F32) == 6 * 2 * 64 * 128 * 4
+    assert based.swa_ring_bytes(2, 3, 48, 128, based.BF16) == 0
+    assert based.prefill_workspace_bytes(1, 1, 100, 16, 64, based.F32) >= 0
+    assert based.lib.based_version() >= 100
+    assert based.strerror(0) == "ok" and "unknown" in based.strerror(77)
+
+
+def test_bad_arguments_are_rejected_before_launch(based):
+    lib = based.lib
+    p = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: every call below fails validation
+    odd = ctypes.c_void_p(0x1004)
+    null = ctypes.c_void_p(0)
+    st = ctypes.c_void_p(0)
+    # prefill
+    assert lib.based_prefill(null, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill(odd, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 0, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, -3, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill(p, p, p, p, null, 1, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 24, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 16, 96, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 7, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 65536, 65536, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    # decode
+    assert lib.based_decode_step(p, p, p, p, null, 1, 1, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_step(p, p, p, p, p, 1, 1, 16, 32, 1, st) == based.ERR_UNSUPPORTED
+    # window attention
+    assert lib.based_swa_prefill(p, p, null, p, null, 1, 1, 8, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_prefill(p, p, p, p, null, 1, 1, 8, 64, 32, 0.125, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_swa_decode(p, p, p, p, p, 0, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_decode(p, p, p, p, null, 1, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_decode(p, p, p, p, p, 1, 1, 1, 80, 64, 0.125, 1, st) == based.ERR_UNSUPPORTED
+    # fused
+    assert lib.based_decode_fused(p, p, p, p, p, 16, 64, p, p, p, p, p, 0, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_fused(p, p, p, p, p, 16, 64, p, p, p, p, null, 1, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_fused(p, p, p, p, p, 8, 64, p, p, p, p, p, 1, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_UNSUPPORTED
+    # state copies
+    assert lib.based_state_export(null, p, p, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
+    assert lib.based_state_import(p, p, p, 1, 1, 16, 100, st) == based.ERR_UNSUPPORTED

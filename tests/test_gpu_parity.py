@@ -1,0 +1,280 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle on the same seeded
+inputs, element by element.  Sizes span several chunks / tiles and a ragged tail."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_18668_amd import synth
+from parity import TOL, TORCH_DTYPE, check_close, down, up
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def based():
+    from paper_2402_18668_amd import based as b
+    return b
+
+
+def make_wl(name, **kw):
+    base = synth.WORKLOADS[name]
+    fields = {f: getattr(base, f) for f in base.__dataclass_fields__}
+    fields.update(kw)
+    return synth.Workload(**fields)
+
+
+def lin_case(wl, B, H, N):
+    q, k, v = synth.linattn_inputs(wl, units=B * H, N=N)
+    return q, k, v
+
+
+# ------------------------------------------------------------------------------------------------
+# linear attention prefill
+# ------------------------------------------------------------------------------------------------
+def run_prefill(based, wl, B, H, N, q, k, v, state=None, has_init=False):
+    tq = up(q, wl.dtype, (B, H, N, wl.d_feat)); tk = up(k, wl.dtype, (B, H, N, wl.d_feat))
+    tv = up(v, wl.dtype, (B, H, N, wl.d_v))
+    y = based.prefill(tq, tk, tv, state=state, has_init=has_init)
+    torch.cuda.synchronize()
+    return down(y).reshape(B * H, N, wl.d_v)
+
+
+def test_prefill_tiny_fp32(based):
+    wl = synth.WORKLOADS["tiny"]
+    q, k, v = synth.linattn_inputs(wl)
+    state = based.alloc_state(wl.B, wl.H, wl.d_feat, wl.d_v)
+    y = run_prefill(based, wl, wl.B, wl.H, wl.N, q, k, v, state=state)
+    want = oracle.linattn_quadratic(q, k, v)
+    check_close(y, want, TOL["f32"], "tiny prefill y")
+    S, z = based.state_export(state, wl.B, wl.H, wl.d_feat, wl.d_v)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(S).reshape(Sw.shape), Sw, TOL["f32"], "tiny prefill S")
+    check_close(down(z).reshape(zw.shape), zw, TOL["f32"], "tiny prefill z")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dp,dv,B,H,N", [
+    (16, 64, 2, 3, 333), (16, 128, 1, 2, 200), (32, 64, 1, 2, 150), (32, 128, 1, 1, 70),
+    (16, 64, 1, 1, 1), (16, 64, 1, 2, 63), (16, 64, 1, 2, 64), (16, 128, 1, 1, 65),
+])
+def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    q, k, v = lin_case(wl, B, H, N)
+    state = based.alloc_state(B, H, dp, dv)
+    y = run_prefill(based, wl, B, H, N, q, k, v, state=state)
+    want = oracle.linattn_quadratic(q, k, v)
+    check_close(y, want, TOL[dtype], f"prefill y {dtype} d'={dp} dv={dv} N={N}")
+    S, z = based.state_export(state, B, H, dp, dv)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(S).reshape(Sw.shape), Sw, TOL[dtype], "prefill S")
+    check_close(down(z).reshape(zw.shape), zw, TOL[dtype], "prefill z")
+
+
+@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 64), ("bf16", 16, 128), ("bf16", 32, 64)])
+def test_prefill_split_with_state(based, dtype, dp, dv):
+    """prefill(N) == prefill(N1) then prefill(N - N1 | state); state import/export round trip."""
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, N, N1 = 1, 3, 300, 130
+    q, k, v = lin_case(wl, B, H, N)
+    want = oracle.linattn_quadratic(q, k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    y1 = run_prefill(based, wl, B, H, N1, q[:, :N1], k[:, :N1], v[:, :N1], state=state)
+    # round trip through the canonical layout into a fresh buffer
+    S, z = based.state_export(state, B, H, dp, dv)
+    state2 = based.alloc_state(B, H, dp, dv)
+    based.state_import(state2, S, z, dp)
+    torch.cuda.synchronize()
+    assert torch.equal(state, state2)
+    y2 = run_prefill(based, wl, B, H, N - N1, q[:, N1:], k[:, N1:], v[:, N1:], state=state2, has_init=True)
+    check_close(y1, want[:, :N1], TOL[dtype], "split prefill part 1")
+    check_close(y2, want[:, N1:], TOL[dtype], "split prefill part 2")
+    S2, z2 = based.state_export(state2, B, H, dp, dv)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(S2).reshape(Sw.shape), Sw, TOL[dtype], "split prefill final S")
+    check_close(down(z2).reshape(zw.shape), zw, TOL[dtype], "split prefill final z")
+
+
+def test_prefill_deterministic(based):
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, N = 2, 4, 512
+    q, k, v = lin_case(wl, B, H, N)
+    a = run_prefill(based, wl, B, H, N, q, k, v)
+    b = run_prefill(based, wl, B, H, N, q, k, v)
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# linear attention decode
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 16, 64), ("bf16", 32, 64),
+                                         ("f32", 32, 128)])
+def test_decode_steps(based, dtype, dp, dv):
+    wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, N0, T = 2, 3, 40, 12
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N0)
+    dec = synth.decode_inputs(wl, T, units=U)
+    # oracle: state after the prefill, then the recurrent view token by token
+    S, z = oracle.linattn_state(k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    based.state_import(state, up(S, "f32", (B, H, S.shape[1], dv)), up(z, "f32", (B, H, z.shape[1])), dp)
+    Sd, zd = S.astype(np.float32).astype(np.float64), z.astype(np.float32).astype(np.float64)
+    for t in range(T):
+        qt, kt, vt = dec["q"][t], dec["k"][t], dec["v"][t]
+        y = based.decode_step(up(qt, dtype, (B, H, dp)), up(kt, dtype, (B, H, dp)), up(vt, dtype, (B, H, dv)), state)
+        yw, Sd, zd = oracle.linattn_recurrent(qt[:, None], kt[:, None], vt[:, None], Sd, zd)
+        check_close(down(y).reshape(U, dv), yw[:, 0], TOL[dtype], f"decode step {t}")
+    Sg, zg = based.state_export(state, B, H, dp, dv)
+    check_close(down(Sg).reshape(Sd.shape), Sd, TOL["f32"], "decode final S")
+    check_close(down(zg).reshape(zd.shape), zd, TOL["f32"], "decode final z")
+
+
+def test_prefill_then_decode_equals_longer_prefill(based):
+    """prefill(N) + one decode step == last row of the quadratic form over N + 1 tokens."""
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, N = 1, 4, 129
+    q, k, v = lin_case(wl, B, H, N + 1)
+    state = based.alloc_state(B, H, wl.d_feat, wl.d_v)
+    run_prefill(based, wl, B, H, N, q[:, :N], k[:, :N], v[:, :N], state=state)
+    y = based.decode_step(up(q[:, N], "bf16", (B, H, 16)), up(k[:, N], "bf16", (B, H, 16)),
+                          up(v[:, N], "bf16", (B, H, 64)), state)
+    want = oracle.linattn_rows(q, k, v, np.array([N]))[:, 0]
+    check_close(down(y).reshape(B * H, 64), want, TOL["bf16"], "prefill + decode")
+
+
+# ------------------------------------------------------------------------------------------------
+# sliding-window attention
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dh,w,B,H,N", [(64, 64, 2, 2, 300), (128, 64, 1, 2, 150), (64, 128, 1, 2, 333),
+                                        (128, 128, 1, 1, 260), (64, 64, 1, 1, 1), (64, 64, 1, 2, 17),
+                                        (128, 64, 1, 1, 64), (64, 64, 1, 1, 65)])
+def test_swa_prefill(based, dtype, dh, w, B, H, N):
+    wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
+    q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
+    scale = 1.0 / math.sqrt(dh)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    y = based.swa_prefill(up(q, dtype, (B, H, N, dh)), up(k, dtype, (B, H, N, dh)), up(v, dtype, (B, H, N, dh)),
+                          w, scale, ring=ring)
+    torch.cuda.synchronize()
+    want = oracle.swa(q, k, v, w, scale)
+    check_close(down(y).reshape(B * H, N, dh), want, TOL[dtype], f"swa prefill {dtype} dh={dh} w={w} N={N}")
+    # ring holds the last min(N, w) rows at slot j mod w, bit-exact copies
+    r = down(ring).reshape(B * H, 2, w, dh)
+    for j in range(max(0, N - w), N):
+        assert np.array_equal(r[:, 0, j % w], k[:, j].astype(np.float64))
+        assert np.array_equal(r[:, 1, j % w], v[:, j].astype(np.float64))
+
+
+@pytest.mark.parametrize("dtype,dh,w", [("f32", 64, 64), ("bf16", 128, 64), ("bf16", 64, 128), ("f32", 128, 128),
+                                        ("bf16", 64, 64)])
+def test_swa_decode_from_empty_and_wrapping(based, dtype, dh, w):
+    """Decode from an empty ring through the wrap-around: every step equals the prefill row."""
+    wl = make_wl("decode_1p3b", d_h=dh, w=w, dtype=dtype)
+    B, H = 1, 3
+    U = B * H
+    T = w + 9
+    dec = synth.decode_inputs(wl, T, units=U)
+    q, k, v = (np.ascontiguousarray(dec[n].transpose(1, 0, 2)) for n in ("swa_q", "swa_k", "swa_v"))
+    scale = 1.0 / math.sqrt(dh)
+    want = oracle.swa(q, k, v, w, scale)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    for t in range(T):
+        y = based.swa_decode(up(q[:, t], dtype, (B, H, dh)), up(k[:, t], dtype, (B, H, dh)),
+                             up(v[:, t], dtype, (B, H, dh)), ring, t + 1, w, scale)
+        check_close(down(y).reshape(U, dh), want[:, t], TOL[dtype], f"swa decode pos {t + 1}")
+
+
+def test_swa_prefill_then_decode(based):
+    wl = synth.WORKLOADS["decode_1p3b"]
+    dtype, dh, w = wl.dtype, wl.d_h, wl.w
+    B, H, N, T = 2, 2, 100, 5
+    U = B * H
+    q, k, v = synth.swa_inputs(wl, units=U, N=N + T)
+    scale = 1.0 / math.sqrt(dh)
+    want = oracle.swa(q, k, v, w, scale)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    based.swa_prefill(up(q[:, :N], dtype, (B, H, N, dh)), up(k[:, :N], dtype, (B, H, N, dh)),
+                      up(v[:, :N], dtype, (B, H, N, dh)), w, scale, ring=ring)
+    for t in range(N, N + T):
+        y = based.swa_decode(up(q[:, t], dtype, (B, H, dh)), up(k[:, t], dtype, (B, H, dh)),
+                             up(v[:, t], dtype, (B, H, dh)), ring, t + 1, w, scale)
+        check_close(down(y).reshape(U, dh), want[:, t], TOL[dtype], f"swa prefill+decode pos {t + 1}")
+
+
+# ------------------------------------------------------------------------------------------------
+# fused decode launch
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dp,dv,dh,w", [("bf16", 16, 128, 128, 64), ("f32", 16, 64, 64, 64),
+                                              ("bf16", 32, 64, 64, 128)])
+def test_decode_fused_equals_separate_calls(based, dtype, dp, dv, dh, w):
+    wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, d_h=dh, w=w, dtype=dtype)
+    B, H, N0, T = 2, 2, 70, 6
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N0)
+    sq, sk, sv = synth.swa_inputs(wl, units=U, N=N0)
+    dec = synth.decode_inputs(wl, T, units=U)
+    scale = 1.0 / math.sqrt(dh)
+    td = TORCH_DTYPE[dtype]
+
+    def fresh():
+        state = based.alloc_state(B, H, dp, dv)
+        run_prefill(based, wl, B, H, N0, q, k, v, state=state)
+        ring = based.alloc_swa_ring(B, H, w, dh, td)
+        based.swa_prefill(up(sq, dtype, (B, H, N0, dh)), up(sk, dtype, (B, H, N0, dh)),
+                          up(sv, dtype, (B, H, N0, dh)), w, scale, ring=ring)
+        return state, ring
+
+    state_a, ring_a = fresh()
+    state_b, ring_b = fresh()
+    # oracle for the window attention over the concatenated history
+    allq = np.concatenate([sq, dec["swa_q"].transpose(1, 0, 2)], axis=1)
+    allk = np.concatenate([sk, dec["swa_k"].transpose(1, 0, 2)], axis=1)
+    allv = np.concatenate([sv, dec["swa_v"].transpose(1, 0, 2)], axis=1)
+    want_swa = oracle.swa_rows(allq, allk, allv, w, scale, np.arange(N0, N0 + T))
+    allq_l = np.concatenate([q, dec["q"].transpose(1, 0, 2)], axis=1)
+    allk_l = np.concatenate([k, dec["k"].transpose(1, 0, 2)], axis=1)
+    allv_l = np.concatenate([v, dec["v"].transpose(1, 0, 2)], axis=1)
+    want_lin = oracle.linattn_rows(allq_l, allk_l, allv_l, np.arange(N0, N0 + T))
+    for t in range(T):
+        args = [up(dec[n][t], dtype, (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+        y1 = based.decode_step(args[0], args[1], args[2], state_a)
+        y2 = based.swa_decode(args[3], args[4], args[5], ring_a, N0 + t + 1, w, scale)
+        f1, f2 = based.decode_fused(args[0], args[1], args[2], state_b, args[3], args[4], args[5], ring_b,
+                                    N0 + t + 1, w, scale)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, f1) and torch.equal(y2, f2)
+        check_close(down(f1).reshape(U, dv), want_lin[:, t], TOL[dtype], f"fused lin step {t}")
+        check_close(down(f2).reshape(U, dh), want_swa[:, t], TOL[dtype], f"fused swa step {t}")
+    assert torch.equal(state_a, state_b) and torch.equal(ring_a, ring_b)
+
+
+# ------------------------------------------------------------------------------------------------
+# full-size workloads, in the launch configuration the benchmark times: sampled rows
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["prefill_360m", "prefill_1p3b"])
+def test_full_size_prefill_sampled_rows(based, name):
+    wl = synth.WORKLOADS[name]
+    B, H, N, U = wl.B, wl.H, wl.N, wl.units
+    q, k, v = synth.linattn_inputs(wl)
+    y = run_prefill(based, wl, B, H, N, q, k, v)
+    units = np.array([0, 1, U // 2, U - 1])
+    rows = np.array([0, 1, 63, 64, 65, 511, 1024, N - 2, N - 1])
+    want = oracle.linattn_rows(q[units], k[units], v[units], rows)
+    check_close(y[units][:, rows], want, TOL[wl.dtype], f"{name} sampled rows")
+    sq, sk, sv = synth.swa_inputs(wl)
+    scale = 1.0 / math.sqrt(wl.d_h)
+    ys = based.swa_prefill(up(sq, wl.dtype, (B, H, N, wl.d_h)), up(sk, wl.dtype, (B, H, N, wl.d_h)),
+                           up(sv, wl.dtype, (B, H, N, wl.d_h)), wl.w, scale)
+    torch.cuda.synchronize()
+    ys = down(ys).reshape(U, N, wl.d_h)
+    want = oracle.swa_rows(sq[units], sk[units], sv[units], wl.w, scale, rows)
+    check_close(ys[units][:, rows], want, TOL[wl.dtype], f"{name} swa sampled rows")
+    # property that holds at any size: outputs are convex combinations of the values seen so far
+    hi = np.maximum.accumulate(v[units].astype(np.float64), axis=1)
+    lo = np.minimum.accumulate(v[units].astype(np.float64), axis=1)
+    slack = TOL[wl.dtype] * np.abs(v).max()
+    assert (y[units] <= hi + slack).all() and (y[units] >= lo - slack).all()
