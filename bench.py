@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the Based sequence-mixer hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of the 360M-layer-shaped workload
+(batch 8, 2048 tokens, 16 heads; d' = 16, d_v = 64; window 64, head dim 64; bf16 in, fp32
+accumulate): the chunked Taylor linear-attention prefill, the sliding-window prefill, and then one
+fused decode step (state update/readout + ring attention) for the next token of every sequence.
+Inputs are seeded synthetic tensors already resident in HBM; several distinct buffer sets are
+rotated so that no step finds its inputs in the 256 MB last-level cache.
+
+Prints ONE JSON line.  ``value`` is tokens/s over the timed steps (B * (N + 1) tokens per step).
+The line also carries the roofline of the dominant kernel (the linear-attention prefill, timed
+with events on its own stream), the decode-state-update roofline on the 1.3B-shaped decode
+workload (batch 128), and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used as roofline denominators
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), or None while unmeasured.
+MEASURED_PREFILL_TRAFFIC_BYTES = None
+
+
+def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64) -> int:
+    """Credited work: readout + update against the D x d_v state, the K-state, the causal half of the
+    intra-chunk block."""
+    D = 1 + dp + dp * dp
+    return 4 * D * dv + 4 * D + (C + 1) * (dp + dv + 1)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--decode-steps", type=int, default=1024, help="steps of the batch-128 decode leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode-leg", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_18668_amd import based, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, N, dp, dv, dh, w = wl.B, wl.H, wl.N, wl.d_feat, wl.d_v, wl.d_h, wl.w
+    U = B * H
+    scale = 1.0 / math.sqrt(dh)
+    bf = torch.bfloat16
+
+    # ---- inputs: seeded host tensors, rounded to bf16, uploaded once ------------------------------
+    q, k, v = synth.linattn_inputs(wl)
+    sq, sk, sv = synth.swa_inputs(wl)
+    dec = synth.decode_inputs(wl, 1)
+
+    def up(a, shape):
+        return torch.from_numpy(np.ascontiguousarray(a)).reshape(shape).to(bf).to(dev).contiguous()
+
+    NSETS = 5   # 5 x 218 MB of q/k/v/y traffic > 1 GB: every step reads cold data
+    base = dict(q=up(q, (B, H, N, dp)), k=up(k, (B, H, N, dp)), v=up(v, (B, H, N, dv)),
+                sq=up(sq, (B, H, N, dh)), sk=up(sk, (B, H, N, dh)), sv=up(sv, (B, H, N, dh)),
+                dq=up(dec["q"][0], (B, H, dp)), dk=up(dec["k"][0], (B, H, dp)), dv=up(dec["v"][0], (B, H, dv)),
+                dsq=up(dec["swa_q"][0], (B, H, dh)), dsk=up(dec["swa_k"][0], (B, H, dh)),
+                dsv=up(dec["swa_v"][0], (B, H, dh)))
+    sets = []
+    for i in range(NSETS):
+        s = {n: (t if i == 0 else t.clone()) for n, t in base.items()}
+        s["y"] = torch.empty((B, H, N, dv), dtype=bf, device=dev)
+        s["sy"] = torch.empty((B, H, N, dh), dtype=bf, device=dev)
+        s["state"] = based.alloc_state(B, H, dp, dv, dev)
+        s["ring"] = based.alloc_swa_ring(B, H, w, dh, bf, dev)
+        s["yl"] = torch.empty((B, H, dv), dtype=bf, device=dev)
+        s["ys"] = torch.empty((B, H, dh), dtype=bf, device=dev)
+        sets.append(s)
+    workspace = based.alloc_prefill_workspace(B, H, N, dp, dv, based.BF16, dev)
+
+    ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def step(i, timed_index=None):
+        s = sets[i % NSETS]
+        if timed_index is not None:
+            ev_a[timed_index].record()
+        based.prefill(s["q"], s["k"], s["v"], y=s["y"], state=s["state"], has_init=False, workspace=workspace)
+        if timed_index is not None:
+            ev_b[timed_index].record()
+        based.swa_prefill(s["sq"], s["sk"], s["sv"], w, scale, y=s["sy"], ring=s["ring"])
+        based.decode_fused(s["dq"], s["dk"], s["dv"], s["state"], s["dsq"], s["dsk"], s["dsv"], s["ring"],
+                           N + 1, w, scale, y_lin=s["yl"], y_swa=s["ys"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_step = B * (N + 1)
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    prefill_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev_a, ev_b)]))
+    flops = lin_prefill_flops_per_token_head(dp, dv) * U * N
+    achieved = flops / (prefill_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "based_prefill (state-increment launch + main chunked launch)",
+        "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_PREFILL_TRAFFIC_BYTES,
+        "avg_ms": round(prefill_ms, 4), "flops_per_launch": flops,
+        "algorithmic_bytes_per_launch": (2 * dp + 2 * dv) * 2 * U * N,
+    }
+
+    out = {
+        "metric": "prefill tokens/s + decode tokens/s per layer; % MFMA / % HBM peak",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "prefill_360m: B8 N2048 H16 d'16 d_v64 + window-64 attention d_h64, "
+                               "then one fused decode step per sequence", "tokens_per_step": tokens_per_step,
+                   "buffer_sets": NSETS},
+        "prefill_tokens_per_s_linear_attention_only": round(B * N / (prefill_ms * 1e-3), 1),
+        "roofline": roofline,
+    }
+
+    # ---- decode leg: 1.3B-shaped, batch 128, fused state update/readout + ring attention ---------
+    if not args.no_decode_leg:
+        out["decode"] = decode_leg(torch, based, synth, dev, args.decode_steps)
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, sq, sk, sv, scale)
+
+    print(json.dumps(out))
+    return 0
+
+
+def decode_leg(torch, based, synth, dev, steps: int):
+    wl = synth.WORKLOADS["decode_1p3b"]
+    B, H, dp, dv, dh, w = wl.B, wl.H, wl.d_feat, wl.d_v, wl.d_h, wl.w
+    U = B * H
+    bf = torch.bfloat16
+    scale = 1.0 / math.sqrt(dh)
+    N0 = wl.N
+    # state and ring from a 512-token seeded prefill (generated on the host in slabs of heads)
+    q, k, v = synth.linattn_inputs(wl)
+    sq, sk, sv = synth.swa_inputs(wl)
+
+    def up(a, shape):
+        return torch.from_numpy(np.ascontiguousarray(a)).reshape(shape).to(bf).to(dev).contiguous()
+
+    state = based.alloc_state(B, H, dp, dv, dev)
+    ring = based.alloc_swa_ring(B, H, w, dh, bf, dev)
+    based.prefill(up(q, (B, H, N0, dp)), up(k, (B, H, N0, dp)), up(v, (B, H, N0, dv)), state=state)
+    based.swa_prefill(up(sq, (B, H, N0, dh)), up(sk, (B, H, N0, dh)), up(sv, (B, H, N0, dh)), w, scale, ring=ring)
+    del q, k, v, sq, sk, sv
+    # a short cycle of decode tokens, reused round-robin (values do not affect the timing)
+    CYC = 8
+    d = synth.decode_inputs(wl, CYC)
+    tq = up(d["q"], (CYC, B, H, dp)); tk = up(d["k"], (CYC, B, H, dp)); tv = up(d["v"], (CYC, B, H, dv))
+    tsq = up(d["swa_q"], (CYC, B, H, dh)); tsk = up(d["swa_k"], (CYC, B, H, dh)); tsv = up(d["swa_v"], (CYC, B, H, dh))
+    yl = torch.empty((B, H, dv), dtype=bf, device=dev)
+    ys = torch.empty((B, H, dh), dtype=bf, device=dev)
+
+    def run(n, fused, lin_only=False):
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for t in range(n):
+            c = t % CYC
+            if lin_only:
+                based.decode_step(tq[c], tk[c], tv[c], state, y=yl)
+            elif fused:
+                based.decode_fused(tq[c], tk[c], tv[c], state, tsq[c], tsk[c], tsv[c], ring, N0 + t + 1, w, scale,
+                                   y_lin=yl, y_swa=ys)
+            else:
+                based.decode_step(tq[c], tk[c], tv[c], state, y=yl)
+                based.swa_decode(tsq[c], tsk[c], tsv[c], ring, N0 + t + 1, w, scale, y=ys)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n   # ms per step
+
+    run(20, True)
+    ms_fused = run(steps, True)
+    ms_lin = run(steps, False, lin_only=True)
+    D = 1 + dp + dp * dp
+    lin_bytes = (2 * (D * dv + D) * 4 + (2 * dp + dv) * 2 + dv * 2) * U
+    swa_bytes = (2 * w * dh * 2 + 2 * dh * 2 + 3 * dh * 2 + dh * 2) * U
+    gbs_lin = lin_bytes / (ms_lin * 1e-3) / 1e9
+    return {
+        "workload": "decode_1p3b: B128 H16 d'16 d_v128 fp32 state + window-64 ring d_h128, bf16 tokens",
+        "steps": steps,
+        "fused_ms_per_step": round(ms_fused, 4),
+        "fused_tokens_per_s": round(B / (ms_fused * 1e-3), 1),
+        "fused_gbs": round((lin_bytes + swa_bytes) / (ms_fused * 1e-3) / 1e9, 1),
+        "state_update_ms_per_step": round(ms_lin, 4),
+        "state_update_tokens_per_s": round(B / (ms_lin * 1e-3), 1),
+        "roofline": {"kernel": "based_decode_step (decode_step_kernel)", "bound": "hbm", "achieved": round(gbs_lin, 1),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs_lin / PEAK_HBM_GBS, 4),
+                     "algorithmic_bytes_per_launch": lin_bytes, "traffic": None},
+    }
+
+
+def cpu_baseline(wl, q, k, v, sq, sk, sv, scale):
+    """The fp64 oracle as it stands, timed on this machine's host cores on a sample of units."""
+    import oracle
+    threads = oracle.threads()
+    U = q.shape[0]
+    units = min(U, max(2, threads // 2))
+    while True:
+        t0 = time.perf_counter()
+        oracle.linattn_quadratic(q[:units], k[:units], v[:units])
+        oracle.swa(sq[:units], sk[:units], sv[:units], wl.w, scale)
+        dt = time.perf_counter() - t0
+        if dt >= 8.0 or units >= U:
+            break
+        units = min(U, max(units + 1, int(units * min(4.0, 12.0 / max(dt, 1e-3)))))
+    tokens = units * wl.N / wl.H   # a token of a sequence spans H units
+    return {"value": round(tokens / dt, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{units} of {U} (batch, head) units of the same workload, both prefill mixers "
+                      f"(quadratic-form linear attention + windowed softmax), fp64, {dt:.1f} s; "
+                      f"scaled as units / H sequences"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

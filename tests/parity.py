@@ -19,8 +19,10 @@ def down(t: torch.Tensor) -> np.ndarray:
 
 
 def check_close(got: np.ndarray, want: np.ndarray, tol: float, what: str, unit_axes=1):
-    """Parity criterion: for every unit (leading ``unit_axes`` axes flattened)
-         |got - want| <= tol * (|want| + rms(want over the unit))   element by element, and
+    """Parity criterion.  The leading ``unit_axes`` axes index independent results ("groups"): an
+    output row y_i (Eq. 2 and Eq. 1 define every row on its own, and its scale shrinks like
+    1/sqrt(i)), or one unit's state tensor.  For every group
+         |got - want| <= tol * (|want| + rms(want over the group))   element by element, and
          max|got - want| / max|want| <= tol.
     Returns (max elementwise excess ratio, max normwise error) for reporting."""
     got = np.asarray(got, dtype=np.float64)
