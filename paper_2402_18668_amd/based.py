@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libbased_hip.so")
+# BASED_HIP_LIB lets a developer point the binding at another build of the same library
+LIB_PATH = os.environ.get("BASED_HIP_LIB") or os.path.join(_HERE, "lib", "libbased_hip.so")
 
 F32, BF16 = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH = 0, 1, 2, 3

@@ -41,6 +41,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int DP = 16;            // d'
 constexpr int C = 64;             // chunk length (tokens)
@@ -96,15 +97,87 @@ __device__ __forceinline__ bf16x8 pack8_acc(const f32x16 &acc, int s)   // regis
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast(bf16x8, w); }
 
+// Workgroup barrier that orders LDS traffic only: this wave's LDS operations have completed
+// (lgkmcnt) before it arrives, and the compiler moves no memory access across it.  Global loads
+// and stores stay in flight (the waves exchange data through LDS only), which is what lets the
+// next chunk's rows stream in underneath the current chunk's arithmetic.
 __device__ __forceinline__ void wg_sync()
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Workspace entry layout: [wave][slot][r / 4][lane][r % 4] floats, so that one 16-byte access per
+// lane is contiguous across the wave.
+__device__ __forceinline__ size_t ws_off(int w, int slot, int j, int lane)
+{
+    return ((((size_t)w * SLOTS + slot) * 4 + j) * 64 + lane) * 4;
+}
+
+// Loads one workspace entry (this wave's 10 accumulator tiles = 40 x 16 bytes per lane) with all
+// loads in flight at once and the wait inside the same statement, so that every output register is
+// valid as far as the compiler can tell.  Left to itself the compiler, short of registers in this
+// kernel, issues these loads one memory latency apiece.
+__device__ __forceinline__ void load_entry(const float *wave_base, int lane, f32x4 (&t)[SLOTS * 4])
+{
+    const float *p0 = wave_base + ws_off(0, 0, 0, lane);
+    const float *p1 = wave_base + ws_off(0, 1, 0, lane);
+    const float *p2 = wave_base + ws_off(0, 2, 0, lane);
+    const float *p3 = wave_base + ws_off(0, 3, 0, lane);
+    const float *p4 = wave_base + ws_off(0, 4, 0, lane);
+    const float *p5 = wave_base + ws_off(0, 5, 0, lane);
+    const float *p6 = wave_base + ws_off(0, 6, 0, lane);
+    const float *p7 = wave_base + ws_off(0, 7, 0, lane);
+    const float *p8 = wave_base + ws_off(0, 8, 0, lane);
+    const float *p9 = wave_base + ws_off(0, 9, 0, lane);
+    asm volatile(
+        "global_load_dwordx4 %0, %40, off offset:0\n\t"
+        "global_load_dwordx4 %1, %40, off offset:1024\n\t"
+        "global_load_dwordx4 %2, %40, off offset:2048\n\t"
+        "global_load_dwordx4 %3, %40, off offset:3072\n\t"
+        "global_load_dwordx4 %4, %41, off offset:0\n\t"
+        "global_load_dwordx4 %5, %41, off offset:1024\n\t"
+        "global_load_dwordx4 %6, %41, off offset:2048\n\t"
+        "global_load_dwordx4 %7, %41, off offset:3072\n\t"
+        "global_load_dwordx4 %8, %42, off offset:0\n\t"
+        "global_load_dwordx4 %9, %42, off offset:1024\n\t"
+        "global_load_dwordx4 %10, %42, off offset:2048\n\t"
+        "global_load_dwordx4 %11, %42, off offset:3072\n\t"
+        "global_load_dwordx4 %12, %43, off offset:0\n\t"
+        "global_load_dwordx4 %13, %43, off offset:1024\n\t"
+        "global_load_dwordx4 %14, %43, off offset:2048\n\t"
+        "global_load_dwordx4 %15, %43, off offset:3072\n\t"
+        "global_load_dwordx4 %16, %44, off offset:0\n\t"
+        "global_load_dwordx4 %17, %44, off offset:1024\n\t"
+        "global_load_dwordx4 %18, %44, off offset:2048\n\t"
+        "global_load_dwordx4 %19, %44, off offset:3072\n\t"
+        "global_load_dwordx4 %20, %45, off offset:0\n\t"
+        "global_load_dwordx4 %21, %45, off offset:1024\n\t"
+        "global_load_dwordx4 %22, %45, off offset:2048\n\t"
+        "global_load_dwordx4 %23, %45, off offset:3072\n\t"
+        "global_load_dwordx4 %24, %46, off offset:0\n\t"
+        "global_load_dwordx4 %25, %46, off offset:1024\n\t"
+        "global_load_dwordx4 %26, %46, off offset:2048\n\t"
+        "global_load_dwordx4 %27, %46, off offset:3072\n\t"
+        "global_load_dwordx4 %28, %47, off offset:0\n\t"
+        "global_load_dwordx4 %29, %47, off offset:1024\n\t"
+        "global_load_dwordx4 %30, %47, off offset:2048\n\t"
+        "global_load_dwordx4 %31, %47, off offset:3072\n\t"
+        "global_load_dwordx4 %32, %48, off offset:0\n\t"
+        "global_load_dwordx4 %33, %48, off offset:1024\n\t"
+        "global_load_dwordx4 %34, %48, off offset:2048\n\t"
+        "global_load_dwordx4 %35, %48, off offset:3072\n\t"
+        "global_load_dwordx4 %36, %49, off offset:0\n\t"
+        "global_load_dwordx4 %37, %49, off offset:1024\n\t"
+        "global_load_dwordx4 %38, %49, off offset:2048\n\t"
+        "global_load_dwordx4 %39, %49, off offset:3072\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]), "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23]), "=&v"(t[24]), "=&v"(t[25]), "=&v"(t[26]), "=&v"(t[27]), "=&v"(t[28]), "=&v"(t[29]), "=&v"(t[30]), "=&v"(t[31]), "=&v"(t[32]), "=&v"(t[33]), "=&v"(t[34]), "=&v"(t[35]), "=&v"(t[36]), "=&v"(t[37]), "=&v"(t[38]), "=&v"(t[39])
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5), "v"(p6), "v"(p7), "v"(p8), "v"(p9)
+        : "memory");
+}
 
 // canonical state row of local feature row fl of main tile t / of the extra (1st/0th order) tile
 __device__ __forceinline__ int canon_row_main(int t, int fl) { return 1 + DP + 32 * t + fl; }
@@ -166,17 +239,18 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
     if (MODE == 0) {
         // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
         for (int p = has_init ? 0 : 1; p <= seg; ++p) {
-            const float *e = ws_unit + (size_t)p * kWsEntryFloats + (size_t)w * SLOTS * 16 * 64 + lane;
+            f32x4 t[SLOTS * 4];
+            load_entry(ws_unit + (size_t)p * kWsEntryFloats + ws_off(w, 0, 0, 0), lane, t);
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) S[tt][c2][r] += e[((tt * 2 + c2) * 16 + r) * 64];
+                    for (int r = 0; r < 16; ++r) S[tt][c2][r] += t[(tt * 2 + c2) * 4 + (r >> 2)][r & 3];
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) X[c2][r] += e[((8 + c2) * 16 + r) * 64];
+                for (int r = 0; r < 16; ++r) X[c2][r] += t[(8 + c2) * 4 + (r >> 2)][r & 3];
         }
     }
     if (MODE == 2) {
@@ -257,37 +331,29 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
     u32x4 const_op = {0u, 0u, 0u, 0u};
     if (g == 0) const_op[0] = 0x3F80u;
 
-    if (MODE != 2) load_raw(tok_begin);
-    int buf = 0;
-    for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C, buf ^= 1) {
-        Stage &st = lds.st[buf];
-        stage(st, tok0);
-
-        // operands that come straight from global memory (this chunk)
-        u32x4 kop[2], qop[2], qbop[2];
-        if (MODE == 0) {
-            const u32x4 zero = {0u, 0u, 0u, 0u};
+    // operands that come straight from global memory: q (two 8-byte pieces per lane) for the
+    // 1st-order rows and the moments; K and Q tiles of the intra-chunk block (wave 1)
+    u32x4 kop[2], qop[2], qbop[2];
+    auto load_ops = [&](int tok0) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                const int tok = tok0 + 32 * t2 + n;
-                const bool ok = tok < tok_end;
-                qbop[t2] = zero;
-                if (ok) {
-                    const u32x2 a = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 4 * g);
-                    const u32x2 b = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 8 + 4 * g);
-                    qbop[t2][0] = a[0]; qbop[t2][1] = a[1]; qbop[t2][2] = b[0]; qbop[t2][3] = b[1];
-                }
-                if (w == 1) {
-                    kop[t2] = ok ? *reinterpret_cast<const u32x4 *>(ku + (size_t)tok * DP + 8 * g) : zero;
-                    qop[t2] = ok ? *reinterpret_cast<const u32x4 *>(qu + (size_t)tok * DP + 8 * g) : zero;
-                }
+        for (int t2 = 0; t2 < 2; ++t2) {
+            const int tok = tok0 + 32 * t2 + n;
+            const bool ok = tok < tok_end;
+            qbop[t2] = zero;
+            if (ok) {
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 4 * g);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 8 + 4 * g);
+                qbop[t2][0] = a[0]; qbop[t2][1] = a[1]; qbop[t2][2] = b[0]; qbop[t2][3] = b[1];
+            }
+            if (w == 1) {
+                kop[t2] = ok ? *reinterpret_cast<const u32x4 *>(ku + (size_t)tok * DP + 8 * g) : zero;
+                qop[t2] = ok ? *reinterpret_cast<const u32x4 *>(qu + (size_t)tok * DP + 8 * g) : zero;
             }
         }
-        if (tok0 + C < tok_end) load_raw(tok0 + C);   // next chunk's rows fly during this chunk
-        wg_sync();
-
-        // V^T operands of this chunk: [kt][s][c2]; lane (g, n): column 32 c2 + n, tokens of the slab
-        bf16x8 vop[2][2][2];
+    };
+    // V^T operands of a chunk: [kt][s][c2]; lane (g, n): column 32 c2 + n, tokens of the slab
+    auto load_vop = [&](const Stage &st, bf16x8 (&vop)[2][2][2]) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -300,6 +366,19 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
                     vop[kt][s][c2] = as_bf16x8(o);
                 }
+    };
+
+    // Pipeline: chunk c+1 is fetched from global memory and staged into the other LDS buffer
+    // during the update phase of chunk c, so its latency hides under the update MFMAs.
+    if (MODE != 2) {
+        load_raw(tok_begin);
+        stage(lds.st[0], tok_begin);
+        if (MODE == 0) load_ops(tok_begin);
+    }
+    int buf = 0;
+    for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C, buf ^= 1) {
+        Stage &st = lds.st[buf];
+        wg_sync();   // this chunk's staging is visible; the other buffer is free
 
         if (MODE == 0) {
             // =============================== readout ============================================
@@ -387,6 +466,8 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                 }
 
                 // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
+                bf16x8 vop[2][2][2];
+                load_vop(st, vop);
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
@@ -446,10 +527,12 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 #pragma unroll
                         for (int i = 0; i < 4; ++i) r4[i] = (Ym[c2][4 * j + i] + o[i]) * inv;
                         if (tok < tok_end) {
-                            u32x2 pk;
-                            pk[0] = (uint32_t)f32_to_bf16_bits(r4[0]) | ((uint32_t)f32_to_bf16_bits(r4[1]) << 16);
-                            pk[1] = (uint32_t)f32_to_bf16_bits(r4[2]) | ((uint32_t)f32_to_bf16_bits(r4[3]) << 16);
-                            *reinterpret_cast<u32x2 *>(yu + (size_t)tok * dv + 32 * c2 + 8 * j + 4 * g) = pk;
+                            f32x4 rv;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) rv[i] = r4[i];
+                            const bf16x4 hv = __builtin_convertvector(rv, bf16x4);
+                            *reinterpret_cast<u32x2 *>(yu + (size_t)tok * dv + 32 * c2 + 8 * j + 4 * g) =
+                                __builtin_bit_cast(u32x2, hv);
                         }
                     }
             };
@@ -461,6 +544,10 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
         // =================================== update =============================================
         // S += phi(K)^T V over this wave's feature rows; lane (g, n): feature row n of the tile
         {
+            const bool more = tok0 + C < tok_end;
+            if (more) load_raw(tok0 + C);
+            bf16x8 vop[2][2][2];
+            load_vop(st, vop);
             const int brow = n & 15, ahalf = n >> 4;
             float kb[2][2][8];
 #pragma unroll
@@ -511,22 +598,36 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                         X[0] = mfma(kk, kk, X[0]);
                     }
                 }
+            if (more) {
+                stage(lds.st[buf ^ 1], tok0 + C);
+                if (MODE == 0) load_ops(tok0 + C);
+            }
         }
     }
 
     // ---- end of segment -----------------------------------------------------------------------
     if (MODE != 0) {
-        float *e = ws_unit + (size_t)(MODE == 1 ? 1 + seg : 0) * kWsEntryFloats + (size_t)w * SLOTS * 16 * 64 + lane;
+        float *e = ws_unit + (size_t)(MODE == 1 ? 1 + seg : 0) * kWsEntryFloats;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) e[((tt * 2 + c2) * 16 + r) * 64] = S[tt][c2][r];
+                for (int j = 0; j < 4; ++j) {
+                    f32x4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = S[tt][c2][4 * j + i];
+                    *reinterpret_cast<f32x4 *>(e + ws_off(w, tt * 2 + c2, j, lane)) = o;
+                }
 #pragma unroll
         for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) e[((8 + c2) * 16 + r) * 64] = X[c2][r];
+            for (int j = 0; j < 4; ++j) {
+                f32x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = X[c2][4 * j + i];
+                *reinterpret_cast<f32x4 *>(e + ws_off(w, 8 + c2, j, lane)) = o;
+            }
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
