@@ -57,8 +57,9 @@ constexpr int KTB_LD = C + 4;     // bf16 [K^T; ones; 0] rows (8-byte aligned re
 constexpr int VT_LD = C + 4;      // bf16 V^T rows
 constexpr int QS_LD = DP + 4;     // fp32 Q rows
 
-// accumulator slots per wave: 4 main tiles x 2 column tiles, then 2 extra
-constexpr int SLOTS = 10;
+// accumulator slots per wave: 4 main tiles x 2 column tiles, then the 1st/0th-order tile (2 column
+// tiles) and the moment tile (both only used by wave 0)
+constexpr int SLOTS = 11;
 constexpr size_t kWsEntryFloats = (size_t)NW * SLOTS * 16 * 64;
 
 struct Stage {
@@ -71,7 +72,8 @@ struct Stage {
 struct Lds {
     Stage st[2];
     float xbuf[NW][8][64][4];     // partial Y^T exchange: [writer][c2 * 4 + r / 4][lane][r % 4]
-    float inv_den[C];
+    float den_inter[C];           // count + phi(q).z over earlier chunks (wave 0)
+    float den_intra[C];           // row sums of the masked intra-chunk block (wave 1)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -116,12 +118,13 @@ __device__ __forceinline__ size_t ws_off(int w, int slot, int j, int lane)
     return ((((size_t)w * SLOTS + slot) * 4 + j) * 64 + lane) * 4;
 }
 
-// Loads one workspace entry (this wave's 10 accumulator tiles = 40 x 16 bytes per lane) with all
+// Loads one workspace entry (this wave's 11 accumulator tiles = 44 x 16 bytes per lane) with all
 // loads in flight at once and the wait inside the same statement, so that every output register is
 // valid as far as the compiler can tell.  Left to itself the compiler, short of registers in this
 // kernel, issues these loads one memory latency apiece.
 __device__ __forceinline__ void load_entry(const float *wave_base, int lane, f32x4 (&t)[SLOTS * 4])
 {
+    static_assert(SLOTS == 11, "the load sequence below is written out for 11 slots");
     const float *p0 = wave_base + ws_off(0, 0, 0, lane);
     const float *p1 = wave_base + ws_off(0, 1, 0, lane);
     const float *p2 = wave_base + ws_off(0, 2, 0, lane);
@@ -132,50 +135,55 @@ __device__ __forceinline__ void load_entry(const float *wave_base, int lane, f32
     const float *p7 = wave_base + ws_off(0, 7, 0, lane);
     const float *p8 = wave_base + ws_off(0, 8, 0, lane);
     const float *p9 = wave_base + ws_off(0, 9, 0, lane);
+    const float *p10 = wave_base + ws_off(0, 10, 0, lane);
     asm volatile(
-        "global_load_dwordx4 %0, %40, off offset:0\n\t"
-        "global_load_dwordx4 %1, %40, off offset:1024\n\t"
-        "global_load_dwordx4 %2, %40, off offset:2048\n\t"
-        "global_load_dwordx4 %3, %40, off offset:3072\n\t"
-        "global_load_dwordx4 %4, %41, off offset:0\n\t"
-        "global_load_dwordx4 %5, %41, off offset:1024\n\t"
-        "global_load_dwordx4 %6, %41, off offset:2048\n\t"
-        "global_load_dwordx4 %7, %41, off offset:3072\n\t"
-        "global_load_dwordx4 %8, %42, off offset:0\n\t"
-        "global_load_dwordx4 %9, %42, off offset:1024\n\t"
-        "global_load_dwordx4 %10, %42, off offset:2048\n\t"
-        "global_load_dwordx4 %11, %42, off offset:3072\n\t"
-        "global_load_dwordx4 %12, %43, off offset:0\n\t"
-        "global_load_dwordx4 %13, %43, off offset:1024\n\t"
-        "global_load_dwordx4 %14, %43, off offset:2048\n\t"
-        "global_load_dwordx4 %15, %43, off offset:3072\n\t"
-        "global_load_dwordx4 %16, %44, off offset:0\n\t"
-        "global_load_dwordx4 %17, %44, off offset:1024\n\t"
-        "global_load_dwordx4 %18, %44, off offset:2048\n\t"
-        "global_load_dwordx4 %19, %44, off offset:3072\n\t"
-        "global_load_dwordx4 %20, %45, off offset:0\n\t"
-        "global_load_dwordx4 %21, %45, off offset:1024\n\t"
-        "global_load_dwordx4 %22, %45, off offset:2048\n\t"
-        "global_load_dwordx4 %23, %45, off offset:3072\n\t"
-        "global_load_dwordx4 %24, %46, off offset:0\n\t"
-        "global_load_dwordx4 %25, %46, off offset:1024\n\t"
-        "global_load_dwordx4 %26, %46, off offset:2048\n\t"
-        "global_load_dwordx4 %27, %46, off offset:3072\n\t"
-        "global_load_dwordx4 %28, %47, off offset:0\n\t"
-        "global_load_dwordx4 %29, %47, off offset:1024\n\t"
-        "global_load_dwordx4 %30, %47, off offset:2048\n\t"
-        "global_load_dwordx4 %31, %47, off offset:3072\n\t"
-        "global_load_dwordx4 %32, %48, off offset:0\n\t"
-        "global_load_dwordx4 %33, %48, off offset:1024\n\t"
-        "global_load_dwordx4 %34, %48, off offset:2048\n\t"
-        "global_load_dwordx4 %35, %48, off offset:3072\n\t"
-        "global_load_dwordx4 %36, %49, off offset:0\n\t"
-        "global_load_dwordx4 %37, %49, off offset:1024\n\t"
-        "global_load_dwordx4 %38, %49, off offset:2048\n\t"
-        "global_load_dwordx4 %39, %49, off offset:3072\n\t"
+        "global_load_dwordx4 %0, %44, off offset:0\n\t"
+        "global_load_dwordx4 %1, %44, off offset:1024\n\t"
+        "global_load_dwordx4 %2, %44, off offset:2048\n\t"
+        "global_load_dwordx4 %3, %44, off offset:3072\n\t"
+        "global_load_dwordx4 %4, %45, off offset:0\n\t"
+        "global_load_dwordx4 %5, %45, off offset:1024\n\t"
+        "global_load_dwordx4 %6, %45, off offset:2048\n\t"
+        "global_load_dwordx4 %7, %45, off offset:3072\n\t"
+        "global_load_dwordx4 %8, %46, off offset:0\n\t"
+        "global_load_dwordx4 %9, %46, off offset:1024\n\t"
+        "global_load_dwordx4 %10, %46, off offset:2048\n\t"
+        "global_load_dwordx4 %11, %46, off offset:3072\n\t"
+        "global_load_dwordx4 %12, %47, off offset:0\n\t"
+        "global_load_dwordx4 %13, %47, off offset:1024\n\t"
+        "global_load_dwordx4 %14, %47, off offset:2048\n\t"
+        "global_load_dwordx4 %15, %47, off offset:3072\n\t"
+        "global_load_dwordx4 %16, %48, off offset:0\n\t"
+        "global_load_dwordx4 %17, %48, off offset:1024\n\t"
+        "global_load_dwordx4 %18, %48, off offset:2048\n\t"
+        "global_load_dwordx4 %19, %48, off offset:3072\n\t"
+        "global_load_dwordx4 %20, %49, off offset:0\n\t"
+        "global_load_dwordx4 %21, %49, off offset:1024\n\t"
+        "global_load_dwordx4 %22, %49, off offset:2048\n\t"
+        "global_load_dwordx4 %23, %49, off offset:3072\n\t"
+        "global_load_dwordx4 %24, %50, off offset:0\n\t"
+        "global_load_dwordx4 %25, %50, off offset:1024\n\t"
+        "global_load_dwordx4 %26, %50, off offset:2048\n\t"
+        "global_load_dwordx4 %27, %50, off offset:3072\n\t"
+        "global_load_dwordx4 %28, %51, off offset:0\n\t"
+        "global_load_dwordx4 %29, %51, off offset:1024\n\t"
+        "global_load_dwordx4 %30, %51, off offset:2048\n\t"
+        "global_load_dwordx4 %31, %51, off offset:3072\n\t"
+        "global_load_dwordx4 %32, %52, off offset:0\n\t"
+        "global_load_dwordx4 %33, %52, off offset:1024\n\t"
+        "global_load_dwordx4 %34, %52, off offset:2048\n\t"
+        "global_load_dwordx4 %35, %52, off offset:3072\n\t"
+        "global_load_dwordx4 %36, %53, off offset:0\n\t"
+        "global_load_dwordx4 %37, %53, off offset:1024\n\t"
+        "global_load_dwordx4 %38, %53, off offset:2048\n\t"
+        "global_load_dwordx4 %39, %53, off offset:3072\n\t"
+        "global_load_dwordx4 %40, %54, off offset:0\n\t"
+        "global_load_dwordx4 %41, %54, off offset:1024\n\t"
+        "global_load_dwordx4 %42, %54, off offset:2048\n\t"
+        "global_load_dwordx4 %43, %54, off offset:3072\n\t"
         "s_waitcnt vmcnt(0)"
-        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]), "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23]), "=&v"(t[24]), "=&v"(t[25]), "=&v"(t[26]), "=&v"(t[27]), "=&v"(t[28]), "=&v"(t[29]), "=&v"(t[30]), "=&v"(t[31]), "=&v"(t[32]), "=&v"(t[33]), "=&v"(t[34]), "=&v"(t[35]), "=&v"(t[36]), "=&v"(t[37]), "=&v"(t[38]), "=&v"(t[39])
-        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5), "v"(p6), "v"(p7), "v"(p8), "v"(p9)
+        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]), "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23]), "=&v"(t[24]), "=&v"(t[25]), "=&v"(t[26]), "=&v"(t[27]), "=&v"(t[28]), "=&v"(t[29]), "=&v"(t[30]), "=&v"(t[31]), "=&v"(t[32]), "=&v"(t[33]), "=&v"(t[34]), "=&v"(t[35]), "=&v"(t[36]), "=&v"(t[37]), "=&v"(t[38]), "=&v"(t[39]), "=&v"(t[40]), "=&v"(t[41]), "=&v"(t[42]), "=&v"(t[43])
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5), "v"(p6), "v"(p7), "v"(p8), "v"(p9), "v"(p10)
         : "memory");
 }
 
@@ -224,7 +232,8 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[4][2];        // main tiles [tt][c2]
-    f32x16 X[2];           // wave 0: 1st/0th-order tile [c2]; wave 1: X[0] = moment tile M'
+    f32x16 X[2];           // wave 0: 1st/0th-order tile [c2]
+    f32x16 M;              // wave 0: moment tile M' = [k, 1]^T [k, 1]
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
@@ -235,6 +244,8 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
     for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) X[c2][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) M[r] = 0.f;
 
     if (MODE == 0) {
         // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
@@ -251,6 +262,8 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) X[c2][r] += t[(8 + c2) * 4 + (r >> 2)][r & 3];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) M[r] += t[10 * 4 + (r >> 2)][r & 3];
         }
     }
     if (MODE == 2) {
@@ -268,13 +281,12 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) X[c2][r] = Su[(size_t)row * dv + col0 + 32 * c2 + n];
                 }
-            } else {
                 float m = 0.f;   // M'[fl][n]
                 if (fl < DP && n < DP) m = zu[1 + DP + fl * DP + n] * 1.41421356237309504880f;
                 else if (fl == DP && n < DP) m = zu[1 + n];
                 else if (fl < DP && n == DP) m = zu[1 + fl];
                 else if (fl == DP && n == DP) m = zu[0];
-                X[0][r] = m;
+                M[r] = m;
             }
         }
     }
@@ -437,21 +449,19 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                         Y[qt][c2] = mfma(s1, as_bf16x8(const_op), Y[qt][c2]);
                     }
                 }
-            } else {
-                // ---- denominator from the moments: count + q.z1 + q^T M q / 2 -------------------
+                // ---- inter-chunk denominator from the moments: count + q.z1 + q^T M q / 2 --------
                 float mres[8];
-                const bf16x8 mhi = pack8_acc(X[0], 0);
+                const bf16x8 mhi = pack8_acc(M, 0);
                 {
                     const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        mres[2 * i] = X[0][2 * i] - bf16lo(hb[i]);
-                        mres[2 * i + 1] = X[0][2 * i + 1] - bf16hi(hb[i]);
+                        mres[2 * i] = M[2 * i] - bf16lo(hb[i]);
+                        mres[2 * i + 1] = M[2 * i + 1] - bf16hi(hb[i]);
                     }
                 }
                 const bf16x8 mlo = pack8(mres);
-                const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[0][8]), 16));
-                float den[2];
+                const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(M[8]), 16));
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt) {
                     f32x16 T;
@@ -462,12 +472,15 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     float d2 = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) d2 = fmaf(T[e], qb[qt][e], d2);
-                    den[qt] = fmaf(d2, kHalfInvC4, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
+                    const float d = fmaf(d2, kHalfInvC4, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
+                    const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
+                    if (g == 0) lds.den_inter[32 * qt + n] = tot;
                 }
-
+            } else {
                 // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
                 bf16x8 vop[2][2][2];
                 load_vop(st, vop);
+                float den[2] = {0.f, 0.f};
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
@@ -498,8 +511,8 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     }
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt) {
-                    const float tot = den[qt] + __shfl_xor(den[qt], 32, 64) + cnt_prev;
-                    if (g == 0) lds.inv_den[32 * qt + n] = 1.f / tot;
+                    const float tot = den[qt] + __shfl_xor(den[qt], 32, 64);
+                    if (g == 0) lds.den_intra[32 * qt + n] = tot;
                 }
             }
 
@@ -517,7 +530,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
             };
             auto finish = [&](const f32x16 (&Ym)[2]) {
                 const int tok = tok0 + 32 * w + n;
-                const float inv = lds.inv_den[32 * w + n];
+                const float inv = 1.f / (lds.den_inter[32 * w + n] + lds.den_intra[32 * w + n]);
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
@@ -560,21 +573,34 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { kb[kt][s][i] = a[i]; kb[kt][s][4 + i] = b[i]; }
                 }
-#pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
+            // rows a of c K^T for one tile: [kt * 2 + s][jj], fetched one tile ahead of its use so the
+            // LDS latency hides under the previous tile's MFMAs
+            f32x4 ka[2][4][2];
+            auto load_ka = [&](int tt, f32x4 (&dst)[4][2]) {
                 const int arow = 8 * w + 2 * tt + ahalf;
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int s = 0; s < 2; ++s) {
                         const float *p = &st.kts[arow][32 * kt + 16 * s + 4 * g];
-                        const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
-                        const f32x4 b = *reinterpret_cast<const f32x4 *>(p + 8);
+                        dst[kt * 2 + s][0] = *reinterpret_cast<const f32x4 *>(p);
+                        dst[kt * 2 + s][1] = *reinterpret_cast<const f32x4 *>(p + 8);
+                    }
+            };
+            load_ka(0, ka[0]);
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                if (tt + 1 < 4) load_ka(tt + 1, ka[(tt + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
                         float pr[8];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            pr[i] = a[i] * kb[kt][s][i];
-                            pr[4 + i] = b[i] * kb[kt][s][4 + i];
+                            pr[i] = ka[tt & 1][kt * 2 + s][0][i] * kb[kt][s][i];
+                            pr[4 + i] = ka[tt & 1][kt * 2 + s][1][i] * kb[kt][s][4 + i];
                         }
                         const bf16x8 phik = pack8(pr);
 #pragma unroll
@@ -582,6 +608,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     }
             }
             // [k_0..k_15, 1, 0..]^T operand: the 1st/0th-order feature rows and the moment operand
+            if (w == 0)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -591,12 +618,9 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
                     u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
                     const bf16x8 kk = as_bf16x8(o);
-                    if (w == 0) {
 #pragma unroll
-                        for (int c2 = 0; c2 < 2; ++c2) X[c2] = mfma(kk, vop[kt][s][c2], X[c2]);
-                    } else {
-                        X[0] = mfma(kk, kk, X[0]);
-                    }
+                    for (int c2 = 0; c2 < 2; ++c2) X[c2] = mfma(kk, vop[kt][s][c2], X[c2]);
+                    M = mfma(kk, kk, M);
                 }
             if (more) {
                 stage(lds.st[buf ^ 1], tok0 + C);
@@ -628,6 +652,13 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                 for (int i = 0; i < 4; ++i) o[i] = X[c2][4 * j + i];
                 *reinterpret_cast<f32x4 *>(e + ws_off(w, 8 + c2, j, lane)) = o;
             }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = M[4 * j + i];
+            *reinterpret_cast<f32x4 *>(e + ws_off(w, 10, j, lane)) = o;
+        }
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -643,11 +674,12 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) Su[(size_t)row * dv + col0 + 32 * c2 + n] = X[c2][r];
                 }
-            } else if (slice == 0) {
-                const float m = X[0][r];
-                if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
-                else if (fl == DP && n < DP) zu[1 + n] = m;
-                else if (fl == DP && n == DP) zu[0] = m;
+                if (slice == 0) {
+                    const float m = M[r];
+                    if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
+                    else if (fl == DP && n < DP) zu[1 + n] = m;
+                    else if (fl == DP && n == DP) zu[0] = m;
+                }
             }
         }
     }
