@@ -108,6 +108,12 @@ __device__ __forceinline__ void wg_sync()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// MFMA instructions ignore the EXEC mask.  A branch on the wave's role is uniform across the wave
+// but the compiler lowers it to lane masking and may drop the jump over a short masked block, in
+// which case the other waves would execute the MFMAs inside it.  An inline-asm statement in the
+// block makes the compiler keep the jump (it never runs inline asm with an empty EXEC mask).
+__device__ __forceinline__ void role_guard() { asm volatile("; wave-role block: keep the execz branch" ::: "memory"); }
+
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -439,6 +445,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                 }
 
             if (w == 0) {
+                role_guard();
                 // 1st-order rows (slab 0: operand is q itself) and the constant row (slab 1)
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2) {
@@ -477,6 +484,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     if (g == 0) lds.den_inter[32 * qt + n] = tot;
                 }
             } else {
+                role_guard();
                 // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
                 bf16x8 vop[2][2][2];
                 load_vop(st, vop);
@@ -613,6 +621,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
+                    role_guard();
                     const uint16_t *p = &st.ktb[n][32 * kt + 16 * s + 4 * g];
                     const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
                     const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
