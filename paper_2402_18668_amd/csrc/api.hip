@@ -123,12 +123,14 @@ int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void
     if (ring && !aligned16(ring)) return BASED_ERR_INVALID_ARG;
     const int U = B * H;
     hipError_t e;
-    if (swa_prefill_mfma_supported(d_h, w, dtype))
-        e = launch_swa_prefill_mfma(q, k, v, y, U, N, d_h, w, scale, (hipStream_t)stream);
-    else
+    if (swa_prefill_mfma_supported(d_h, w, dtype)) {
+        // this kernel also fills the ring
+        e = launch_swa_prefill_mfma(q, k, v, y, ring, U, N, d_h, w, scale, (hipStream_t)stream);
+    } else {
         e = launch_swa_prefill_ref(q, k, v, y, U, N, d_h, w, scale, dtype, (hipStream_t)stream);
-    if (e == hipSuccess && ring)
-        e = launch_swa_ring_fill(k, v, ring, U, N, d_h, w, dtype, (hipStream_t)stream);
+        if (e == hipSuccess && ring)
+            e = launch_swa_ring_fill(k, v, ring, U, N, d_h, w, dtype, (hipStream_t)stream);
+    }
     return status_of(e);
 }
 

@@ -66,8 +66,8 @@ hipError_t launch_decode_step(const void *q, const void *k, const void *v, void 
 hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
                                   int dh, int w, float scale, int dtype, hipStream_t s);
 bool swa_prefill_mfma_supported(int dh, int w, int dtype);
-hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                   int dh, int w, float scale, hipStream_t s);
+hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
+                                   int N, int dh, int w, float scale, hipStream_t s);
 hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, int U, int N, int dh, int w,
                                 int dtype, hipStream_t s);
 hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,

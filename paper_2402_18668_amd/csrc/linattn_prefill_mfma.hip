@@ -596,24 +596,30 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
                     }
             };
             load_ka(0, ka[0]);
+            // Software pipeline over the 16 (tile, slab) steps: the feature products of step i + 1 are
+            // computed (into a second operand register set) while the MFMAs of step i run.  With a
+            // single operand register set the vector ALU would have to wait for each MFMA to finish
+            // reading it before overwriting it, and the two pipes would take turns instead of overlapping.
+            auto gen = [&](int step) {
+                const int tt = step >> 2, ks = step & 3;   // ks = kt * 2 + s
+                float pr[8];
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                if (tt + 1 < 4) load_ka(tt + 1, ka[(tt + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 4; ++i) {
+                    pr[i] = ka[tt & 1][ks][0][i] * kb[ks >> 1][ks & 1][i];
+                    pr[4 + i] = ka[tt & 1][ks][1][i] * kb[ks >> 1][ks & 1][4 + i];
+                }
+                return pack8(pr);
+            };
+            bf16x8 phik[2];
+            phik[0] = gen(0);
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
+            for (int step = 0; step < 16; ++step) {
+                const int tt = step >> 2, ks = step & 3;
+                if (ks == 0 && tt + 1 < 4) load_ka(tt + 1, ka[(tt + 1) & 1]);
+                if (step + 1 < 16) phik[(step + 1) & 1] = gen(step + 1);
 #pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        float pr[8];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            pr[i] = ka[tt & 1][kt * 2 + s][0][i] * kb[kt][s][i];
-                            pr[4 + i] = ka[tt & 1][kt * 2 + s][1][i] * kb[kt][s][4 + i];
-                        }
-                        const bf16x8 phik = pack8(pr);
-#pragma unroll
-                        for (int c2 = 0; c2 < 2; ++c2) S[tt][c2] = mfma(phik, vop[kt][s][c2], S[tt][c2]);
-                    }
+                for (int c2 = 0; c2 < 2; ++c2)
+                    S[tt][c2] = mfma(phik[step & 1], vop[ks >> 1][ks & 1][c2], S[tt][c2]);
             }
             // [k_0..k_15, 1, 0..]^T operand: the 1st/0th-order feature rows and the moment operand
             if (w == 0)

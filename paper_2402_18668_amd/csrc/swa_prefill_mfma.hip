@@ -46,7 +46,8 @@ template <int DH, int W>
 __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__restrict__ q,
                                                               const uint16_t *__restrict__ k,
                                                               const uint16_t *__restrict__ v,
-                                                              uint16_t *__restrict__ y, int N,
+                                                              uint16_t *__restrict__ y,
+                                                              uint16_t *__restrict__ ring, int N,
                                                               float scale_log2e)
 {
     using Cfg = SwaCfg<DH, W>;
@@ -81,6 +82,13 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             vv = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
         }
         *reinterpret_cast<u32x4 *>(Ks + (size_t)r * K_LD + c * 8) = kv;
+        // the w-slot ring receives the last min(N, w) rows (slot = position mod w); each row is
+        // written by the block that owns it as a query row (staged rows W .. W + BQ - 1)
+        if (ring && r >= W && key < N && key >= N - W) {
+            uint16_t *rk = ring + (size_t)u * 2 * W * DH + (size_t)(key % W) * DH + c * 8;
+            *reinterpret_cast<u32x4 *>(rk) = kv;
+            *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = vv;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             Vt[(size_t)(c * 8 + 2 * i) * VT_LD + r] = (uint16_t)(vv[i] & 0xffffu);
@@ -187,8 +195,8 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
 }
 
 template <int DH, int W>
-static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                  float scale, hipStream_t s)
+static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
+                                  int N, float scale, hipStream_t s)
 {
     using Cfg = SwaCfg<DH, W>;
     auto kern = swa_prefill_mfma_kernel<DH, W>;
@@ -197,7 +205,7 @@ static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, v
     if (e != hipSuccess) return e;
     const size_t nblk = (size_t)(N + BQ - 1) / BQ;
     hipLaunchKernelGGL(kern, dim3((unsigned)(nblk * U)), dim3(NT), Cfg::lds_bytes, s, (const uint16_t *)q,
-                       (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y, N,
+                       (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y, (uint16_t *)ring, N,
                        scale * 1.44269504088896340736f);
     return hipGetLastError();
 }
@@ -207,13 +215,13 @@ bool swa_prefill_mfma_supported(int dh, int w, int dtype)
     return dtype == BASED_BF16 && (dh == 64 || dh == 128) && (w == 64 || w == 128);
 }
 
-hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                   int dh, int w, float scale, hipStream_t s)
+hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
+                                   int N, int dh, int w, float scale, hipStream_t s)
 {
-    if (dh == 64 && w == 64) return launch_swa_mfma<64, 64>(q, k, v, y, U, N, scale, s);
-    if (dh == 64 && w == 128) return launch_swa_mfma<64, 128>(q, k, v, y, U, N, scale, s);
-    if (dh == 128 && w == 64) return launch_swa_mfma<128, 64>(q, k, v, y, U, N, scale, s);
-    if (dh == 128 && w == 128) return launch_swa_mfma<128, 128>(q, k, v, y, U, N, scale, s);
+    if (dh == 64 && w == 64) return launch_swa_mfma<64, 64>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 64 && w == 128) return launch_swa_mfma<64, 128>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 128 && w == 64) return launch_swa_mfma<128, 64>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 128 && w == 128) return launch_swa_mfma<128, 128>(q, k, v, y, ring, U, N, scale, s);
     return hipErrorInvalidValue;
 }
 
