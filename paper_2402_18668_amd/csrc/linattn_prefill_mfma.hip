@@ -6,13 +6,16 @@
 // KV-state S (Eq. 3) read out with phi(Q) and updated with phi(K)^T V.  The expanded features
 // are produced in registers straight into MFMA operand layout and never stored anywhere.
 //
-// Work split.  One workgroup of two waves per (unit, 64-column slice of d_v, sequence segment).
+// Work split.  One workgroup of four waves per (unit, 64-column slice of d_v, sequence segment).
 // The 2nd-order feature rows (a, b) -> x_a x_b / sqrt(2) are cut into 8 tiles of 32 rows
-// (tile t holds a in {2t, 2t+1}, all b); wave w owns tiles 4w .. 4w+3, whose 32x32 fp32 state
-// tiles stay in its accumulator registers for the whole segment.  Wave 0 also owns the tile of
-// the 1st/0th-order rows [x_0..x_15, 1]; wave 1 also does the intra-chunk block and the
-// denominator.  Per chunk each wave produces a partial Y^T over its feature rows; the two
-// partials are exchanged through LDS (each wave finishes 32 of the 64 tokens).
+// (tile t holds a in {2t, 2t+1}, all b); wave w owns tiles 2w and 2w+1, whose 32x32 fp32 state
+// tiles stay in its registers for the whole segment.  The remaining work is spread over the
+// waves: wave 0 owns the tile of the 1st/0th-order rows [x_0..x_15, 1]; wave 1 the moments that
+// give the denominator; waves 2 and 3 the intra-chunk block.  Per chunk each wave produces a
+// partial Y^T over its feature rows; the partials are exchanged through LDS and wave w finishes
+// the 32x32 output tile (query tile w / 2, column tile w % 2).  Each wave needs fewer than 256
+// registers, so two workgroups (eight waves) share a CU and one wave's vector-ALU work (feature
+// products, conversions) overlaps the other's MFMAs.
 //
 // MFMA 32x32x16 register layouts used throughout (lane = 32 g + n):
 //   A operand: row n, k-slots 8g .. 8g+7;  B operand: column n, k-slots 8g .. 8g+7;
@@ -39,13 +42,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int DP = 16;            // d'
 constexpr int C = 64;             // chunk length (tokens)
-constexpr int NW = 2;             // waves per workgroup
+constexpr int NW = 4;             // waves per workgroup
 constexpr int NT = NW * 64;
 constexpr int DVS = 64;           // d_v columns per workgroup
 constexpr float kC4 = 0.84089641525371454303f;   // 2^(-1/4): (x_a c)(x_b c) = x_a x_b / sqrt(2)
@@ -56,24 +59,29 @@ constexpr int KTS_LD = C + 4;     // fp32 K^T rows
 constexpr int KTB_LD = C + 4;     // bf16 [K^T; ones; 0] rows (8-byte aligned reads)
 constexpr int VT_LD = C + 4;      // bf16 V^T rows
 constexpr int QS_LD = DP + 4;     // fp32 Q rows
+constexpr int RB_LD = DP + 8;     // bf16 row-major Q / K rows (48-byte stride)
 
-// accumulator slots per wave: 4 main tiles x 2 column tiles, then the 1st/0th-order tile (2 column
-// tiles) and the moment tile (both only used by wave 0)
-constexpr int SLOTS = 11;
-constexpr size_t kWsEntryFloats = (size_t)NW * SLOTS * 16 * 64;
+// Workspace entry (one segment's state in accumulator layout): 19 slots of 16 registers x 64
+// lanes: slot 4w + 2tt + c2 = main tile tt of wave w, column tile c2; slots 16, 17 = 1st/0th-order
+// tile (column tiles 0, 1); slot 18 = moment tile.  Within a slot: [r / 4][lane][r % 4], so that
+// one 16-byte access per lane is contiguous across the wave.
+constexpr int WS_SLOTS = 19;
+constexpr size_t kWsEntryFloats = (size_t)WS_SLOTS * 16 * 64;
 
 struct Stage {
     float kts[DP][KTS_LD];        // c * K^T
     uint16_t ktb[32][KTB_LD];     // rows 0..15 K^T (bf16), row 16 token-valid ones, rest zero
     uint16_t vt[DVS][VT_LD];      // V^T (bf16)
     float qs[C][QS_LD];           // c * Q
+    uint16_t qrow[C][RB_LD];      // Q rows, bf16 as given
+    uint16_t krow[C][RB_LD];      // K rows, bf16 as given
 };
 
 struct Lds {
-    Stage st[2];
-    float xbuf[NW][8][64][4];     // partial Y^T exchange: [writer][c2 * 4 + r / 4][lane][r % 4]
-    float den_inter[C];           // count + phi(q).z over earlier chunks (wave 0)
-    float den_intra[C];           // row sums of the masked intra-chunk block (wave 1)
+    Stage st;
+    float xbuf[NW][3][4][64][4];  // partial Y^T tiles: [destination wave][sender slot][r / 4][lane][r % 4]
+    float den_inter[C];           // count + phi(q).z over earlier chunks (wave 1)
+    float den_intra[2][C];        // row sums of the masked intra-chunk block (waves 2 and 3)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -99,6 +107,12 @@ __device__ __forceinline__ bf16x8 pack8_acc(const f32x16 &acc, int s)   // regis
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast(bf16x8, w); }
 
+__device__ __forceinline__ void zero16(f32x16 &a)
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[r] = 0.f;
+}
+
 // Workgroup barrier that orders LDS traffic only: this wave's LDS operations have completed
 // (lgkmcnt) before it arrives, and the compiler moves no memory access across it.  Global loads
 // and stores stay in flight (the waves exchange data through LDS only), which is what lets the
@@ -114,86 +128,62 @@ __device__ __forceinline__ void wg_sync()
 // block makes the compiler keep the jump (it never runs inline asm with an empty EXEC mask).
 __device__ __forceinline__ void role_guard() { asm volatile("; wave-role block: keep the execz branch" ::: "memory"); }
 
+// Makes the compiler forget what it knows about an accumulator tile (no instruction is emitted).
+// Used between the two query-tile passes of the readout so that the bf16 copies of the state are
+// re-made per pass instead of being kept live across both (32 registers).
+__device__ __forceinline__ void forget(f32x16 &a) { asm volatile("" : "+v"(a)); }
+
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// Workspace entry layout: [wave][slot][r / 4][lane][r % 4] floats, so that one 16-byte access per
-// lane is contiguous across the wave.
-__device__ __forceinline__ size_t ws_off(int w, int slot, int j, int lane)
+__device__ __forceinline__ size_t ws_slot_off(int slot, int j, int lane)
 {
-    return ((((size_t)w * SLOTS + slot) * 4 + j) * 64 + lane) * 4;
+    return (((size_t)slot * 4 + j) * 64 + lane) * 4;
 }
 
-// Loads one workspace entry (this wave's 11 accumulator tiles = 44 x 16 bytes per lane) with all
-// loads in flight at once and the wait inside the same statement, so that every output register is
-// valid as far as the compiler can tell.  Left to itself the compiler, short of registers in this
-// kernel, issues these loads one memory latency apiece.
-__device__ __forceinline__ void load_entry(const float *wave_base, int lane, f32x4 (&t)[SLOTS * 4])
+// Loads six workspace slots (24 x 16 bytes per lane) with all loads in flight at once and the
+// wait inside the same statement, so that every output register is valid as far as the compiler
+// can tell.  (Separate load statements whose results the compiler believes complete would let
+// it reuse those registers before the data has arrived.)
+__device__ __forceinline__ void load_slots(const float *p0, const float *p1, const float *p2,
+                                           const float *p3, const float *p4, const float *p5,
+                                           f32x4 (&t)[24])
 {
-    static_assert(SLOTS == 11, "the load sequence below is written out for 11 slots");
-    const float *p0 = wave_base + ws_off(0, 0, 0, lane);
-    const float *p1 = wave_base + ws_off(0, 1, 0, lane);
-    const float *p2 = wave_base + ws_off(0, 2, 0, lane);
-    const float *p3 = wave_base + ws_off(0, 3, 0, lane);
-    const float *p4 = wave_base + ws_off(0, 4, 0, lane);
-    const float *p5 = wave_base + ws_off(0, 5, 0, lane);
-    const float *p6 = wave_base + ws_off(0, 6, 0, lane);
-    const float *p7 = wave_base + ws_off(0, 7, 0, lane);
-    const float *p8 = wave_base + ws_off(0, 8, 0, lane);
-    const float *p9 = wave_base + ws_off(0, 9, 0, lane);
-    const float *p10 = wave_base + ws_off(0, 10, 0, lane);
     asm volatile(
-        "global_load_dwordx4 %0, %44, off offset:0\n\t"
-        "global_load_dwordx4 %1, %44, off offset:1024\n\t"
-        "global_load_dwordx4 %2, %44, off offset:2048\n\t"
-        "global_load_dwordx4 %3, %44, off offset:3072\n\t"
-        "global_load_dwordx4 %4, %45, off offset:0\n\t"
-        "global_load_dwordx4 %5, %45, off offset:1024\n\t"
-        "global_load_dwordx4 %6, %45, off offset:2048\n\t"
-        "global_load_dwordx4 %7, %45, off offset:3072\n\t"
-        "global_load_dwordx4 %8, %46, off offset:0\n\t"
-        "global_load_dwordx4 %9, %46, off offset:1024\n\t"
-        "global_load_dwordx4 %10, %46, off offset:2048\n\t"
-        "global_load_dwordx4 %11, %46, off offset:3072\n\t"
-        "global_load_dwordx4 %12, %47, off offset:0\n\t"
-        "global_load_dwordx4 %13, %47, off offset:1024\n\t"
-        "global_load_dwordx4 %14, %47, off offset:2048\n\t"
-        "global_load_dwordx4 %15, %47, off offset:3072\n\t"
-        "global_load_dwordx4 %16, %48, off offset:0\n\t"
-        "global_load_dwordx4 %17, %48, off offset:1024\n\t"
-        "global_load_dwordx4 %18, %48, off offset:2048\n\t"
-        "global_load_dwordx4 %19, %48, off offset:3072\n\t"
-        "global_load_dwordx4 %20, %49, off offset:0\n\t"
-        "global_load_dwordx4 %21, %49, off offset:1024\n\t"
-        "global_load_dwordx4 %22, %49, off offset:2048\n\t"
-        "global_load_dwordx4 %23, %49, off offset:3072\n\t"
-        "global_load_dwordx4 %24, %50, off offset:0\n\t"
-        "global_load_dwordx4 %25, %50, off offset:1024\n\t"
-        "global_load_dwordx4 %26, %50, off offset:2048\n\t"
-        "global_load_dwordx4 %27, %50, off offset:3072\n\t"
-        "global_load_dwordx4 %28, %51, off offset:0\n\t"
-        "global_load_dwordx4 %29, %51, off offset:1024\n\t"
-        "global_load_dwordx4 %30, %51, off offset:2048\n\t"
-        "global_load_dwordx4 %31, %51, off offset:3072\n\t"
-        "global_load_dwordx4 %32, %52, off offset:0\n\t"
-        "global_load_dwordx4 %33, %52, off offset:1024\n\t"
-        "global_load_dwordx4 %34, %52, off offset:2048\n\t"
-        "global_load_dwordx4 %35, %52, off offset:3072\n\t"
-        "global_load_dwordx4 %36, %53, off offset:0\n\t"
-        "global_load_dwordx4 %37, %53, off offset:1024\n\t"
-        "global_load_dwordx4 %38, %53, off offset:2048\n\t"
-        "global_load_dwordx4 %39, %53, off offset:3072\n\t"
-        "global_load_dwordx4 %40, %54, off offset:0\n\t"
-        "global_load_dwordx4 %41, %54, off offset:1024\n\t"
-        "global_load_dwordx4 %42, %54, off offset:2048\n\t"
-        "global_load_dwordx4 %43, %54, off offset:3072\n\t"
+        "global_load_dwordx4 %0, %24, off offset:0\n\t"
+        "global_load_dwordx4 %1, %24, off offset:1024\n\t"
+        "global_load_dwordx4 %2, %24, off offset:2048\n\t"
+        "global_load_dwordx4 %3, %24, off offset:3072\n\t"
+        "global_load_dwordx4 %4, %25, off offset:0\n\t"
+        "global_load_dwordx4 %5, %25, off offset:1024\n\t"
+        "global_load_dwordx4 %6, %25, off offset:2048\n\t"
+        "global_load_dwordx4 %7, %25, off offset:3072\n\t"
+        "global_load_dwordx4 %8, %26, off offset:0\n\t"
+        "global_load_dwordx4 %9, %26, off offset:1024\n\t"
+        "global_load_dwordx4 %10, %26, off offset:2048\n\t"
+        "global_load_dwordx4 %11, %26, off offset:3072\n\t"
+        "global_load_dwordx4 %12, %27, off offset:0\n\t"
+        "global_load_dwordx4 %13, %27, off offset:1024\n\t"
+        "global_load_dwordx4 %14, %27, off offset:2048\n\t"
+        "global_load_dwordx4 %15, %27, off offset:3072\n\t"
+        "global_load_dwordx4 %16, %28, off offset:0\n\t"
+        "global_load_dwordx4 %17, %28, off offset:1024\n\t"
+        "global_load_dwordx4 %18, %28, off offset:2048\n\t"
+        "global_load_dwordx4 %19, %28, off offset:3072\n\t"
+        "global_load_dwordx4 %20, %29, off offset:0\n\t"
+        "global_load_dwordx4 %21, %29, off offset:1024\n\t"
+        "global_load_dwordx4 %22, %29, off offset:2048\n\t"
+        "global_load_dwordx4 %23, %29, off offset:3072\n\t"
         "s_waitcnt vmcnt(0)"
-        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]), "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23]), "=&v"(t[24]), "=&v"(t[25]), "=&v"(t[26]), "=&v"(t[27]), "=&v"(t[28]), "=&v"(t[29]), "=&v"(t[30]), "=&v"(t[31]), "=&v"(t[32]), "=&v"(t[33]), "=&v"(t[34]), "=&v"(t[35]), "=&v"(t[36]), "=&v"(t[37]), "=&v"(t[38]), "=&v"(t[39]), "=&v"(t[40]), "=&v"(t[41]), "=&v"(t[42]), "=&v"(t[43])
-        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5), "v"(p6), "v"(p7), "v"(p8), "v"(p9), "v"(p10)
+        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]),
+          "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]),
+          "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]),
+          "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23])
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5)
         : "memory");
 }
 
-// canonical state row of local feature row fl of main tile t / of the extra (1st/0th order) tile
+// canonical state row of local feature row fl of main tile t / of the 1st/0th-order tile
 __device__ __forceinline__ int canon_row_main(int t, int fl) { return 1 + DP + 32 * t + fl; }
 __device__ __forceinline__ int canon_row_extra(int fl) { return fl < DP ? 1 + fl : (fl == DP ? 0 : -1); }
 
@@ -205,7 +195,7 @@ __device__ __forceinline__ int canon_row_extra(int fl) { return fl < DP ? 1 + fl
 // The main launch never reads the caller's state buffer, so writing the final state back into it
 // cannot race with another workgroup still starting up.
 template <int MODE>
-__global__ __launch_bounds__(NT) void prefill_mfma_kernel(
+__global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws, int N,
     int dv, int seg_len, int G)
@@ -213,7 +203,7 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
     __shared__ __align__(16) Lds lds;
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6;              // wave: owns main tiles 4w .. 4w+3
+    const int w = tid >> 6;   // wave index: owns main tiles 2w, 2w+1
     const int lane = tid & 63;
     const int g = lane >> 5, n = lane & 31;
 
@@ -237,39 +227,41 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
     float *ws_unit = ws ? ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats : nullptr;
 
     // ---- accumulators -------------------------------------------------------------------------
-    f32x16 S[4][2];        // main tiles [tt][c2]
-    f32x16 X[2];           // wave 0: 1st/0th-order tile [c2]
-    f32x16 M;              // wave 0: moment tile M' = [k, 1]^T [k, 1]
+    f32x16 S[2][2];        // main tiles [tt][c2]
+    f32x16 X[2];           // wave 0: 1st/0th-order tile [c2]; wave 1: X[0] = moment tile
+                           // M' = [k, 1]^T [k, 1]; unused by waves 2, 3
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
+    for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) S[tt][c2][r] = 0.f;
-#pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) X[c2][r] = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) M[r] = 0.f;
+        for (int c2 = 0; c2 < 2; ++c2) zero16(S[tt][c2]);
+    zero16(X[0]); zero16(X[1]);
 
     if (MODE == 0) {
         // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
         for (int p = has_init ? 0 : 1; p <= seg; ++p) {
-            f32x4 t[SLOTS * 4];
-            load_entry(ws_unit + (size_t)p * kWsEntryFloats + ws_off(w, 0, 0, 0), lane, t);
+            const float *e = ws_unit + (size_t)p * kWsEntryFloats;
+            // slots 4w .. 4w+3, and for waves 0 / 1 their extra tiles (other waves re-read a main slot)
+            const int x0 = w == 0 ? 16 : (w == 1 ? 18 : 4 * w);
+            const int x1 = w == 0 ? 17 : 4 * w;
+            f32x4 t[24];
+            load_slots(e + ws_slot_off(4 * w + 0, 0, lane), e + ws_slot_off(4 * w + 1, 0, lane),
+                       e + ws_slot_off(4 * w + 2, 0, lane), e + ws_slot_off(4 * w + 3, 0, lane),
+                       e + ws_slot_off(x0, 0, lane), e + ws_slot_off(x1, 0, lane), t);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) S[tt][c2][r] += t[(tt * 2 + c2) * 4 + (r >> 2)][r & 3];
+            if (w == 0) {
 #pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2)
+                for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) X[c2][r] += t[(8 + c2) * 4 + (r >> 2)][r & 3];
+                    for (int r = 0; r < 16; ++r) X[c2][r] += t[(4 + c2) * 4 + (r >> 2)][r & 3];
+            } else if (w == 1) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) M[r] += t[10 * 4 + (r >> 2)][r & 3];
+                for (int r = 0; r < 16; ++r) X[0][r] += t[4 * 4 + (r >> 2)][r & 3];
+            }
         }
     }
     if (MODE == 2) {
@@ -277,424 +269,356 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
-                    S[tt][c2][r] = Su[(size_t)canon_row_main(4 * w + tt, fl) * dv + col0 + 32 * c2 + n];
+                    S[tt][c2][r] = Su[(size_t)canon_row_main(2 * w + tt, fl) * dv + col0 + 32 * c2 + n];
             if (w == 0) {
                 const int row = canon_row_extra(fl);
                 if (row >= 0) {
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) X[c2][r] = Su[(size_t)row * dv + col0 + 32 * c2 + n];
                 }
+            } else if (w == 1) {
                 float m = 0.f;   // M'[fl][n]
                 if (fl < DP && n < DP) m = zu[1 + DP + fl * DP + n] * 1.41421356237309504880f;
                 else if (fl == DP && n < DP) m = zu[1 + n];
                 else if (fl < DP && n == DP) m = zu[1 + fl];
                 else if (fl == DP && n == DP) m = zu[0];
-                M[r] = m;
+                X[0][r] = m;
             }
         }
     }
 
-    // zero rows 17..31 of both K'^T staging buffers once
-    for (int i = tid; i < 2 * 15 * KTB_LD; i += NT) {
-        const int b = i / (15 * KTB_LD), rem = i % (15 * KTB_LD);
-        lds.st[b].ktb[17 + rem / KTB_LD][rem % KTB_LD] = 0;
-    }
+    // zero rows 17..31 of the K'^T staging rows and the unused half of den_intra[1] once
+    for (int i = tid; i < 15 * KTB_LD; i += NT) lds.st.ktb[17 + i / KTB_LD][i % KTB_LD] = 0;
+    if (tid < C) lds.den_intra[1][tid] = 0.f;
 
     // ---- staging: global -> registers -> LDS ----------------------------------------------------
-    const int s_tok = tid & 63, s_half = tid >> 6;
-    u32x4 raw_k, raw_q, raw_v[4];
+    const int s_tok = tid & 63, s_q = tid >> 6;   // this thread stages a quarter of token s_tok's row
+    u32x2 raw_k, raw_q;
+    u32x4 raw_v[2];
+    // per-lane element offsets inside a chunk (32-bit, added to a uniform per-chunk base pointer)
+    const uint32_t koff = (uint32_t)(s_tok * DP + 4 * s_q);
+    const uint32_t voff = (uint32_t)s_tok * (uint32_t)dv + (uint32_t)(16 * s_q);
     auto load_raw = [&](int tok0) {
-        const int tok = tok0 + s_tok;
-        const bool ok = tok < tok_end;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        raw_k = ok ? *reinterpret_cast<const u32x4 *>(ku + (size_t)tok * DP + 8 * s_half) : zero;
-        if (MODE == 0) raw_q = ok ? *reinterpret_cast<const u32x4 *>(qu + (size_t)tok * DP + 8 * s_half) : zero;
+        const bool ok = tok0 + s_tok < tok_end;
+        const u32x2 zero2 = {0u, 0u};
+        const u32x4 zero4 = {0u, 0u, 0u, 0u};
+        const uint16_t *kc = ku + (size_t)tok0 * DP, *qc = qu + (size_t)tok0 * DP;
+        const uint16_t *vc = vu + (size_t)tok0 * dv;
+        raw_k = ok ? *reinterpret_cast<const u32x2 *>(kc + koff) : zero2;
+        if (MODE == 0) raw_q = ok ? *reinterpret_cast<const u32x2 *>(qc + koff) : zero2;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            raw_v[j] = ok ? *reinterpret_cast<const u32x4 *>(vu + (size_t)tok * dv + 32 * s_half + 8 * j) : zero;
+        for (int j = 0; j < 2; ++j) raw_v[j] = ok ? *reinterpret_cast<const u32x4 *>(vc + voff + 8 * j) : zero4;
     };
-    auto stage = [&](Stage &st, int tok0) {
+    auto stage = [&](int tok0) {
+        Stage &st = lds.st;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const uint32_t wd = raw_k[i];
-            st.kts[8 * s_half + 2 * i][s_tok] = bf16lo(wd) * kC4;
-            st.kts[8 * s_half + 2 * i + 1][s_tok] = bf16hi(wd) * kC4;
-            st.ktb[8 * s_half + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
-            st.ktb[8 * s_half + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
+            st.kts[4 * s_q + 2 * i][s_tok] = bf16lo(wd) * kC4;
+            st.kts[4 * s_q + 2 * i + 1][s_tok] = bf16hi(wd) * kC4;
+            st.ktb[4 * s_q + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
+            st.ktb[4 * s_q + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
         }
-        if (s_half == 0) st.ktb[16][s_tok] = (tok0 + s_tok < tok_end) ? (uint16_t)0x3F80u : (uint16_t)0u;
+        *reinterpret_cast<u32x2 *>(&st.krow[s_tok][4 * s_q]) = raw_k;
+        if (s_q == 0) st.ktb[16][s_tok] = (tok0 + s_tok < tok_end) ? (uint16_t)0x3F80u : (uint16_t)0u;
         if (MODE == 0) {
-            f32x4 lo, hi;
-            lo[0] = bf16lo(raw_q[0]) * kC4; lo[1] = bf16hi(raw_q[0]) * kC4;
-            lo[2] = bf16lo(raw_q[1]) * kC4; lo[3] = bf16hi(raw_q[1]) * kC4;
-            hi[0] = bf16lo(raw_q[2]) * kC4; hi[1] = bf16hi(raw_q[2]) * kC4;
-            hi[2] = bf16lo(raw_q[3]) * kC4; hi[3] = bf16hi(raw_q[3]) * kC4;
-            *reinterpret_cast<f32x4 *>(&st.qs[s_tok][8 * s_half]) = lo;
-            *reinterpret_cast<f32x4 *>(&st.qs[s_tok][8 * s_half + 4]) = hi;
+            f32x4 qv;
+            qv[0] = bf16lo(raw_q[0]) * kC4; qv[1] = bf16hi(raw_q[0]) * kC4;
+            qv[2] = bf16lo(raw_q[1]) * kC4; qv[3] = bf16hi(raw_q[1]) * kC4;
+            *reinterpret_cast<f32x4 *>(&st.qs[s_tok][4 * s_q]) = qv;
+            *reinterpret_cast<u32x2 *>(&st.qrow[s_tok][4 * s_q]) = raw_q;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t wd = raw_v[j][i];
-                st.vt[32 * s_half + 8 * j + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
-                st.vt[32 * s_half + 8 * j + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
+                st.vt[16 * s_q + 8 * j + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
+                st.vt[16 * s_q + 8 * j + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
             }
     };
 
-    // operand whose only non-zero entry is k-slot 0 (the constant feature, local row 16)
-    u32x4 const_op = {0u, 0u, 0u, 0u};
-    if (g == 0) const_op[0] = 0x3F80u;
-
-    // operands that come straight from global memory: q (two 8-byte pieces per lane) for the
-    // 1st-order rows and the moments; K and Q tiles of the intra-chunk block (wave 1)
-    u32x4 kop[2], qop[2], qbop[2];
-    auto load_ops = [&](int tok0) {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-            const int tok = tok0 + 32 * t2 + n;
-            const bool ok = tok < tok_end;
-            qbop[t2] = zero;
-            if (ok) {
-                const u32x2 a = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 4 * g);
-                const u32x2 b = *reinterpret_cast<const u32x2 *>(qu + (size_t)tok * DP + 8 + 4 * g);
-                qbop[t2][0] = a[0]; qbop[t2][1] = a[1]; qbop[t2][2] = b[0]; qbop[t2][3] = b[1];
-            }
-            if (w == 1) {
-                kop[t2] = ok ? *reinterpret_cast<const u32x4 *>(ku + (size_t)tok * DP + 8 * g) : zero;
-                qop[t2] = ok ? *reinterpret_cast<const u32x4 *>(qu + (size_t)tok * DP + 8 * g) : zero;
-            }
-        }
-    };
-    // V^T operands of a chunk: [kt][s][c2]; lane (g, n): column 32 c2 + n, tokens of the slab
-    auto load_vop = [&](const Stage &st, bf16x8 (&vop)[2][2][2]) {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    const uint16_t *p = &st.vt[32 * c2 + n][32 * kt + 16 * s + 4 * g];
-                    const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                    const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                    u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                    vop[kt][s][c2] = as_bf16x8(o);
-                }
-    };
-
-    // Pipeline: chunk c+1 is fetched from global memory and staged into the other LDS buffer
-    // during the update phase of chunk c, so its latency hides under the update MFMAs.
+    // Pipeline: the rows of chunk c+1 are fetched from global memory into registers before the
+    // update phase of chunk c and written to LDS after it, so their latency hides under the MFMAs.
     if (MODE != 2) {
         load_raw(tok_begin);
-        stage(lds.st[0], tok_begin);
-        if (MODE == 0) load_ops(tok_begin);
+        stage(tok_begin);
     }
-    int buf = 0;
-    for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C, buf ^= 1) {
-        Stage &st = lds.st[buf];
-        wg_sync();   // this chunk's staging is visible; the other buffer is free
+    for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C) {
+        const Stage &st = lds.st;
+        wg_sync();   // this chunk's staging is visible
 
         if (MODE == 0) {
             // =============================== readout ============================================
-            f32x16 Y[2][2];   // Y^T [qt][c2]: lane (g, n) = query 32 qt + n, register r = column
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) Y[qt][c2][r] = 0.f;
-
-            float qa[2][8], qb[2][8];   // c*q_a for a = 8w .. 8w+7; c*q_b for b = 8 jj + 4 g + i
+            // One query tile (32 tokens) at a time, so that only two partial output tiles are live:
+            // Y^T [c2]: lane (g, n) = query 32 qt + n, register r = column within column tile c2.
+            f32x16 Yown;      // this wave's partial of the tile it finishes (query tile w / 2, column tile w % 2)
+            zero16(Yown);
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
-                const float *row = st.qs[32 * qt + n];
-                const f32x4 a0 = *reinterpret_cast<const f32x4 *>(row + 8 * w);
-                const f32x4 a1 = *reinterpret_cast<const f32x4 *>(row + 8 * w + 4);
-                const f32x4 b0 = *reinterpret_cast<const f32x4 *>(row + 4 * g);
-                const f32x4 b1 = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
+                f32x16 Y[2];
+                zero16(Y[0]); zero16(Y[1]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    qa[qt][i] = a0[i]; qa[qt][4 + i] = a1[i];
-                    qb[qt][i] = b0[i]; qb[qt][4 + i] = b1[i];
-                }
-            }
+                for (int tt = 0; tt < 2; ++tt) { forget(S[tt][0]); forget(S[tt][1]); }
 
-            // inter-chunk: Y^T += S^T phi(Q)^T over this wave's feature rows
+                float qa[4], qb[8];   // c*q_a for a = 4w .. 4w+3; c*q_b for b = 8 jj + 4 g + i
+                {
+                    const float *row = st.qs[32 * qt + n];
+                    const f32x4 a0 = *reinterpret_cast<const f32x4 *>(row + 4 * w);
+                    const f32x4 b0 = *reinterpret_cast<const f32x4 *>(row + 4 * g);
+                    const f32x4 b1 = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+                    for (int i = 0; i < 4; ++i) { qa[i] = a0[i]; qb[i] = b0[i]; qb[4 + i] = b1[i]; }
+                }
+
+                // inter-chunk: Y^T += S^T phi(Q)^T over this wave's feature rows
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    bf16x8 phiq[2];
+                for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
+                    for (int s = 0; s < 2; ++s) {
                         float pr[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) pr[e] = qa[qt][2 * tt + s] * qb[qt][e];
-                        phiq[qt] = pack8(pr);
+                        for (int e = 0; e < 8; ++e) pr[e] = qa[2 * tt + s] * qb[e];
+                        const bf16x8 phiq = pack8(pr);
+#pragma unroll
+                        for (int c2 = 0; c2 < 2; ++c2) Y[c2] = mfma(pack8_acc(S[tt][c2], s), phiq, Y[c2]);
                     }
+
+                // q pieces of this lane's query: elements 4g .. 4g+3 and 8+4g .. 8+4g+3 (bf16, as given)
+                auto load_qb = [&]() {
+                    const uint16_t *p = &st.qrow[32 * qt + n][4 * g];
+                    const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
+                    const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
+                    u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+                    return as_bf16x8(o);
+                };
+                if (w == 0) {
+                    role_guard();
+                    // 1st-order rows (slab 0: operand is q itself) and the constant row (slab 1: an
+                    // operand whose only non-zero entry is k-slot 0 = local row 16)
+                    const bf16x8 qbo = load_qb();
+                    u32x4 cst = {0u, 0u, 0u, 0u};
+                    if (g == 0) cst[0] = 0x3F80u;
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) {
-                        const bf16x8 sb = pack8_acc(S[tt][c2], s);
-#pragma unroll
-                        for (int qt = 0; qt < 2; ++qt) Y[qt][c2] = mfma(sb, phiq[qt], Y[qt][c2]);
+                        Y[c2] = mfma(pack8_acc(X[c2], 0), qbo, Y[c2]);
+                        Y[c2] = mfma(pack8_acc(X[c2], 1), as_bf16x8(cst), Y[c2]);
                     }
-                }
-
-            if (w == 0) {
-                role_guard();
-                // 1st-order rows (slab 0: operand is q itself) and the constant row (slab 1)
+                } else if (w == 1) {
+                    role_guard();
+                    const bf16x8 qbo = load_qb();
+                    // ---- inter-chunk denominator from the moments: count + q.z1 + q^T M q / 2 ----
+                    float mres[8];
+                    const bf16x8 mhi = pack8_acc(X[0], 0);
+                    {
+                        const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    const bf16x8 s0 = pack8_acc(X[c2], 0), s1 = pack8_acc(X[c2], 1);
-#pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
-                        Y[qt][c2] = mfma(s0, as_bf16x8(qbop[qt]), Y[qt][c2]);
-                        Y[qt][c2] = mfma(s1, as_bf16x8(const_op), Y[qt][c2]);
+                        for (int i = 0; i < 4; ++i) {
+                            mres[2 * i] = X[0][2 * i] - bf16lo(hb[i]);
+                            mres[2 * i + 1] = X[0][2 * i + 1] - bf16hi(hb[i]);
+                        }
                     }
-                }
-                // ---- inter-chunk denominator from the moments: count + q.z1 + q^T M q / 2 --------
-                float mres[8];
-                const bf16x8 mhi = pack8_acc(M, 0);
-                {
-                    const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        mres[2 * i] = M[2 * i] - bf16lo(hb[i]);
-                        mres[2 * i + 1] = M[2 * i + 1] - bf16hi(hb[i]);
-                    }
-                }
-                const bf16x8 mlo = pack8(mres);
-                const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(M[8]), 16));
-#pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                    const bf16x8 mlo = pack8(mres);
+                    const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[0][8]), 16));
                     f32x16 T;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) T[r] = 0.f;
-                    T = mfma(mhi, as_bf16x8(qbop[qt]), T);
-                    T = mfma(mlo, as_bf16x8(qbop[qt]), T);
+                    zero16(T);
+                    T = mfma(mhi, qbo, T);
+                    T = mfma(mlo, qbo, T);
                     float d2 = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) d2 = fmaf(T[e], qb[qt][e], d2);
+                    for (int e = 0; e < 8; ++e) d2 = fmaf(T[e], qb[e], d2);
                     const float d = fmaf(d2, kHalfInvC4, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
                     const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
                     if (g == 0) lds.den_inter[32 * qt + n] = tot;
-                }
-            } else {
-                role_guard();
-                // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
-                bf16x8 vop[2][2][2];
-                load_vop(st, vop);
-                float den[2] = {0.f, 0.f};
+                } else if (w == 2 || qt == 1) {
+                    role_guard();
+                    // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ------
+                    // wave 2: key tile 0 against query tiles 0 and 1; wave 3: key tile 1 against query tile 1
+                    const int kt = w - 2;
+                    const bool diag = kt == qt;
+                    bf16x8 vk[2][2];   // V^T operands of key tile kt: [s][c2]
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                    for (int s = 0; s < 2; ++s)
 #pragma unroll
-                    for (int kt = 0; kt <= qt; ++kt) {
-                        f32x16 P;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) P[r] = 0.f;
-                        P = mfma(as_bf16x8(kop[kt]), as_bf16x8(qop[qt]), P);   // rows keys, columns queries
-                        float dsum = 0.f;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const float x = P[r];
-                            float p = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
-                            if (kt == qt) {
-                                const int key = 8 * (r >> 2) + 4 * g + (r & 3);
-                                p = key <= n ? p : 0.f;
-                            }
-                            P[r] = p;
-                            dsum += p;
+                        for (int c2 = 0; c2 < 2; ++c2) {
+                            const uint16_t *p = &st.vt[32 * c2 + n][32 * kt + 16 * s + 4 * g];
+                            const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
+                            const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
+                            u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+                            vk[s][c2] = as_bf16x8(o);
                         }
-                        den[qt] += dsum;
+                    f32x16 P;
+                    zero16(P);
+                    {   // rows keys (K tile kt), columns queries (Q tile qt), contraction over d'
+                        const u32x4 kop = *reinterpret_cast<const u32x4 *>(&st.krow[32 * kt + n][8 * g]);
+                        const u32x4 qop = *reinterpret_cast<const u32x4 *>(&st.qrow[32 * qt + n][8 * g]);
+                        P = mfma(as_bf16x8(kop), as_bf16x8(qop), P);
+                    }
+                    float dsum = 0.f;
 #pragma unroll
-                        for (int s = 0; s < 2; ++s) {
-                            const bf16x8 pb = pack8_acc(P, s);
-#pragma unroll
-                            for (int c2 = 0; c2 < 2; ++c2) Y[qt][c2] = mfma(vop[kt][s][c2], pb, Y[qt][c2]);
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        const float x = P[r];
+                        float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
+                        const int key = 8 * (r >> 2) + 4 * g + (r & 3);
+                        pv = (!diag || key <= n) ? pv : 0.f;
+                        P[r] = pv;
+                        dsum += pv;
                     }
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
-                    const float tot = den[qt] + __shfl_xor(den[qt], 32, 64);
-                    if (g == 0) lds.den_intra[32 * qt + n] = tot;
+                    for (int s = 0; s < 2; ++s) {
+                        const bf16x8 pb = pack8_acc(P, s);
+#pragma unroll
+                        for (int c2 = 0; c2 < 2; ++c2) Y[c2] = mfma(vk[s][c2], pb, Y[c2]);
+                    }
+                    dsum += __shfl_xor(dsum, 32, 64);
+                    if (g == 0) lds.den_intra[kt][32 * qt + n] = dsum;
+                }
+
+                // partial tiles of this query tile go to the waves that finish them
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    const int d = 2 * qt + c2;
+                    if (d == w) {
+                        Yown = Y[c2];
+                    } else {
+                        const int slot = ((w - d) & 3) - 1;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            f32x4 o;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[i] = Y[c2][4 * j + i];
+                            *reinterpret_cast<f32x4 *>(&lds.xbuf[d][slot][j][lane][0]) = o;
+                        }
+                    }
                 }
             }
-
-            // ---- exchange partials: wave w finishes query tile qt = w ----------------------------
-            auto put_partial = [&](const f32x16 (&Yo)[2]) {
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        f32x4 o;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) o[i] = Yo[c2][4 * j + i];
-                        *reinterpret_cast<f32x4 *>(&lds.xbuf[w][c2 * 4 + j][lane][0]) = o;
-                    }
-            };
-            auto finish = [&](const f32x16 (&Ym)[2]) {
-                const int tok = tok0 + 32 * w + n;
-                const float inv = 1.f / (lds.den_inter[32 * w + n] + lds.den_intra[32 * w + n]);
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const f32x4 o = *reinterpret_cast<const f32x4 *>(&lds.xbuf[1 - w][c2 * 4 + j][lane][0]);
-                        float r4[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) r4[i] = (Ym[c2][4 * j + i] + o[i]) * inv;
-                        if (tok < tok_end) {
-                            f32x4 rv;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) rv[i] = r4[i];
-                            const bf16x4 hv = __builtin_convertvector(rv, bf16x4);
-                            *reinterpret_cast<u32x2 *>(yu + (size_t)tok * dv + 32 * c2 + 8 * j + 4 * g) =
-                                __builtin_bit_cast(u32x2, hv);
-                        }
-                    }
-            };
-            if (w == 0) put_partial(Y[1]); else put_partial(Y[0]);
             wg_sync();
-            if (w == 0) finish(Y[0]); else finish(Y[1]);
+            {
+                const int qt = w >> 1, c2 = w & 1;
+                const int tok = tok0 + 32 * qt + n;
+                const int qi = 32 * qt + n;
+                const float inv = 1.f / (lds.den_inter[qi] + lds.den_intra[0][qi] + lds.den_intra[1][qi]);
+                uint16_t *yc = yu + (size_t)tok0 * dv;
+                const uint32_t yoff = (uint32_t)(32 * qt + n) * (uint32_t)dv + (uint32_t)(32 * c2 + 4 * g);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4 acc;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[i] = Yown[4 * j + i];
+#pragma unroll
+                    for (int sl = 0; sl < 3; ++sl) {
+                        const f32x4 o = *reinterpret_cast<const f32x4 *>(&lds.xbuf[w][sl][j][lane][0]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[i] += o[i];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[i] *= inv;
+                    if (tok < tok_end) {
+                        const bf16x4 hv = __builtin_convertvector(acc, bf16x4);
+                        *reinterpret_cast<u32x2 *>(yc + yoff + 8 * j) = __builtin_bit_cast(u32x2, hv);
+                    }
+                }
+            }
         }
 
         // =================================== update =============================================
         // S += phi(K)^T V over this wave's feature rows; lane (g, n): feature row n of the tile
+        const bool more = tok0 + C < tok_end;
+        if (more) load_raw(tok0 + C);
         {
-            const bool more = tok0 + C < tok_end;
-            if (more) load_raw(tok0 + C);
-            bf16x8 vop[2][2][2];
-            load_vop(st, vop);
             const int brow = n & 15, ahalf = n >> 4;
-            float kb[2][2][8];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
-                    const float *p = &st.kts[brow][32 * kt + 16 * s + 4 * g];
-                    const f32x4 a = *reinterpret_cast<const f32x4 *>(p);
-                    const f32x4 b = *reinterpret_cast<const f32x4 *>(p + 8);
+                    const int tcol = 32 * kt + 16 * s + 4 * g;   // first token of this lane's k-slots
+                    bf16x8 vk[2];   // V^T operands [c2]: column 32 c2 + n, tokens of the slab
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { kb[kt][s][i] = a[i]; kb[kt][s][4 + i] = b[i]; }
-                }
-            // rows a of c K^T for one tile: [kt * 2 + s][jj], fetched one tile ahead of its use so the
-            // LDS latency hides under the previous tile's MFMAs
-            f32x4 ka[2][4][2];
-            auto load_ka = [&](int tt, f32x4 (&dst)[4][2]) {
-                const int arow = 8 * w + 2 * tt + ahalf;
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        const float *p = &st.kts[arow][32 * kt + 16 * s + 4 * g];
-                        dst[kt * 2 + s][0] = *reinterpret_cast<const f32x4 *>(p);
-                        dst[kt * 2 + s][1] = *reinterpret_cast<const f32x4 *>(p + 8);
+                    for (int c2 = 0; c2 < 2; ++c2) {
+                        const uint16_t *p = &st.vt[32 * c2 + n][tcol];
+                        const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
+                        const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
+                        u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+                        vk[c2] = as_bf16x8(o);
                     }
-            };
-            load_ka(0, ka[0]);
-            // Software pipeline over the 16 (tile, slab) steps: the feature products of step i + 1 are
-            // computed (into a second operand register set) while the MFMAs of step i run.  With a
-            // single operand register set the vector ALU would have to wait for each MFMA to finish
-            // reading it before overwriting it, and the two pipes would take turns instead of overlapping.
-            auto gen = [&](int step) {
-                const int tt = step >> 2, ks = step & 3;   // ks = kt * 2 + s
-                float pr[8];
+                    const f32x4 kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
+                    const f32x4 kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    pr[i] = ka[tt & 1][ks][0][i] * kb[ks >> 1][ks & 1][i];
-                    pr[4 + i] = ka[tt & 1][ks][1][i] * kb[ks >> 1][ks & 1][4 + i];
+                    for (int tt = 0; tt < 2; ++tt) {
+                        const int arow = 4 * w + 2 * tt + ahalf;
+                        const f32x4 ka0 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol]);
+                        const f32x4 ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
+                        float pr[8];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) { pr[i] = ka0[i] * kb0[i]; pr[4 + i] = ka1[i] * kb1[i]; }
+                        const bf16x8 phik = pack8(pr);
+#pragma unroll
+                        for (int c2 = 0; c2 < 2; ++c2) S[tt][c2] = mfma(phik, vk[c2], S[tt][c2]);
+                    }
+                    // [k_0..k_15, 1, 0..]^T operand: the 1st/0th-order feature rows (wave 0), the moments (wave 1)
+                    if (w < 2) {
+                        role_guard();
+                        const uint16_t *p = &st.ktb[n][tcol];
+                        const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
+                        const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
+                        u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+                        const bf16x8 kk = as_bf16x8(o);
+                        if (w == 0) {
+#pragma unroll
+                            for (int c2 = 0; c2 < 2; ++c2) X[c2] = mfma(kk, vk[c2], X[c2]);
+                        } else {
+                            X[0] = mfma(kk, kk, X[0]);
+                        }
+                    }
                 }
-                return pack8(pr);
-            };
-            bf16x8 phik[2];
-            phik[0] = gen(0);
-#pragma unroll
-            for (int step = 0; step < 16; ++step) {
-                const int tt = step >> 2, ks = step & 3;
-                if (ks == 0 && tt + 1 < 4) load_ka(tt + 1, ka[(tt + 1) & 1]);
-                if (step + 1 < 16) phik[(step + 1) & 1] = gen(step + 1);
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-                    S[tt][c2] = mfma(phik[step & 1], vop[ks >> 1][ks & 1][c2], S[tt][c2]);
-            }
-            // [k_0..k_15, 1, 0..]^T operand: the 1st/0th-order feature rows and the moment operand
-            if (w == 0)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    role_guard();
-                    const uint16_t *p = &st.ktb[n][32 * kt + 16 * s + 4 * g];
-                    const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                    const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                    u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                    const bf16x8 kk = as_bf16x8(o);
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) X[c2] = mfma(kk, vop[kt][s][c2], X[c2]);
-                    M = mfma(kk, kk, M);
-                }
-            if (more) {
-                stage(lds.st[buf ^ 1], tok0 + C);
-                if (MODE == 0) load_ops(tok0 + C);
-            }
+        }
+        if (more) {
+            wg_sync();   // every wave is done reading this chunk's staging
+            stage(tok0 + C);
         }
     }
 
     // ---- end of segment -----------------------------------------------------------------------
     if (MODE != 0) {
         float *e = ws_unit + (size_t)(MODE == 1 ? 1 + seg : 0) * kWsEntryFloats;
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    f32x4 o;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) o[i] = S[tt][c2][4 * j + i];
-                    *reinterpret_cast<f32x4 *>(e + ws_off(w, tt * 2 + c2, j, lane)) = o;
-                }
-#pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2)
+        auto put = [&](int slot, const f32x16 &a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 f32x4 o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = X[c2][4 * j + i];
-                *reinterpret_cast<f32x4 *>(e + ws_off(w, 8 + c2, j, lane)) = o;
+                for (int i = 0; i < 4; ++i) o[i] = a[4 * j + i];
+                *reinterpret_cast<f32x4 *>(e + ws_slot_off(slot, j, lane)) = o;
             }
+        };
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f32x4 o;
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = M[4 * j + i];
-            *reinterpret_cast<f32x4 *>(e + ws_off(w, 10, j, lane)) = o;
-        }
+            for (int c2 = 0; c2 < 2; ++c2) put(4 * w + 2 * tt + c2, S[tt][c2]);
+        if (w == 0) { put(16, X[0]); put(17, X[1]); }
+        if (w == 1) put(18, X[0]);
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
-                    Su[(size_t)canon_row_main(4 * w + tt, fl) * dv + col0 + 32 * c2 + n] = S[tt][c2][r];
+                    Su[(size_t)canon_row_main(2 * w + tt, fl) * dv + col0 + 32 * c2 + n] = S[tt][c2][r];
             if (w == 0) {
                 const int row = canon_row_extra(fl);
                 if (row >= 0) {
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) Su[(size_t)row * dv + col0 + 32 * c2 + n] = X[c2][r];
                 }
-                if (slice == 0) {
-                    const float m = M[r];
-                    if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
-                    else if (fl == DP && n < DP) zu[1 + n] = m;
-                    else if (fl == DP && n == DP) zu[0] = m;
-                }
+            } else if (w == 1 && slice == 0) {
+                const float m = X[0][r];
+                if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
+                else if (fl == DP && n < DP) zu[1 + n] = m;
+                else if (fl == DP && n == DP) zu[0] = m;
             }
         }
     }
@@ -703,12 +627,12 @@ __global__ __launch_bounds__(NT) void prefill_mfma_kernel(
 // ---- host side ----------------------------------------------------------------------------------
 namespace {
 
-// Segments per sequence: enough workgroups to put a wave on every SIMD of the chip, but segments
+// Segments per sequence: enough workgroups to put two on every CU of the chip, but segments
 // of at least 512 tokens so that the state increments stay small next to q, k, v, y.
 int pick_segments(int U, int N, int dv)
 {
     const long groups = (long)U * (dv / DVS);
-    const long want = 512;   // workgroups of two waves
+    const long want = 512;
     int G = (int)((want + groups - 1) / groups);
     const int max_by_len = N / 512;
     if (G > max_by_len) G = max_by_len;
