@@ -1,14 +1,31 @@
 // Sliding-window causal softmax attention over whole sequences (Sec. 3.2 restricting Eq. 1) on
 // the gfx950 matrix cores: bf16 in, fp32 scores / softmax / accumulation.
 //
-// One workgroup of four waves per (unit, block of 128 consecutive queries).  The w + 128 key and
-// value rows the block can see are staged in LDS once (K row-major, V transposed) and reused by
-// the four waves; each wave owns one tile of 32 queries and walks the w / 32 + 1 key tiles that
-// overlap its window.  Scores are computed transposed (S^T = K Q^T: lane = query, registers =
-// keys), so the row maximum and row sum of the softmax are lane-local plus one cross-lane add,
-// and the probabilities become the operand of Y^T = V^T P^T with a register-local conversion:
-// with k-slot 8g + 4jj + i of slab s mapped to key 16 s + 8 jj + 4 g + i of the tile, accumulator
-// registers 8s .. 8s+7 of a lane are exactly its k-slots (MFMA 32x32x16; lane = 32 g + n).
+// Work split.  One workgroup of four waves per (unit, segment of the sequence) walks its segment
+// in steps of 128 queries; each wave owns one tile of 32 queries of the step and walks the
+// w / 32 + 1 key tiles that overlap its window.
+//
+// Staging.  The w + 128 key and value rows a step can see sit in an LDS ring.  Each step
+// overwrites the 128 oldest rows with its 128 new ones, which were fetched into registers during
+// the previous step, so every row is read from global memory once per segment, with fully
+// coalesced row-major loads, and its latency hides under the arithmetic.  (Fetching K per query
+// tile instead multiplies the L2 traffic by w / 32 + 1.)  The Q tile of the next step is
+// prefetched the same way.
+//
+// Operands.  K and Q tiles are MFMA operands exactly as they lie in memory: a lane's 8 k-slots
+// are 16 contiguous bytes of its row.  The operand of P.V needs 8 keys of one column per lane,
+// which the transposing LDS read (ds_read_b64_tr_b16) delivers from the row-major V rows.
+//
+// Softmax.  Scores are computed transposed (S^T = K Q^T: lane = query, registers = keys), so the
+// row maximum and row sum are lane-local plus one cross-lane exchange, and the probabilities
+// become the operand of Y^T = V^T P^T with a register-local conversion: with k-slot 8g + 4jj + i
+// of slab s mapped to key 16 s + 8 jj + 4 g + i of the tile, accumulator registers 8s .. 8s+7 of
+// a lane are exactly its k-slots (MFMA 32x32x16; lane = 32 g + n).
+//
+// Output.  Y^T leaves a lane holding scattered 8-byte pieces of its query's row; the tile is
+// turned through a per-wave LDS staging area so that it is stored as whole 128-byte segments.
+// The last w rows of K and V of a sequence are also written to the decode ring buffer by the
+// workgroup that owns the last segment.
 #include "common.h"
 
 namespace based {
@@ -22,16 +39,19 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BQ = 128;   // queries per workgroup
 constexpr int NT = 256;
 
 template <int DH, int W> struct SwaCfg {
     static constexpr int NK = W + BQ;          // staged key rows
+    static constexpr int V_LD = DH + 16;       // bf16 elements per staged V row (row stride = 8 banks mod 32)
     static constexpr int K_LD = DH + 8;        // bf16 elements per staged K row (16-byte pad)
-    static constexpr int VT_LD = NK + 4;       // bf16 elements per staged V^T row (8-byte aligned)
     static constexpr int NKT = W / 32 + 1;     // key tiles per query tile
-    static constexpr size_t lds_bytes = ((size_t)NK * K_LD + (size_t)DH * VT_LD) * 2;
+    static constexpr int Y_LD = 64 + 8;        // bf16 elements per row of a wave's output staging tile (64 columns a pass)
+    static constexpr size_t lds_bytes = ((size_t)NK * (V_LD + K_LD) + (size_t)4 * 32 * Y_LD) * 2;
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -48,149 +68,225 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                                                               const uint16_t *__restrict__ v,
                                                               uint16_t *__restrict__ y,
                                                               uint16_t *__restrict__ ring, int N,
-                                                              float scale_log2e)
+                                                              int seg_len, int nseg, float scale_log2e)
 {
     using Cfg = SwaCfg<DH, W>;
-    constexpr int NK = Cfg::NK, K_LD = Cfg::K_LD, VT_LD = Cfg::VT_LD, NKT = Cfg::NKT;
+    constexpr int NK = Cfg::NK, V_LD = Cfg::V_LD, K_LD = Cfg::K_LD, NKT = Cfg::NKT;
     constexpr int SLABS = DH / 16;   // k-slabs of the score contraction
     constexpr int CT = DH / 32;      // column tiles of the output
+    constexpr int CPR = DH / 8;      // 16-byte chunks per row
+    constexpr int NEWIT = BQ * CPR / NT;   // 16-byte chunks per thread for the BQ new rows of a step
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    uint16_t *Ks = reinterpret_cast<uint16_t *>(lds_raw);      // [NK][K_LD]
-    uint16_t *Vt = Ks + (size_t)NK * K_LD;                     // [DH][VT_LD]
+    uint16_t *Vs = reinterpret_cast<uint16_t *>(lds_raw);      // [NK][V_LD]: ring of staged V rows
+    uint16_t *Ks = Vs + (size_t)NK * V_LD;                     // [NK][K_LD]: ring of staged K rows
+    constexpr int Y_LD = Cfg::Y_LD;
+    uint16_t *Ysh = Ks + (size_t)NK * K_LD;                    // [4 waves][32][Y_LD]: output tiles on their way out
 
     const int tid = threadIdx.x;
     // wave index as a scalar, so that branches on it are scalar branches (MFMA ignores EXEC)
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, g = lane >> 5, n = lane & 31;
-    const int nblk = (N + BQ - 1) / BQ;
-    const int u = blockIdx.x / nblk, i0 = (blockIdx.x % nblk) * BQ;
+    const int u = blockIdx.x / nseg, seg = blockIdx.x % nseg;
+    const int q0 = seg * seg_len;                       // first query of this workgroup's segment
+    const int q_end = min(N, q0 + seg_len);
     const size_t base = (size_t)u * N * DH;
-    const int key0 = i0 - W;   // sequence position of staged row 0 (may be negative)
+    uint16_t *ring_u = ring ? ring + (size_t)u * 2 * W * DH : nullptr;
 
-    // ---- stage K (row-major) and V (transposed); rows outside the sequence are zero ------------
-    // A wave instruction handles 64 consecutive rows of one 16-byte column chunk: the transposed
-    // 2-byte V writes of its lanes are then contiguous in LDS (no bank conflicts).
-    constexpr int CPR = DH / 8;   // 16-byte chunks per row
-    static_assert(NK % 64 == 0, "staged rows must be a multiple of the wave size");
-    for (int idx = tid; idx < NK * CPR; idx += NT) {
-        const int c = (idx >> 6) % CPR, r = (idx & 63) + 64 * (idx / (64 * CPR));
-        const int key = key0 + r;
-        u32x4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (key >= 0 && key < N) {
-            kv = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
-            vv = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
+    // Staged row of key position p lives in LDS row (p - (q0 - W)) mod NK: a ring of W + BQ rows.
+    // A step handles BQ queries; going to the next step overwrites the BQ oldest rows with the BQ
+    // new keys, every K / V row of the segment is staged exactly once (plus the W-row halo at the
+    // segment start), and the next step's rows are fetched into registers while this step computes.
+    auto stage_rows = [&](int first_key, int first_slot_row, int rows) {   // used for the initial fill
+        for (int idx = tid; idx < rows * CPR; idx += NT) {
+            const int r = idx / CPR, c = idx % CPR;
+            const int key = first_key + r;
+            u32x4 vv = {0u, 0u, 0u, 0u}, kv = {0u, 0u, 0u, 0u};
+            if (key >= 0 && key < N) {
+                vv = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
+                kv = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
+                // the w-slot ring receives the last min(N, w) rows (slot = position mod w), written
+                // by the segment that owns the row as a query row
+                if (ring_u && key >= q0 && key >= N - W) {
+                    uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
+                    *reinterpret_cast<u32x4 *>(rk) = kv;
+                    *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = vv;
+                }
+            }
+            const int slot = (first_slot_row + r) % NK;
+            *reinterpret_cast<u32x4 *>(Vs + (size_t)slot * V_LD + c * 8) = vv;
+            *reinterpret_cast<u32x4 *>(Ks + (size_t)slot * K_LD + c * 8) = kv;
         }
-        *reinterpret_cast<u32x4 *>(Ks + (size_t)r * K_LD + c * 8) = kv;
-        // the w-slot ring receives the last min(N, w) rows (slot = position mod w); each row is
-        // written by the block that owns it as a query row (staged rows W .. W + BQ - 1)
-        if (ring && r >= W && key < N && key >= N - W) {
-            uint16_t *rk = ring + (size_t)u * 2 * W * DH + (size_t)(key % W) * DH + c * 8;
-            *reinterpret_cast<u32x4 *>(rk) = kv;
-            *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = vv;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            Vt[(size_t)(c * 8 + 2 * i) * VT_LD + r] = (uint16_t)(vv[i] & 0xffffu);
-            Vt[(size_t)(c * 8 + 2 * i + 1) * VT_LD + r] = (uint16_t)(vv[i] >> 16);
-        }
-    }
+    };
+    stage_rows(q0 - W, 0, NK);
 
-    // ---- this wave's query tile: Q operand straight from global memory ---------------------------
-    const int qbase = i0 + 32 * wv;          // first query of the tile
-    const int query = qbase + n;
-    const bool q_ok = query < N;
-    u32x4 qop[SLABS];
-#pragma unroll
-    for (int s = 0; s < SLABS; ++s) {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        qop[s] = q_ok ? *reinterpret_cast<const u32x4 *>(q + base + (size_t)query * DH + 16 * s + 8 * g) : zero;
-    }
-    __syncthreads();
-    if (qbase >= N) return;   // whole tile past the end (no barrier follows)
-
-    // ---- scores: S^T tile t covers staged rows 32 wv + 32 t .. +31 --------------------------------
-    f32x16 P[NKT];
-#pragma unroll
-    for (int t = 0; t < NKT; ++t) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) P[t][r] = 0.f;
-        const uint16_t *krow = Ks + (size_t)(32 * wv + 32 * t + n) * K_LD + 8 * g;
+    u32x4 nk[NEWIT], nv[NEWIT];   // next step's new rows, in flight during this step
+    u32x4 qop[SLABS], qnext[SLABS];
+    auto load_q = [&](int step_q0, u32x4 (&dst)[SLABS]) {
+        const int query = step_q0 + 32 * wv + n;
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
-            const u32x4 kop = *reinterpret_cast<const u32x4 *>(krow + 16 * s);
-            P[t] = mfma(as_bf16x8(kop), as_bf16x8(qop[s]), P[t]);
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            dst[s] = query < q_end ? *reinterpret_cast<const u32x4 *>(q + base + (size_t)query * DH + 16 * s + 8 * g) : zero;
         }
-    }
+    };
+    load_q(q0, qop);
+    __syncthreads();
 
-    // ---- mask, softmax statistics (lane = query; its keys sit in registers and in lane ^ 32) ------
-    float m = -INFINITY;
+    for (int sq0 = q0; sq0 < q_end; sq0 += BQ) {
+        const bool more = sq0 + BQ < q_end;
+        if (more) {   // prefetch the BQ rows of the next step and its queries
 #pragma unroll
-    for (int t = 0; t < NKT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int local = 8 * (r >> 2) + 4 * g + (r & 3);
-            const int key = qbase - W + 32 * t + local;
-            bool ok = key >= 0;
-            if (t == 0) ok = ok && local > n;          // key > query - w
-            if (t == NKT - 1) ok = ok && local <= n;   // key <= query
-            const float x = ok ? P[t][r] * scale_log2e : -INFINITY;
-            P[t][r] = x;
-            m = fmaxf(m, x);
+            for (int it = 0; it < NEWIT; ++it) {
+                const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+                const int key = sq0 + BQ + r;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                nk[it] = key < N ? *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8) : zero;
+                nv[it] = key < N ? *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8) : zero;
+            }
+            load_q(sq0 + BQ, qnext);
         }
-    m = fmaxf(m, __shfl_xor(m, 32, 64));
-    // the query's own key is always visible, so m is finite for every query inside the sequence
-    const float mm = q_ok ? m : 0.f;
-    float sum = 0.f;
-#pragma unroll
-    for (int t = 0; t < NKT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(P[t][r] - mm);   // exp2(-inf) = 0 for masked keys
-            P[t][r] = p;
-            sum += p;
-        }
-    sum += __shfl_xor(sum, 32, 64);
 
-    // ---- Y^T = V^T P^T ----------------------------------------------------------------------------
-    f32x16 Y[CT];
+        const int qbase = sq0 + 32 * wv;          // first query of this wave's tile
+        const int query = qbase + n;
+        const bool q_ok = query < q_end;
+        if (qbase < q_end) {
+            // row of key position p in the LDS ring
+            const int rel0 = qbase - W - (q0 - W);   // ring position of the oldest key tile of this query tile
+
+            // ---- scores: S^T tile t holds keys qbase - W + 32 t .. +31 (rows) against the 32 queries --
+            f32x16 P[NKT];
 #pragma unroll
-    for (int c2 = 0; c2 < CT; ++c2)
+            for (int t = 0; t < NKT; ++t) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) Y[c2][r] = 0.f;
+                for (int r = 0; r < 16; ++r) P[t][r] = 0.f;
+                const int slot0 = (rel0 + 32 * t) % NK;   // tiles never wrap inside (NK is a multiple of 32)
+                const uint16_t *krow = Ks + (size_t)(slot0 + n) * K_LD + 8 * g;
 #pragma unroll
-    for (int t = 0; t < NKT; ++t)
+                for (int s = 0; s < SLABS; ++s) {
+                    const u32x4 kop = *reinterpret_cast<const u32x4 *>(krow + 16 * s);
+                    P[t] = mfma(as_bf16x8(kop), as_bf16x8(qop[s]), P[t]);
+                }
+            }
+
+            // ---- mask, softmax statistics (lane = query; its keys sit in registers and in lane ^ 32) --
+            float m = -INFINITY;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            f32x8 f;
+            for (int t = 0; t < NKT; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = P[t][8 * s + e];
-            const bf16x8 pb = __builtin_convertvector(f, bf16x8);
-            const int rowk = 32 * wv + 32 * t + 16 * s + 4 * g;   // first staged key of this lane's k-slots
+                for (int r = 0; r < 16; ++r) {
+                    const int local = 8 * (r >> 2) + 4 * g + (r & 3);
+                    const int key = qbase - W + 32 * t + local;
+                    bool ok = key >= 0;
+                    if (t == 0) ok = ok && local > n;          // key > query - w
+                    if (t == NKT - 1) ok = ok && local <= n;   // key <= query
+                    const float x = ok ? P[t][r] * scale_log2e : -INFINITY;
+                    P[t][r] = x;
+                    m = fmaxf(m, x);
+                }
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            // the query's own key is always visible, so m is finite for every query inside the sequence
+            const float mm = q_ok ? m : 0.f;
+            float sum = 0.f;
 #pragma unroll
-            for (int c2 = 0; c2 < CT; ++c2) {
-                const uint16_t *p = Vt + (size_t)(32 * c2 + n) * VT_LD + rowk;
-                const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                Y[c2] = mfma(as_bf16x8(o), pb, Y[c2]);
+            for (int t = 0; t < NKT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pe = __builtin_amdgcn_exp2f(P[t][r] - mm);   // exp2(-inf) = 0 for masked keys
+                    P[t][r] = pe;
+                    sum += pe;
+                }
+            sum += __shfl_xor(sum, 32, 64);
+
+            // ---- Y^T = V^T P^T ----------------------------------------------------------------------------
+            f32x16 Y[CT];
+#pragma unroll
+            for (int c2 = 0; c2 < CT; ++c2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) Y[c2][r] = 0.f;
+#pragma unroll
+            for (int t = 0; t < NKT; ++t) {
+                const int slot0 = (rel0 + 32 * t) % NK;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    f32x8 f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = P[t][8 * s + e];
+                    const bf16x8 pb = __builtin_convertvector(f, bf16x8);
+                    // V^T operand: lane (g, n) needs column 32 c2 + n at the 8 keys of its k-slots (two runs
+                    // of 4 consecutive staged rows).  Transposing read: in each group of 16 lanes, lane k
+                    // supplies the address of 4 consecutive columns of row (k / 4), columns 4 (k % 4) .. of the
+                    // group's 16-column block, and receives column k of that block at the 4 rows.
+                    const int rowk = slot0 + 16 * s + 4 * g;   // first staged row of this lane's k-slots
+                    const int kk = lane & 15, grp = (lane >> 4) & 1;
+                    const uint16_t *pv = Vs + (size_t)(rowk + (kk >> 2)) * V_LD + 16 * grp + 4 * (kk & 3);
+#pragma unroll
+                    for (int c2 = 0; c2 < CT; ++c2) {
+                        const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) s16x4 *)(pv + 32 * c2));
+                        const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) s16x4 *)(pv + 32 * c2 + 8 * V_LD));
+                        s16x8 o;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) { o[i] = a[i]; o[4 + i] = b[i]; }
+                        Y[c2] = mfma(__builtin_bit_cast(bf16x8, o), pb, Y[c2]);
+                    }
+                }
+            }
+
+            // ---- normalise and store ---------------------------------------------------------------------
+            // lane = query, register r = column 8 (r / 4) + 4 g + r % 4: stored directly, a lane would
+            // write 8-byte pieces of its own row (16-byte write requests, which stall the memory
+            // pipeline).  The tile goes through this wave's LDS staging rows instead and leaves as
+            // whole 128-byte row segments, 64 columns a pass: lane l writes 16 bytes of row l / 8.
+            {
+                const float inv = q_ok ? 1.f / sum : 0.f;
+                uint16_t *yt = Ysh + (size_t)wv * 32 * Y_LD;
+#pragma unroll
+                for (int cp = 0; cp < DH / 64; ++cp) {
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            f32x4 o;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[i] = Y[2 * cp + c2][4 * j + i] * inv;
+                            const bf16x4 hv = __builtin_convertvector(o, bf16x4);
+                            *reinterpret_cast<u32x2 *>(yt + (size_t)n * Y_LD + 32 * c2 + 8 * j + 4 * g) =
+                                __builtin_bit_cast(u32x2, hv);
+                        }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's tile is complete in LDS
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int row = it * 8 + lane / 8, c = lane % 8;
+                        const u32x4 val = *reinterpret_cast<const u32x4 *>(yt + (size_t)row * Y_LD + c * 8);
+                        if (qbase + row < q_end)
+                            *reinterpret_cast<u32x4 *>(y + base + (size_t)(qbase + row) * DH + 64 * cp + c * 8) = val;
+                    }
+                }
             }
         }
 
-    // ---- normalise and store: lane = query, register r = column 8 (r / 4) + 4 g + r % 4 ----------
-    if (q_ok) {
-        const float inv = 1.f / sum;
-        uint16_t *yrow = y + base + (size_t)query * DH + 4 * g;
+        if (more) {
+            __syncthreads();   // every wave is done with the rows that are overwritten now
+            const int rel_new = (sq0 + BQ) - (q0 - W);   // ring position of the first new key
 #pragma unroll
-        for (int c2 = 0; c2 < CT; ++c2)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                f32x4 o;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = Y[c2][4 * j + i] * inv;
-                const bf16x4 hv = __builtin_convertvector(o, bf16x4);
-                *reinterpret_cast<u32x2 *>(yrow + 32 * c2 + 8 * j) = __builtin_bit_cast(u32x2, hv);
+            for (int it = 0; it < NEWIT; ++it) {
+                const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+                const int key = sq0 + BQ + r;
+                const int slot = (rel_new + r) % NK;
+                *reinterpret_cast<u32x4 *>(Vs + (size_t)slot * V_LD + c * 8) = nv[it];
+                *reinterpret_cast<u32x4 *>(Ks + (size_t)slot * K_LD + c * 8) = nk[it];
+                if (ring_u && key < N && key >= N - W && key < q_end) {
+                    uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
+                    *reinterpret_cast<u32x4 *>(rk) = nk[it];
+                    *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = nv[it];
+                }
             }
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) qop[s] = qnext[s];
+            __syncthreads();
+        }
     }
 }
 
@@ -203,10 +299,17 @@ static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, v
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::lds_bytes);
     if (e != hipSuccess) return e;
-    const size_t nblk = (size_t)(N + BQ - 1) / BQ;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(nblk * U)), dim3(NT), Cfg::lds_bytes, s, (const uint16_t *)q,
-                       (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y, (uint16_t *)ring, N,
-                       scale * 1.44269504088896340736f);
+    // Segments per sequence: enough workgroups to fill the chip twice over, but segments of at least
+    // 4 steps so that the W-row halo at a segment start stays small next to the segment.
+    const int steps = (N + BQ - 1) / BQ;
+    int nseg = (int)((768 + (long)U - 1) / U);
+    if (nseg > steps / 4) nseg = steps / 4;
+    if (nseg < 1) nseg = 1;
+    const int seg_len = ((steps + nseg - 1) / nseg) * BQ;
+    nseg = (N + seg_len - 1) / seg_len;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)nseg * U)), dim3(NT), Cfg::lds_bytes, s,
+                       (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y,
+                       (uint16_t *)ring, N, seg_len, nseg, scale * 1.44269504088896340736f);
     return hipGetLastError();
 }
 
