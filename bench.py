@@ -31,9 +31,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), or None while unmeasured.
-MEASURED_PREFILL_TRAFFIC_BYTES = None
+# HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
+# profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
+# They hold for the workloads this file times and for the kernels as committed with those summaries.
+MEASURED_PREFILL_TRAFFIC_BYTES = 214576087     # based_prefill, both launches (prefill_360m)
+MEASURED_DECODE_TRAFFIC_BYTES = 578799519      # decode_step_kernel (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64) -> int:
@@ -51,6 +53,9 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=1024, help="steps of the batch-128 decode leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-leg", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain device copies of 1 GiB (not timed): the known traffic that "
+                         "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -97,6 +102,14 @@ def main() -> int:
         s["ys"] = torch.empty((B, H, dh), dtype=bf, device=dev)
         sets.append(s)
     workspace = based.alloc_prefill_workspace(B, H, N, dp, dv, based.BF16, dev)
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
@@ -222,7 +235,7 @@ def decode_leg(torch, based, synth, dev, steps: int):
         "state_update_tokens_per_s": round(B / (ms_lin * 1e-3), 1),
         "roofline": {"kernel": "based_decode_step (decode_step_kernel)", "bound": "hbm", "achieved": round(gbs_lin, 1),
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs_lin / PEAK_HBM_GBS, 4),
-                     "algorithmic_bytes_per_launch": lin_bytes, "traffic": None},
+                     "algorithmic_bytes_per_launch": lin_bytes, "traffic": MEASURED_DECODE_TRAFFIC_BYTES},
     }
 
 

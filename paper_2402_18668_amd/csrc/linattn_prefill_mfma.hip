@@ -60,6 +60,7 @@ constexpr int KTB_LD = C + 4;     // bf16 [K^T; ones; 0] rows (8-byte aligned re
 constexpr int VT_LD = C + 4;      // bf16 V^T rows
 constexpr int QS_LD = DP + 4;     // fp32 Q rows
 constexpr int RB_LD = DP + 8;     // bf16 row-major Q / K rows (48-byte stride)
+constexpr int YT_LD = 32 + 8;     // bf16 rows of a finished output tile on its way out (80-byte stride)
 
 // Workspace entry (one segment's state in accumulator layout): 19 slots of 16 registers x 64
 // lanes: slot 4w + 2tt + c2 = main tile tt of wave w, column tile c2; slots 16, 17 = 1st/0th-order
@@ -498,28 +499,40 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             wg_sync();
             {
                 const int qt = w >> 1, c2 = w & 1;
-                const int tok = tok0 + 32 * qt + n;
                 const int qi = 32 * qt + n;
                 const float inv = 1.f / (lds.den_inter[qi] + lds.den_intra[0][qi] + lds.den_intra[1][qi]);
-                uint16_t *yc = yu + (size_t)tok0 * dv;
-                const uint32_t yoff = (uint32_t)(32 * qt + n) * (uint32_t)dv + (uint32_t)(32 * c2 + 4 * g);
+                // Sum the partials, normalise, and turn the tile through LDS (the wave's own exchange
+                // slot, which it has finished reading by then): a lane holds 8-byte pieces of its
+                // token's row, and stored directly those become 16-byte write requests that stall the
+                // memory pipeline; from LDS the tile leaves as 64-byte row segments, 16 rows a store.
+                f32x4 acc[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    f32x4 acc;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[i] = Yown[4 * j + i];
+                    for (int i = 0; i < 4; ++i) acc[j][i] = Yown[4 * j + i];
 #pragma unroll
                     for (int sl = 0; sl < 3; ++sl) {
                         const f32x4 o = *reinterpret_cast<const f32x4 *>(&lds.xbuf[w][sl][j][lane][0]);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[i] += o[i];
+                        for (int i = 0; i < 4; ++i) acc[j][i] += o[i];
                     }
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[i] *= inv;
-                    if (tok < tok_end) {
-                        const bf16x4 hv = __builtin_convertvector(acc, bf16x4);
-                        *reinterpret_cast<u32x2 *>(yc + yoff + 8 * j) = __builtin_bit_cast(u32x2, hv);
-                    }
+                    for (int i = 0; i < 4; ++i) acc[j][i] *= inv;
+                }
+                uint16_t *yt = reinterpret_cast<uint16_t *>(&lds.xbuf[w][0][0][0][0]);   // [32][YT_LD] bf16
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bf16x4 hv = __builtin_convertvector(acc[j], bf16x4);
+                    *reinterpret_cast<u32x2 *>(yt + n * YT_LD + 8 * j + 4 * g) = __builtin_bit_cast(u32x2, hv);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                uint16_t *yc = yu + (size_t)tok0 * dv;
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int row = 16 * it + (lane >> 2), c = lane & 3;
+                    const u32x4 val = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * c);
+                    const uint32_t yoff = (uint32_t)(32 * qt + row) * (uint32_t)dv + (uint32_t)(32 * c2 + 8 * c);
+                    if (tok0 + 32 * qt + row < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff) = val;
                 }
             }
         }
