@@ -6,16 +6,25 @@
 // KV-state S (Eq. 3) read out with phi(Q) and updated with phi(K)^T V.  The expanded features
 // are produced in registers straight into MFMA operand layout and never stored anywhere.
 //
+// Symmetric packing of the 2nd-order block.  The state rows (a, b) and (b, a) of Eq. 4 are equal
+// (x_a x_b = x_b x_a), so only one row per unordered pair is carried: row (a, delta) stands for
+// the pair {a, (a + delta) mod 16} with delta = 0 .. 7 for every a (128 rows) and delta = 8 for
+// a < 8 (8 rows), 136 rows instead of 256.  The k side builds x_a x_b / sqrt(2) (the canonical
+// state row); the q side builds sqrt(2) x_a x_b for delta != 0 (the pair counts twice in the sum
+// over ordered pairs) and x_a^2 / sqrt(2) for delta = 0.  The cyclic enumeration keeps the
+// operand construction regular: for a fixed delta the 16 features are x (.) rotate(x, delta).
+// The final state is written in the canonical layout (both rows of a pair); an initial state is
+// read as its symmetric part, which is all the readout can see.
+//
 // Work split.  One workgroup of four waves per (unit, 64-column slice of d_v, sequence segment).
-// The 2nd-order feature rows (a, b) -> x_a x_b / sqrt(2) are cut into 8 tiles of 32 rows
-// (tile t holds a in {2t, 2t+1}, all b); wave w owns tiles 2w and 2w+1, whose 32x32 fp32 state
-// tiles stay in its registers for the whole segment.  The remaining work is spread over the
-// waves: wave 0 owns the tile of the 1st/0th-order rows [x_0..x_15, 1]; wave 1 the moments that
-// give the denominator; waves 2 and 3 the intra-chunk block.  Per chunk each wave produces a
+// Wave w owns the 32 rows delta in {2w, 2w+1} (its "main tile"), whose 32x32 fp32 state tiles
+// stay in its registers for the whole segment.  The remaining work is spread over the waves:
+// wave 0 owns the "extra tile" [x_0..x_15, 1, 0 x 7, the 8 rows of delta = 8]; wave 1 the moments
+// that give the denominator; waves 2 and 3 the intra-chunk block.  Per chunk each wave produces a
 // partial Y^T over its feature rows; the partials are exchanged through LDS and wave w finishes
-// the 32x32 output tile (query tile w / 2, column tile w % 2).  Each wave needs fewer than 256
-// registers, so two workgroups (eight waves) share a CU and one wave's vector-ALU work (feature
-// products, conversions) overlaps the other's MFMAs.
+// the 32x32 output tile (query tile w / 2, column tile w % 2).  Two workgroups (eight waves)
+// share a CU, so one wave's vector-ALU work (feature products, conversions) overlaps another's
+// MFMAs.
 //
 // MFMA 32x32x16 register layouts used throughout (lane = 32 g + n):
 //   A operand: row n, k-slots 8g .. 8g+7;  B operand: column n, k-slots 8g .. 8g+7;
@@ -41,6 +50,7 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -51,8 +61,9 @@ constexpr int C = 64;             // chunk length (tokens)
 constexpr int NW = 4;             // waves per workgroup
 constexpr int NT = NW * 64;
 constexpr int DVS = 64;           // d_v columns per workgroup
-constexpr float kC4 = 0.84089641525371454303f;   // 2^(-1/4): (x_a c)(x_b c) = x_a x_b / sqrt(2)
-constexpr float kHalfInvC4 = 0.59460355750136053336f;  // 0.5 * 2^(1/4)
+constexpr float kCK = 0.84089641525371454303f;   // 2^(-1/4): (c k_a)(c k_b) = k_a k_b / sqrt(2)
+constexpr float kCQ = 1.18920711500272106672f;   // 2^(+1/4): (c q_a)(c q_b) = sqrt(2) q_a q_b
+constexpr float kHalfInvCQ = 0.42044820762685725f;   // 0.5 / kCQ
 
 // LDS strides (elements)
 constexpr int KTS_LD = C + 4;     // fp32 K^T rows
@@ -62,18 +73,19 @@ constexpr int QS_LD = DP + 4;     // fp32 Q rows
 constexpr int RB_LD = DP + 8;     // bf16 row-major Q / K rows (48-byte stride)
 constexpr int YT_LD = 32 + 8;     // bf16 rows of a finished output tile on its way out (80-byte stride)
 
-// Workspace entry (one segment's state in accumulator layout): 19 slots of 16 registers x 64
-// lanes: slot 4w + 2tt + c2 = main tile tt of wave w, column tile c2; slots 16, 17 = 1st/0th-order
-// tile (column tiles 0, 1); slot 18 = moment tile.  Within a slot: [r / 4][lane][r % 4], so that
-// one 16-byte access per lane is contiguous across the wave.
-constexpr int WS_SLOTS = 19;
+// Workspace entry (one segment's state in accumulator layout): 11 slots of 16 registers x 64
+// lanes: slot 2w + c2 = main tile of wave w, column tile c2; slots 8, 9 = extra tile (column
+// tiles 0, 1); slot 10 = moment tile.  Within a slot: [r / 4][lane][r % 4], so that one 16-byte
+// access per lane is contiguous across the wave.
+constexpr int WS_SLOTS = 11;
 constexpr size_t kWsEntryFloats = (size_t)WS_SLOTS * 16 * 64;
 
 struct Stage {
-    float kts[DP][KTS_LD];        // c * K^T
-    uint16_t ktb[32][KTB_LD];     // rows 0..15 K^T (bf16), row 16 token-valid ones, rest zero
+    float kts[DP][KTS_LD];        // c_k * K^T
+    uint16_t ktb[32][KTB_LD];     // rows 0..15 K^T (bf16), row 16 token-valid ones, rows 17..23 zero,
+                                  // rows 24..31 k_a k_(a+8) / sqrt(2) (the delta = 8 feature rows)
     uint16_t vt[DVS][VT_LD];      // V^T (bf16)
-    float qs[C][QS_LD];           // c * Q
+    float qs[C][QS_LD];           // c_q * Q
     uint16_t qrow[C][RB_LD];      // Q rows, bf16 as given
     uint16_t krow[C][RB_LD];      // K rows, bf16 as given
 };
@@ -129,11 +141,6 @@ __device__ __forceinline__ void wg_sync()
 // block makes the compiler keep the jump (it never runs inline asm with an empty EXEC mask).
 __device__ __forceinline__ void role_guard() { asm volatile("; wave-role block: keep the execz branch" ::: "memory"); }
 
-// Makes the compiler forget what it knows about an accumulator tile (no instruction is emitted).
-// Used between the two query-tile passes of the readout so that the bf16 copies of the state are
-// re-made per pass instead of being kept live across both (32 registers).
-__device__ __forceinline__ void forget(f32x16 &a) { asm volatile("" : "+v"(a)); }
-
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -142,51 +149,59 @@ __device__ __forceinline__ size_t ws_slot_off(int slot, int j, int lane)
     return (((size_t)slot * 4 + j) * 64 + lane) * 4;
 }
 
-// Loads six workspace slots (24 x 16 bytes per lane) with all loads in flight at once and the
+// Loads four workspace slots (16 x 16 bytes per lane) with all loads in flight at once and the
 // wait inside the same statement, so that every output register is valid as far as the compiler
 // can tell.  (Separate load statements whose results the compiler believes complete would let
 // it reuse those registers before the data has arrived.)
 __device__ __forceinline__ void load_slots(const float *p0, const float *p1, const float *p2,
-                                           const float *p3, const float *p4, const float *p5,
-                                           f32x4 (&t)[24])
+                                           const float *p3, f32x4 (&t)[16])
 {
     asm volatile(
-        "global_load_dwordx4 %0, %24, off offset:0\n\t"
-        "global_load_dwordx4 %1, %24, off offset:1024\n\t"
-        "global_load_dwordx4 %2, %24, off offset:2048\n\t"
-        "global_load_dwordx4 %3, %24, off offset:3072\n\t"
-        "global_load_dwordx4 %4, %25, off offset:0\n\t"
-        "global_load_dwordx4 %5, %25, off offset:1024\n\t"
-        "global_load_dwordx4 %6, %25, off offset:2048\n\t"
-        "global_load_dwordx4 %7, %25, off offset:3072\n\t"
-        "global_load_dwordx4 %8, %26, off offset:0\n\t"
-        "global_load_dwordx4 %9, %26, off offset:1024\n\t"
-        "global_load_dwordx4 %10, %26, off offset:2048\n\t"
-        "global_load_dwordx4 %11, %26, off offset:3072\n\t"
-        "global_load_dwordx4 %12, %27, off offset:0\n\t"
-        "global_load_dwordx4 %13, %27, off offset:1024\n\t"
-        "global_load_dwordx4 %14, %27, off offset:2048\n\t"
-        "global_load_dwordx4 %15, %27, off offset:3072\n\t"
-        "global_load_dwordx4 %16, %28, off offset:0\n\t"
-        "global_load_dwordx4 %17, %28, off offset:1024\n\t"
-        "global_load_dwordx4 %18, %28, off offset:2048\n\t"
-        "global_load_dwordx4 %19, %28, off offset:3072\n\t"
-        "global_load_dwordx4 %20, %29, off offset:0\n\t"
-        "global_load_dwordx4 %21, %29, off offset:1024\n\t"
-        "global_load_dwordx4 %22, %29, off offset:2048\n\t"
-        "global_load_dwordx4 %23, %29, off offset:3072\n\t"
+        "global_load_dwordx4 %0, %16, off offset:0\n\t"
+        "global_load_dwordx4 %1, %16, off offset:1024\n\t"
+        "global_load_dwordx4 %2, %16, off offset:2048\n\t"
+        "global_load_dwordx4 %3, %16, off offset:3072\n\t"
+        "global_load_dwordx4 %4, %17, off offset:0\n\t"
+        "global_load_dwordx4 %5, %17, off offset:1024\n\t"
+        "global_load_dwordx4 %6, %17, off offset:2048\n\t"
+        "global_load_dwordx4 %7, %17, off offset:3072\n\t"
+        "global_load_dwordx4 %8, %18, off offset:0\n\t"
+        "global_load_dwordx4 %9, %18, off offset:1024\n\t"
+        "global_load_dwordx4 %10, %18, off offset:2048\n\t"
+        "global_load_dwordx4 %11, %18, off offset:3072\n\t"
+        "global_load_dwordx4 %12, %19, off offset:0\n\t"
+        "global_load_dwordx4 %13, %19, off offset:1024\n\t"
+        "global_load_dwordx4 %14, %19, off offset:2048\n\t"
+        "global_load_dwordx4 %15, %19, off offset:3072\n\t"
         "s_waitcnt vmcnt(0)"
         : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]),
           "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]),
-          "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15]), "=&v"(t[16]), "=&v"(t[17]), "=&v"(t[18]),
-          "=&v"(t[19]), "=&v"(t[20]), "=&v"(t[21]), "=&v"(t[22]), "=&v"(t[23])
-        : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(p4), "v"(p5)
+          "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15])
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
         : "memory");
 }
 
-// canonical state row of local feature row fl of main tile t / of the 1st/0th-order tile
-__device__ __forceinline__ int canon_row_main(int t, int fl) { return 1 + DP + 32 * t + fl; }
-__device__ __forceinline__ int canon_row_extra(int fl) { return fl < DP ? 1 + fl : (fl == DP ? 0 : -1); }
+// Canonical state rows (Eq. 4 order: row 0 constant, 1 + a linear, 1 + d' + a d' + b the pair
+// (a, b)) of a packed row.  A pair row has two canonical rows (equal for delta = 0).
+struct CanonRows { int r1, r2; };   // r1 < 0: the packed row is padding
+__device__ __forceinline__ CanonRows canon_pair(int a, int b)
+{
+    return {1 + DP + a * DP + b, 1 + DP + b * DP + a};
+}
+// local row fl of the main tile of wave w: delta = 2w + fl / 16, a = fl % 16
+__device__ __forceinline__ CanonRows canon_rows_main(int w, int fl)
+{
+    const int a = fl & 15;
+    return canon_pair(a, (a + 2 * w + (fl >> 4)) & 15);
+}
+// local row fl of the extra tile: 0..15 linear, 16 constant, 24..31 the delta = 8 pairs
+__device__ __forceinline__ CanonRows canon_rows_extra(int fl)
+{
+    if (fl < DP) return {1 + fl, 1 + fl};
+    if (fl == DP) return {0, 0};
+    if (fl >= 24) return canon_pair(fl - 24, fl - 16);
+    return {-1, -1};
+}
 
 }  // namespace
 
@@ -204,7 +219,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     __shared__ __align__(16) Lds lds;
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6;   // wave index: owns main tiles 2w, 2w+1
+    const int w = tid >> 6;   // wave index: owns the main tile delta in {2w, 2w+1}
     const int lane = tid & 63;
     const int g = lane >> 5, n = lane & 31;
 
@@ -228,40 +243,34 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     float *ws_unit = ws ? ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats : nullptr;
 
     // ---- accumulators -------------------------------------------------------------------------
-    f32x16 S[2][2];        // main tiles [tt][c2]
-    f32x16 X[2];           // wave 0: 1st/0th-order tile [c2]; wave 1: X[0] = moment tile
+    f32x16 S[2];           // main tile [c2]
+    f32x16 X[2];           // wave 0: extra tile [c2]; wave 1: X[0] = moment tile
                            // M' = [k, 1]^T [k, 1]; unused by waves 2, 3
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2) zero16(S[tt][c2]);
+    zero16(S[0]); zero16(S[1]);
     zero16(X[0]); zero16(X[1]);
 
     if (MODE == 0) {
         // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
         for (int p = has_init ? 0 : 1; p <= seg; ++p) {
             const float *e = ws_unit + (size_t)p * kWsEntryFloats;
-            // slots 4w .. 4w+3, and for waves 0 / 1 their extra tiles (other waves re-read a main slot)
-            const int x0 = w == 0 ? 16 : (w == 1 ? 18 : 4 * w);
-            const int x1 = w == 0 ? 17 : 4 * w;
-            f32x4 t[24];
-            load_slots(e + ws_slot_off(4 * w + 0, 0, lane), e + ws_slot_off(4 * w + 1, 0, lane),
-                       e + ws_slot_off(4 * w + 2, 0, lane), e + ws_slot_off(4 * w + 3, 0, lane),
+            // slots 2w, 2w+1, and for waves 0 / 1 their extra tiles (other waves re-read a main slot)
+            const int x0 = w == 0 ? 8 : (w == 1 ? 10 : 2 * w);
+            const int x1 = w == 0 ? 9 : 2 * w;
+            f32x4 t[16];
+            load_slots(e + ws_slot_off(2 * w + 0, 0, lane), e + ws_slot_off(2 * w + 1, 0, lane),
                        e + ws_slot_off(x0, 0, lane), e + ws_slot_off(x1, 0, lane), t);
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
+            for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) S[tt][c2][r] += t[(tt * 2 + c2) * 4 + (r >> 2)][r & 3];
+                for (int r = 0; r < 16; ++r) S[c2][r] += t[c2 * 4 + (r >> 2)][r & 3];
             if (w == 0) {
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) X[c2][r] += t[(4 + c2) * 4 + (r >> 2)][r & 3];
+                    for (int r = 0; r < 16; ++r) X[c2][r] += t[(2 + c2) * 4 + (r >> 2)][r & 3];
             } else if (w == 1) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) X[0][r] += t[4 * 4 + (r >> 2)][r & 3];
+                for (int r = 0; r < 16; ++r) X[0][r] += t[2 * 4 + (r >> 2)][r & 3];
             }
         }
     }
@@ -269,16 +278,20 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
+            const CanonRows cm = canon_rows_main(w, fl);
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-                    S[tt][c2][r] = Su[(size_t)canon_row_main(2 * w + tt, fl) * dv + col0 + 32 * c2 + n];
+            for (int c2 = 0; c2 < 2; ++c2) {
+                const size_t col = (size_t)col0 + 32 * c2 + n;
+                S[c2][r] = 0.5f * (Su[(size_t)cm.r1 * dv + col] + Su[(size_t)cm.r2 * dv + col]);
+            }
             if (w == 0) {
-                const int row = canon_row_extra(fl);
-                if (row >= 0) {
+                const CanonRows cx = canon_rows_extra(fl);
+                if (cx.r1 >= 0) {
 #pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) X[c2][r] = Su[(size_t)row * dv + col0 + 32 * c2 + n];
+                    for (int c2 = 0; c2 < 2; ++c2) {
+                        const size_t col = (size_t)col0 + 32 * c2 + n;
+                        X[c2][r] = 0.5f * (Su[(size_t)cx.r1 * dv + col] + Su[(size_t)cx.r2 * dv + col]);
+                    }
                 }
             } else if (w == 1) {
                 float m = 0.f;   // M'[fl][n]
@@ -291,46 +304,71 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         }
     }
 
-    // zero rows 17..31 of the K'^T staging rows and the unused half of den_intra[1] once
-    for (int i = tid; i < 15 * KTB_LD; i += NT) lds.st.ktb[17 + i / KTB_LD][i % KTB_LD] = 0;
+    // zero rows 17..23 of the K'^T staging rows and the unused half of den_intra[1] once
+    for (int i = tid; i < 7 * KTB_LD; i += NT) lds.st.ktb[17 + i / KTB_LD][i % KTB_LD] = 0;
     if (tid < C) lds.den_intra[1][tid] = 0.f;
 
     // ---- staging: global -> registers -> LDS ----------------------------------------------------
-    const int s_tok = tid & 63, s_q = tid >> 6;   // this thread stages a quarter of token s_tok's row
-    u32x2 raw_k, raw_q;
+    // Thread (s_tok, s_q) stages, of token s_tok: elements 4h .. 4h+3 and 8+4h .. 8+4h+3 (h = s_q % 2)
+    // of the K row (waves 0, 1) or of the Q row (waves 2, 3), and a quarter of the V row.  Holding
+    // elements a and a + 8 together lets the K threads build the delta = 8 feature rows here.
+    const int s_tok = tid & 63, s_q = tid >> 6, s_h = s_q & 1;
+    u32x2 raw_x[2];        // the two 8-byte pieces of the K or Q row
     u32x4 raw_v[2];
     // per-lane element offsets inside a chunk (32-bit, added to a uniform per-chunk base pointer)
-    const uint32_t koff = (uint32_t)(s_tok * DP + 4 * s_q);
+    const uint32_t xoff = (uint32_t)(s_tok * DP + 4 * s_h);
     const uint32_t voff = (uint32_t)s_tok * (uint32_t)dv + (uint32_t)(16 * s_q);
     auto load_raw = [&](int tok0) {
         const bool ok = tok0 + s_tok < tok_end;
         const u32x2 zero2 = {0u, 0u};
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
-        const uint16_t *kc = ku + (size_t)tok0 * DP, *qc = qu + (size_t)tok0 * DP;
+        const uint16_t *xc = (s_q < 2 ? ku : qu) + (size_t)tok0 * DP;
         const uint16_t *vc = vu + (size_t)tok0 * dv;
-        raw_k = ok ? *reinterpret_cast<const u32x2 *>(kc + koff) : zero2;
-        if (MODE == 0) raw_q = ok ? *reinterpret_cast<const u32x2 *>(qc + koff) : zero2;
+        if (MODE == 0 || s_q < 2) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) raw_x[j] = ok ? *reinterpret_cast<const u32x2 *>(xc + xoff + 8 * j) : zero2;
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j) raw_v[j] = ok ? *reinterpret_cast<const u32x4 *>(vc + voff + 8 * j) : zero4;
     };
     auto stage = [&](int tok0) {
         Stage &st = lds.st;
+        if (s_q < 2) {
+            float kf[2][4];   // c_k * k: [j][i] = element 8 j + 4 h + i
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t wd = raw_k[i];
-            st.kts[4 * s_q + 2 * i][s_tok] = bf16lo(wd) * kC4;
-            st.kts[4 * s_q + 2 * i + 1][s_tok] = bf16hi(wd) * kC4;
-            st.ktb[4 * s_q + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
-            st.ktb[4 * s_q + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
-        }
-        *reinterpret_cast<u32x2 *>(&st.krow[s_tok][4 * s_q]) = raw_k;
-        if (s_q == 0) st.ktb[16][s_tok] = (tok0 + s_tok < tok_end) ? (uint16_t)0x3F80u : (uint16_t)0u;
-        if (MODE == 0) {
-            f32x4 qv;
-            qv[0] = bf16lo(raw_q[0]) * kC4; qv[1] = bf16hi(raw_q[0]) * kC4;
-            qv[2] = bf16lo(raw_q[1]) * kC4; qv[3] = bf16hi(raw_q[1]) * kC4;
-            *reinterpret_cast<f32x4 *>(&st.qs[s_tok][4 * s_q]) = qv;
-            *reinterpret_cast<u32x2 *>(&st.qrow[s_tok][4 * s_q]) = raw_q;
+            for (int j = 0; j < 2; ++j) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const uint32_t wd = raw_x[j][i];
+                    const int a = 8 * j + 4 * s_h + 2 * i;
+                    kf[j][2 * i] = bf16lo(wd) * kCK;
+                    kf[j][2 * i + 1] = bf16hi(wd) * kCK;
+                    st.kts[a][s_tok] = kf[j][2 * i];
+                    st.kts[a + 1][s_tok] = kf[j][2 * i + 1];
+                    st.ktb[a][s_tok] = (uint16_t)(wd & 0xffffu);
+                    st.ktb[a + 1][s_tok] = (uint16_t)(wd >> 16);
+                }
+                *reinterpret_cast<u32x2 *>(&st.krow[s_tok][8 * j + 4 * s_h]) = raw_x[j];
+            }
+            f32x4 pr;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pr[i] = kf[0][i] * kf[1][i];
+            const u32x2 pb = __builtin_bit_cast(u32x2, __builtin_convertvector(pr, bf16x4));
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                st.ktb[24 + 4 * s_h + 2 * i][s_tok] = (uint16_t)(pb[i] & 0xffffu);
+                st.ktb[24 + 4 * s_h + 2 * i + 1][s_tok] = (uint16_t)(pb[i] >> 16);
+            }
+            if (s_q == 0) st.ktb[16][s_tok] = (tok0 + s_tok < tok_end) ? (uint16_t)0x3F80u : (uint16_t)0u;
+        } else if (MODE == 0) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                f32x4 qv;
+                qv[0] = bf16lo(raw_x[j][0]) * kCQ; qv[1] = bf16hi(raw_x[j][0]) * kCQ;
+                qv[2] = bf16lo(raw_x[j][1]) * kCQ; qv[3] = bf16hi(raw_x[j][1]) * kCQ;
+                *reinterpret_cast<f32x4 *>(&st.qs[s_tok][8 * j + 4 * s_h]) = qv;
+                *reinterpret_cast<u32x2 *>(&st.qrow[s_tok][8 * j + 4 * s_h]) = raw_x[j];
+            }
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
@@ -358,35 +396,53 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             // Y^T [c2]: lane (g, n) = query 32 qt + n, register r = column within column tile c2.
             f32x16 Yown;      // this wave's partial of the tile it finishes (query tile w / 2, column tile w % 2)
             zero16(Yown);
+            // bf16 copies of the state tiles: operands of the readout, [slab][c2]
+            bf16x8 Sb[2][2];
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) Sb[sl][c2] = pack8_acc(S[c2], sl);
+            const float diag_w = w == 0 ? 0.5f : 1.f;   // delta = 0 (wave 0, slab 0): x_a^2 / sqrt(2)
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 f32x16 Y[2];
                 zero16(Y[0]); zero16(Y[1]);
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt) { forget(S[tt][0]); forget(S[tt][1]); }
 
-                float qa[4], qb[8];   // c*q_a for a = 4w .. 4w+3; c*q_b for b = 8 jj + 4 g + i
+                // This lane's query row, rotated: qa[j] = c_q q[(4g + j) % 16] for j = 0..3, 8..11 (the
+                // "a side": k-slot (jj, i) is a = 8 jj + 4 g + i) and qr[j] = c_q q[(4g + 2w + j) % 16]
+                // (the "b side" of delta = 2w + s: b = a + delta is qr[(8 jj + i + s) % 16]).
+                float qa[8], qr[16];
                 {
                     const float *row = st.qs[32 * qt + n];
-                    const f32x4 a0 = *reinterpret_cast<const f32x4 *>(row + 4 * w);
-                    const f32x4 b0 = *reinterpret_cast<const f32x4 *>(row + 4 * g);
-                    const f32x4 b1 = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
+                    const f32x4 a0 = *reinterpret_cast<const f32x4 *>(row + 4 * g);
+                    const f32x4 a1 = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { qa[i] = a0[i]; qb[i] = b0[i]; qb[4 + i] = b1[i]; }
+                    for (int i = 0; i < 4; ++i) { qa[i] = a0[i]; qa[4 + i] = a1[i]; }
+                    const int rot = 4 * g + 2 * w;
+#pragma unroll
+                    for (int m = 0; m < 8; ++m) {
+                        if (m == 3 || m == 7) continue;   // qr[6], qr[7], qr[14], qr[15] are never used
+                        const f32x2 pp = *reinterpret_cast<const f32x2 *>(row + ((rot + 2 * m) & 15));
+                        qr[2 * m] = pp[0];
+                        qr[2 * m + 1] = pp[1];
+                    }
                 }
 
                 // inter-chunk: Y^T += S^T phi(Q)^T over this wave's feature rows
 #pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
+                for (int sl = 0; sl < 2; ++sl) {
+                    float pr[8];
 #pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-                        float pr[8];
+                    for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) pr[e] = qa[2 * tt + s] * qb[e];
-                        const bf16x8 phiq = pack8(pr);
+                        for (int i = 0; i < 4; ++i) {
+                            const float av = sl == 0 ? qa[4 * jj + i] * diag_w : qa[4 * jj + i];
+                            pr[4 * jj + i] = av * qr[(8 * jj + i + sl) & 15];
+                        }
+                    const bf16x8 phiq = pack8(pr);
 #pragma unroll
-                        for (int c2 = 0; c2 < 2; ++c2) Y[c2] = mfma(pack8_acc(S[tt][c2], s), phiq, Y[c2]);
-                    }
+                    for (int c2 = 0; c2 < 2; ++c2) Y[c2] = mfma(Sb[sl][c2], phiq, Y[c2]);
+                }
 
                 // q pieces of this lane's query: elements 4g .. 4g+3 and 8+4g .. 8+4g+3 (bf16, as given)
                 auto load_qb = [&]() {
@@ -398,15 +454,19 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 };
                 if (w == 0) {
                     role_guard();
-                    // 1st-order rows (slab 0: operand is q itself) and the constant row (slab 1: an
-                    // operand whose only non-zero entry is k-slot 0 = local row 16)
+                    // extra tile.  Slab 0: the 1st-order rows (the operand is q itself).  Slab 1: the
+                    // constant row (k-slot 0 of g = 0 = local row 16) and the delta = 8 rows
+                    // (k-slots 4 + i = local row 24 + 4g + i: sqrt(2) q_a q_(a+8), a = 4g + i)
                     const bf16x8 qbo = load_qb();
-                    u32x4 cst = {0u, 0u, 0u, 0u};
-                    if (g == 0) cst[0] = 0x3F80u;
+                    float pr[8];
+                    pr[0] = g == 0 ? 1.f : 0.f; pr[1] = 0.f; pr[2] = 0.f; pr[3] = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[4 + i] = qa[i] * qa[4 + i];
+                    const bf16x8 hi = pack8(pr);
 #pragma unroll
                     for (int c2 = 0; c2 < 2; ++c2) {
                         Y[c2] = mfma(pack8_acc(X[c2], 0), qbo, Y[c2]);
-                        Y[c2] = mfma(pack8_acc(X[c2], 1), as_bf16x8(cst), Y[c2]);
+                        Y[c2] = mfma(pack8_acc(X[c2], 1), hi, Y[c2]);
                     }
                 } else if (w == 1) {
                     role_guard();
@@ -430,8 +490,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                     T = mfma(mlo, qbo, T);
                     float d2 = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) d2 = fmaf(T[e], qb[e], d2);
-                    const float d = fmaf(d2, kHalfInvC4, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
+                    for (int e = 0; e < 8; ++e) d2 = fmaf(T[e], qa[e], d2);   // row of T[e] = 8 (e / 4) + 4 g + e % 4
+                    const float d = fmaf(d2, kHalfInvCQ, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
                     const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
                     if (g == 0) lds.den_inter[32 * qt + n] = tot;
                 } else if (w == 2 || qt == 1) {
@@ -542,7 +602,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         const bool more = tok0 + C < tok_end;
         if (more) load_raw(tok0 + C);
         {
-            const int brow = n & 15, ahalf = n >> 4;
+            // main tile: row n is the pair a = n % 16, b = (a + 2w + n / 16) % 16
+            const int arow = n & 15, brow = (arow + 2 * w + (n >> 4)) & 15;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -557,21 +618,19 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                         u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
                         vk[c2] = as_bf16x8(o);
                     }
-                    const f32x4 kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
-                    const f32x4 kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
-#pragma unroll
-                    for (int tt = 0; tt < 2; ++tt) {
-                        const int arow = 4 * w + 2 * tt + ahalf;
+                    {
                         const f32x4 ka0 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol]);
                         const f32x4 ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
+                        const f32x4 kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
+                        const f32x4 kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
                         float pr[8];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) { pr[i] = ka0[i] * kb0[i]; pr[4 + i] = ka1[i] * kb1[i]; }
                         const bf16x8 phik = pack8(pr);
 #pragma unroll
-                        for (int c2 = 0; c2 < 2; ++c2) S[tt][c2] = mfma(phik, vk[c2], S[tt][c2]);
+                        for (int c2 = 0; c2 < 2; ++c2) S[c2] = mfma(phik, vk[c2], S[c2]);
                     }
-                    // [k_0..k_15, 1, 0..]^T operand: the 1st/0th-order feature rows (wave 0), the moments (wave 1)
+                    // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand: the extra tile (wave 0), the moments (wave 1)
                     if (w < 2) {
                         role_guard();
                         const uint16_t *p = &st.ktb[n][tcol];
@@ -607,25 +666,29 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             }
         };
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) put(4 * w + 2 * tt + c2, S[tt][c2]);
-        if (w == 0) { put(16, X[0]); put(17, X[1]); }
-        if (w == 1) put(18, X[0]);
+        for (int c2 = 0; c2 < 2; ++c2) put(2 * w + c2, S[c2]);
+        if (w == 0) { put(8, X[0]); put(9, X[1]); }
+        if (w == 1) put(10, X[0]);
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
+            const CanonRows cm = canon_rows_main(w, fl);
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-                    Su[(size_t)canon_row_main(2 * w + tt, fl) * dv + col0 + 32 * c2 + n] = S[tt][c2][r];
+            for (int c2 = 0; c2 < 2; ++c2) {
+                const size_t col = (size_t)col0 + 32 * c2 + n;
+                Su[(size_t)cm.r1 * dv + col] = S[c2][r];
+                if (cm.r2 != cm.r1) Su[(size_t)cm.r2 * dv + col] = S[c2][r];
+            }
             if (w == 0) {
-                const int row = canon_row_extra(fl);
-                if (row >= 0) {
+                const CanonRows cx = canon_rows_extra(fl);
+                if (cx.r1 >= 0) {
 #pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) Su[(size_t)row * dv + col0 + 32 * c2 + n] = X[c2][r];
+                    for (int c2 = 0; c2 < 2; ++c2) {
+                        const size_t col = (size_t)col0 + 32 * c2 + n;
+                        Su[(size_t)cx.r1 * dv + col] = X[c2][r];
+                        if (cx.r2 != cx.r1) Su[(size_t)cx.r2 * dv + col] = X[c2][r];
+                    }
                 }
             } else if (w == 1 && slice == 0) {
                 const float m = X[0][r];
