@@ -315,24 +315,27 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     const int s_tok = tid & 63, s_q = tid >> 6, s_h = s_q & 1;
     u32x2 raw_x[2];        // the two 8-byte pieces of the K or Q row
     u32x4 raw_v[2];
-    // per-lane element offsets inside a chunk (32-bit, added to a uniform per-chunk base pointer)
-    const uint32_t xoff = (uint32_t)(s_tok * DP + 4 * s_h);
-    const uint32_t voff = (uint32_t)s_tok * (uint32_t)dv + (uint32_t)(16 * s_q);
+    // Loads are unconditional (rows past the end of the segment re-read its last row and are zeroed
+    // when staged): a conditional load would have the compiler pre-zero its destination registers,
+    // and before that write it waits for every memory operation still in flight, stores included.
     auto load_raw = [&](int tok0) {
-        const bool ok = tok0 + s_tok < tok_end;
-        const u32x2 zero2 = {0u, 0u};
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
-        const uint16_t *xc = (s_q < 2 ? ku : qu) + (size_t)tok0 * DP;
-        const uint16_t *vc = vu + (size_t)tok0 * dv;
+        const int tok = min(tok0 + s_tok, tok_end - 1);
+        const uint16_t *xc = (s_q < 2 ? ku : qu) + (size_t)tok * DP + 4 * s_h;
+        const uint16_t *vc = vu + (size_t)tok * dv + 16 * s_q;
         if (MODE == 0 || s_q < 2) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) raw_x[j] = ok ? *reinterpret_cast<const u32x2 *>(xc + xoff + 8 * j) : zero2;
+            for (int j = 0; j < 2; ++j) raw_x[j] = *reinterpret_cast<const u32x2 *>(xc + 8 * j);
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) raw_v[j] = ok ? *reinterpret_cast<const u32x4 *>(vc + voff + 8 * j) : zero4;
+        for (int j = 0; j < 2; ++j) raw_v[j] = *reinterpret_cast<const u32x4 *>(vc + 8 * j);
     };
     auto stage = [&](int tok0) {
         Stage &st = lds.st;
+        if (tok0 + s_tok >= tok_end) {
+            const u32x2 zero2 = {0u, 0u};
+            const u32x4 zero4 = {0u, 0u, 0u, 0u};
+            raw_x[0] = zero2; raw_x[1] = zero2; raw_v[0] = zero4; raw_v[1] = zero4;
+        }
         if (s_q < 2) {
             float kf[2][4];   // c_k * k: [j][i] = element 8 j + 4 h + i
 #pragma unroll
@@ -380,8 +383,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             }
     };
 
-    // Pipeline: the rows of chunk c+1 are fetched from global memory into registers before the
-    // update phase of chunk c and written to LDS after it, so their latency hides under the MFMAs.
+    // Pipeline: the rows of chunk c+1 are fetched from global memory into registers at the top of
+    // chunk c and written to LDS at its bottom, so their latency hides under the whole chunk.
     if (MODE != 2) {
         load_raw(tok_begin);
         stage(tok_begin);
@@ -389,6 +392,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C) {
         const Stage &st = lds.st;
         wg_sync();   // this chunk's staging is visible
+        const bool more = tok0 + C < tok_end;
+        if (more) load_raw(tok0 + C);   // a whole chunk ahead: consumed by stage() at the bottom
 
         if (MODE == 0) {
             // =============================== readout ============================================
@@ -587,20 +592,31 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 uint16_t *yc = yu + (size_t)tok0 * dv;
+                // A full chunk stores without a per-lane condition: stores that are certain to be
+                // issued can be counted, so the later wait for the prefetched rows (issued before
+                // them; the counter retires in order) does not have to wait for the stores as well.
+                u32x4 val[2];
+                uint32_t yoff[2];
 #pragma unroll
                 for (int it = 0; it < 2; ++it) {
                     const int row = 16 * it + (lane >> 2), c = lane & 3;
-                    const u32x4 val = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * c);
-                    const uint32_t yoff = (uint32_t)(32 * qt + row) * (uint32_t)dv + (uint32_t)(32 * c2 + 8 * c);
-                    if (tok0 + 32 * qt + row < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff) = val;
+                    val[it] = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * c);
+                    yoff[it] = (uint32_t)(32 * qt + row) * (uint32_t)dv + (uint32_t)(32 * c2 + 8 * c);
+                }
+                if (tok0 + C <= tok_end) {
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+                } else {
+#pragma unroll
+                    for (int it = 0; it < 2; ++it)
+                        if (tok0 + 32 * qt + 16 * it + (lane >> 2) < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 }
             }
         }
 
         // =================================== update =============================================
         // S += phi(K)^T V over this wave's feature rows; lane (g, n): feature row n of the tile
-        const bool more = tok0 + C < tok_end;
-        if (more) load_raw(tok0 + C);
         {
             // main tile: row n is the pair a = n % 16, b = (a + 2w + n / 16) % 16
             const int arow = n & 15, brow = (arow + 2 * w + (n >> 4)) & 15;

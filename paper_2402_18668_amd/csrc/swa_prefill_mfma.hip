@@ -122,15 +122,22 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
 
     u32x4 nk[NEWIT], nv[NEWIT];   // next step's new rows, in flight during this step
     u32x4 qop[SLABS], qnext[SLABS];
+    // Loads of the pipeline are unconditional (a row past the end of the sequence re-reads the last
+    // row; it is zeroed when staged, or belongs to a query that is never stored).  With a conditional
+    // load the compiler cannot tell how many memory operations are in flight, waits for all of them
+    // wherever it needs one, and the prefetch below would be waited for as soon as it is issued.
     auto load_q = [&](int step_q0, u32x4 (&dst)[SLABS]) {
-        const int query = step_q0 + 32 * wv + n;
+        const int query = min(step_q0 + 32 * wv + n, N - 1);
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) {
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            dst[s] = query < q_end ? *reinterpret_cast<const u32x4 *>(q + base + (size_t)query * DH + 16 * s + 8 * g) : zero;
-        }
+        for (int s = 0; s < SLABS; ++s)
+            dst[s] = *reinterpret_cast<const u32x4 *>(q + base + (size_t)query * DH + 16 * s + 8 * g);
     };
     load_q(q0, qop);
+    // The first queries have arrived before the pipeline starts (an asm statement that takes them as
+    // operands): otherwise every step would wait for "loads that may still be in flight from before
+    // the loop", which at that point means waiting for the prefetch it has just issued.
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qop[s]));
     __syncthreads();
 
     for (int sq0 = q0; sq0 < q_end; sq0 += BQ) {
@@ -139,10 +146,9 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
 #pragma unroll
             for (int it = 0; it < NEWIT; ++it) {
                 const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
-                const int key = sq0 + BQ + r;
-                const u32x4 zero = {0u, 0u, 0u, 0u};
-                nk[it] = key < N ? *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8) : zero;
-                nv[it] = key < N ? *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8) : zero;
+                const int key = min(sq0 + BQ + r, N - 1);
+                nk[it] = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
+                nv[it] = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
             }
             load_q(sq0 + BQ, qnext);
         }
@@ -150,7 +156,8 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
         const int qbase = sq0 + 32 * wv;          // first query of this wave's tile
         const int query = qbase + n;
         const bool q_ok = query < q_end;
-        if (qbase < q_end) {
+        {   // every wave computes (a tile past the end of the segment works on staged rows like any
+            // other and stores nothing): no wave-dependent branch around the stores below
             // row of key position p in the LDS ring
             const int rel0 = qbase - W - (q0 - W);   // ring position of the oldest key tile of this query tile
 
@@ -256,12 +263,25 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                                 __builtin_bit_cast(u32x2, hv);
                         }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's tile is complete in LDS
+                    u32x4 val[4];
+                    uint16_t *dst[4];
 #pragma unroll
                     for (int it = 0; it < 4; ++it) {
                         const int row = it * 8 + lane / 8, c = lane % 8;
-                        const u32x4 val = *reinterpret_cast<const u32x4 *>(yt + (size_t)row * Y_LD + c * 8);
-                        if (qbase + row < q_end)
-                            *reinterpret_cast<u32x4 *>(y + base + (size_t)(qbase + row) * DH + 64 * cp + c * 8) = val;
+                        val[it] = *reinterpret_cast<const u32x4 *>(yt + (size_t)row * Y_LD + c * 8);
+                        dst[it] = y + base + (size_t)(qbase + row) * DH + 64 * cp + c * 8;
+                    }
+                    // A full step stores without a per-lane condition, so that the stores can be
+                    // counted and the wait for the prefetched rows (older, retired in order) is not
+                    // also a wait for these stores.
+                    if (sq0 + BQ <= q_end) {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it) *reinterpret_cast<u32x4 *>(dst[it]) = val[it];
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            if (qbase + it * 8 + lane / 8 < q_end) *reinterpret_cast<u32x4 *>(dst[it]) = val[it];
+                        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
                     }
                 }
             }
@@ -275,6 +295,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                 const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
                 const int key = sq0 + BQ + r;
                 const int slot = (rel_new + r) % NK;
+                if (key >= N) {
+                    const u32x4 zero = {0u, 0u, 0u, 0u};
+                    nk[it] = zero; nv[it] = zero;
+                }
                 *reinterpret_cast<u32x4 *>(Vs + (size_t)slot * V_LD + c * 8) = nv[it];
                 *reinterpret_cast<u32x4 *>(Ks + (size_t)slot * K_LD + c * 8) = nk[it];
                 if (ring_u && key < N && key >= N - W && key < q_end) {
