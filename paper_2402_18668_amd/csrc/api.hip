@@ -123,7 +123,9 @@ int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void
     if (ring && !aligned16(ring)) return BASED_ERR_INVALID_ARG;
     const int U = B * H;
     hipError_t e;
-    if (swa_prefill_mfma_supported(d_h, w, dtype)) {
+    // the matrix-core kernel takes the row maximum of the unscaled scores, which is the maximum of
+    // the scaled ones only for a positive scale; anything else goes to the vector-ALU kernel
+    if (swa_prefill_mfma_supported(d_h, w, dtype) && scale > 0.f) {
         // this kernel also fills the ring
         e = launch_swa_prefill_mfma(q, k, v, y, ring, U, N, d_h, w, scale, (hipStream_t)stream);
     } else {

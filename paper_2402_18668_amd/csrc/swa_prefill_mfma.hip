@@ -28,6 +28,8 @@
 // workgroup that owns the last segment.
 #include "common.h"
 
+#include <type_traits>
+
 namespace based {
 
 namespace {
@@ -97,28 +99,36 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     // A step handles BQ queries; going to the next step overwrites the BQ oldest rows with the BQ
     // new keys, every K / V row of the segment is staged exactly once (plus the W-row halo at the
     // segment start), and the next step's rows are fetched into registers while this step computes.
-    auto stage_rows = [&](int first_key, int first_slot_row, int rows) {   // used for the initial fill
-        for (int idx = tid; idx < rows * CPR; idx += NT) {
-            const int r = idx / CPR, c = idx % CPR;
-            const int key = first_key + r;
-            u32x4 vv = {0u, 0u, 0u, 0u}, kv = {0u, 0u, 0u, 0u};
-            if (key >= 0 && key < N) {
-                vv = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
-                kv = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
-                // the w-slot ring receives the last min(N, w) rows (slot = position mod w), written
-                // by the segment that owns the row as a query row
-                if (ring_u && key >= q0 && key >= N - W) {
-                    uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
-                    *reinterpret_cast<u32x4 *>(rk) = kv;
-                    *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = vv;
-                }
-            }
-            const int slot = (first_slot_row + r) % NK;
-            *reinterpret_cast<u32x4 *>(Vs + (size_t)slot * V_LD + c * 8) = vv;
-            *reinterpret_cast<u32x4 *>(Ks + (size_t)slot * K_LD + c * 8) = kv;
+    {   // initial fill: keys q0 - W .. q0 + BQ - 1 into ring rows 0 .. NK - 1, every load in flight at once
+        constexpr int FILLIT = NK * CPR / NT;
+        static_assert(NK * CPR % NT == 0, "the initial fill is a whole number of passes");
+        u32x4 fk[FILLIT], fv[FILLIT];
+#pragma unroll
+        for (int it = 0; it < FILLIT; ++it) {
+            const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+            const int key = min(max(q0 - W + r, 0), N - 1);
+            fk[it] = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
+            fv[it] = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
         }
-    };
-    stage_rows(q0 - W, 0, NK);
+#pragma unroll
+        for (int it = 0; it < FILLIT; ++it) {
+            const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+            const int key = q0 - W + r;
+            if (key < 0 || key >= N) {
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                fk[it] = zero; fv[it] = zero;
+            }
+            *reinterpret_cast<u32x4 *>(Vs + (size_t)r * V_LD + c * 8) = fv[it];
+            *reinterpret_cast<u32x4 *>(Ks + (size_t)r * K_LD + c * 8) = fk[it];
+            // the w-slot ring receives the last min(N, w) rows (slot = position mod w), written
+            // by the segment that owns the row as a query row
+            if (ring_u && key >= q0 && key < N && key >= N - W) {
+                uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
+                *reinterpret_cast<u32x4 *>(rk) = fk[it];
+                *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = fv[it];
+            }
+        }
+    }
 
     u32x4 nk[NEWIT], nv[NEWIT];   // next step's new rows, in flight during this step
     u32x4 qop[SLABS], qnext[SLABS];
@@ -177,29 +187,39 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             }
 
             // ---- mask, softmax statistics (lane = query; its keys sit in registers and in lane ^ 32) --
+            // Raw scores are masked and their maximum taken; the scale (times log2 e) is applied inside
+            // the exponential, exp2(scale * (x - m)), which is one fused multiply-add per element.
+            // Only the first and the last key tile of a query tile cut the window; keys before the
+            // start of the sequence exist only for the first w queries (a uniform branch).
             float m = -INFINITY;
+            auto mask_and_max = [&](auto head_c) {
+                constexpr bool HEAD = decltype(head_c)::value;
 #pragma unroll
-            for (int t = 0; t < NKT; ++t)
+                for (int t = 0; t < NKT; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int local = 8 * (r >> 2) + 4 * g + (r & 3);
-                    const int key = qbase - W + 32 * t + local;
-                    bool ok = key >= 0;
-                    if (t == 0) ok = ok && local > n;          // key > query - w
-                    if (t == NKT - 1) ok = ok && local <= n;   // key <= query
-                    const float x = ok ? P[t][r] * scale_log2e : -INFINITY;
-                    P[t][r] = x;
-                    m = fmaxf(m, x);
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int local = 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (HEAD || t == 0 || t == NKT - 1) {
+                            bool ok = true;
+                            if (HEAD) ok = qbase - W + 32 * t + local >= 0;
+                            if (t == 0) ok = ok && local > n;          // key > query - w
+                            if (t == NKT - 1) ok = ok && local <= n;   // key <= query
+                            P[t][r] = ok ? P[t][r] : -INFINITY;
+                        }
+                        m = fmaxf(m, P[t][r]);
+                    }
+            };
+            if (qbase < W) mask_and_max(std::true_type{});
+            else mask_and_max(std::false_type{});
             m = fmaxf(m, __shfl_xor(m, 32, 64));
             // the query's own key is always visible, so m is finite for every query inside the sequence
-            const float mm = q_ok ? m : 0.f;
+            const float neg_ms = q_ok ? -m * scale_log2e : 0.f;
             float sum = 0.f;
 #pragma unroll
             for (int t = 0; t < NKT; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pe = __builtin_amdgcn_exp2f(P[t][r] - mm);   // exp2(-inf) = 0 for masked keys
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(P[t][r], scale_log2e, neg_ms));   // exp2(-inf) = 0: masked keys
                     P[t][r] = pe;
                     sum += pe;
                 }
