@@ -26,7 +26,13 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
     constexpr int RPS = NT / LPR;    // rows per sweep step
     constexpr int STEPS = (D + RPS - 1) / RPS;
     constexpr int DPAD = STEPS * RPS;
-    constexpr int UNR = 8;           // state rows in flight per lane
+    // State rows in flight per lane.  A narrow state (d_v = 64: 18 rows per lane) is fetched in one
+    // round, so that a small batch, which cannot hide latency behind other workgroups, pays one trip
+    // to memory; a wide one goes in rounds of 8 rows, each round fetched while the one before it is
+    // worked on.
+    constexpr int UNR = STEPS <= 20 ? STEPS : 8;
+    constexpr int ROUNDS = (STEPS + UNR - 1) / UNR;
+    constexpr int ZPT = (D + NT - 1) / NT;   // K-state features per thread
 
     __shared__ float pk[DPAD], pq[DPAD];
     __shared__ float qs[DP], ks[DP];
@@ -47,6 +53,21 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
         const T *vp = v + (size_t)u * DV + col4;
         v4 = make_float4(to_f32(vp[0]), to_f32(vp[1]), to_f32(vp[2]), to_f32(vp[3]));
     }
+    // The state does not depend on the token: its first round and the K-state are requested now and
+    // arrive while the features are expanded.  Rows past D re-read row D - 1 and are not used.
+    float4 *Srow = reinterpret_cast<float4 *>(Su + col4);
+    auto load_round = [&](int st0, float4 (&dst)[UNR]) {
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int f = min((st0 + j) * RPS + row, D - 1);
+            dst[j] = Srow[(size_t)f * (DV / 4)];
+        }
+    };
+    float4 sv[UNR];
+    load_round(0, sv);
+    float zv[ZPT];
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) zv[i] = zu[min(tid + i * NT, D - 1)];
     __syncthreads();
     // feature expansion (Eq. 4) in LDS; rows past D are zero so the tail of the sweep is inert
     for (int f = tid; f < DPAD; f += NT) {
@@ -63,33 +84,54 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
 
     // K-state: each feature handled by one thread
     float dpart = 0.f;
-    for (int f = tid; f < D; f += NT) {
-        const float zn = zu[f] + pk[f];
-        zu[f] = zn;
-        dpart = fmaf(pq[f], zn, dpart);
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+        const int f = tid + i * NT;
+        if (f < D) {
+            const float zn = zv[i] + pk[f];
+            zu[f] = zn;
+            dpart = fmaf(pq[f], zn, dpart);
+        }
     }
 
     // one read-modify-write sweep over the KV-state, readout fused in
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 *Srow = reinterpret_cast<float4 *>(Su + col4);
-#pragma unroll 1
-    for (int st0 = 0; st0 < STEPS; st0 += UNR) {
-        float4 sv[UNR];
+    // A round whose rows all exist stores without a per-lane condition: stores that are certain to
+    // be issued can be counted, so waiting for the next round's rows (requested before them) is not
+    // also a wait for these stores to complete.
+    auto work_round = [&](int st0, float4 (&cur)[UNR]) {
+        const bool full = (st0 + UNR) * RPS <= D;
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
-            const int f = (st0 + j) * RPS + row;
-            if (st0 + j < STEPS && f < D) sv[j] = Srow[(size_t)f * (DV / 4)];
+            const int f = min((st0 + j) * RPS + row, DPAD - 1);   // features D .. DPAD - 1 are zero
+            const float a = pk[f], b = pq[f];
+            cur[j].x = fmaf(a, v4.x, cur[j].x); cur[j].y = fmaf(a, v4.y, cur[j].y);
+            cur[j].z = fmaf(a, v4.z, cur[j].z); cur[j].w = fmaf(a, v4.w, cur[j].w);
+            acc.x = fmaf(b, cur[j].x, acc.x); acc.y = fmaf(b, cur[j].y, acc.y);
+            acc.z = fmaf(b, cur[j].z, acc.z); acc.w = fmaf(b, cur[j].w, acc.w);
         }
+        if (full) {
 #pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            const int f = (st0 + j) * RPS + row;
-            if (st0 + j < STEPS && f < D) {
-                const float a = pk[f], b = pq[f];
-                sv[j].x = fmaf(a, v4.x, sv[j].x); sv[j].y = fmaf(a, v4.y, sv[j].y);
-                sv[j].z = fmaf(a, v4.z, sv[j].z); sv[j].w = fmaf(a, v4.w, sv[j].w);
-                Srow[(size_t)f * (DV / 4)] = sv[j];
-                acc.x = fmaf(b, sv[j].x, acc.x); acc.y = fmaf(b, sv[j].y, acc.y);
-                acc.z = fmaf(b, sv[j].z, acc.z); acc.w = fmaf(b, sv[j].w, acc.w);
+            for (int j = 0; j < UNR; ++j) Srow[(size_t)((st0 + j) * RPS + row) * (DV / 4)] = cur[j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int f = (st0 + j) * RPS + row;
+                if (st0 + j < STEPS && f < D) Srow[(size_t)f * (DV / 4)] = cur[j];
+            }
+        }
+    };
+    if (ROUNDS == 1) {
+        work_round(0, sv);
+    } else {
+        float4 sn[UNR];
+#pragma unroll 1
+        for (int r = 0; r < ROUNDS; r += 2) {
+            if (r + 1 < ROUNDS) load_round((r + 1) * UNR, sn);
+            work_round(r * UNR, sv);
+            if (r + 1 < ROUNDS) {
+                if (r + 2 < ROUNDS) load_round((r + 2) * UNR, sv);
+                work_round((r + 1) * UNR, sn);
             }
         }
     }
