@@ -201,24 +201,27 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
     T *Kr = ring + (size_t)u * 2 * W * DH;
     T *Vr = Kr + (size_t)W * DH;
 
-    Ch qc, kc[PASSES], vc[PASSES];
-    qc.raw = *reinterpret_cast<const decltype(qc.raw) *>(q + (size_t)u * DH + chunk * CE);
-    // all loads are independent of the scores: issue them up front
+    // Every load is unconditional and issued up front (none depends on the scores): the token's own
+    // q, k, v chunks, then the ring rows.  Rows the window does not hold yet re-read row 0 and are
+    // zeroed, the row of this token's slot is replaced by the new k, v once the data is here.  (A
+    // conditional load of the new row inside the sweep would wait for every ring row requested before it.)
+    using Raw = decltype(Ch::raw);
+    Ch qc, kc[PASSES], vc[PASSES], knew, vnew;
+    qc.raw = *reinterpret_cast<const Raw *>(q + (size_t)u * DH + chunk * CE);
+    knew.raw = *reinterpret_cast<const Raw *>(k + (size_t)u * DH + chunk * CE);
+    vnew.raw = *reinterpret_cast<const Raw *>(v + (size_t)u * DH + chunk * CE);
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int j = p * RPP + rg;
-        if (j == slot) {
-            kc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(k + (size_t)u * DH + chunk * CE);
-            vc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(v + (size_t)u * DH + chunk * CE);
-            *reinterpret_cast<decltype(qc.raw) *>(Kr + (size_t)j * DH + chunk * CE) = kc[p].raw;
-            *reinterpret_cast<decltype(qc.raw) *>(Vr + (size_t)j * DH + chunk * CE) = vc[p].raw;
-        } else if (j < valid) {
-            kc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(Kr + (size_t)j * DH + chunk * CE);
-            vc[p].raw = *reinterpret_cast<const decltype(qc.raw) *>(Vr + (size_t)j * DH + chunk * CE);
-        } else {
-            kc[p].raw = decltype(qc.raw){};
-            vc[p].raw = decltype(qc.raw){};
-        }
+        const int jr = j < valid ? j : 0;
+        kc[p].raw = *reinterpret_cast<const Raw *>(Kr + (size_t)jr * DH + chunk * CE);
+        vc[p].raw = *reinterpret_cast<const Raw *>(Vr + (size_t)jr * DH + chunk * CE);
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int j = p * RPP + rg;
+        if (j == slot) { kc[p].raw = knew.raw; vc[p].raw = vnew.raw; }
+        else if (j >= valid) { kc[p].raw = Raw{}; vc[p].raw = Raw{}; }
     }
     // scores
 #pragma unroll
@@ -259,6 +262,11 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
         for (int r = 0; r < RPP; ++r) num += part[r][tid];
         y[(size_t)u * DH + tid] = from_f32<T>(num / sum);
     }
+    // cache update: the new row goes into its slot (the threads of that row group hold it)
+    if (rg == slot % RPP) {
+        *reinterpret_cast<Raw *>(Kr + (size_t)slot * DH + chunk * CE) = knew.raw;
+        *reinterpret_cast<Raw *>(Vr + (size_t)slot * DH + chunk * CE) = vnew.raw;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -280,7 +288,7 @@ __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, 
 }
 
 // Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
-// the window attention step.
+// the window attention step.  (Interleaving the two kinds block by block measured 15 % slower.)
 template <int DP, int DV, int DH, int W, typename T>
 __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
     const T *q, const T *k, const T *v, T *y_lin, float *state, const T *sq, const T *sk,
