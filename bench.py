@@ -38,10 +38,12 @@ MEASURED_PREFILL_TRAFFIC_BYTES = 214576087     # based_prefill, both launches (p
 MEASURED_DECODE_TRAFFIC_BYTES = 578799519      # decode_step_kernel (decode_1p3b)
 
 
-def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64) -> int:
-    """Credited work: readout + update against the D x d_v state, the K-state, the causal half of the
-    intra-chunk block."""
-    D = 1 + dp + dp * dp
+def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
+    """Credited work: readout + update against the state, the K-state, the causal half of the
+    intra-chunk block.  The bf16 d' = 16 kernel carries one state row per unordered feature pair
+    (D_sym = 1 + d' + d'(d'+1)/2 rows instead of D = 1 + d' + d'^2), so it is credited with D_sym;
+    ``packed=False`` gives the figure of the full D-row formulation for comparison."""
+    D = 1 + dp + (dp * (dp + 1) // 2 if packed else dp * dp)
     return 4 * D * dv + 4 * D + (C + 1) * (dp + dv + 1)
 
 
@@ -140,12 +142,16 @@ def main() -> int:
 
     prefill_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev_a, ev_b)]))
     flops = lin_prefill_flops_per_token_head(dp, dv) * U * N
+    flops_full_d = lin_prefill_flops_per_token_head(dp, dv, packed=False) * U * N
     achieved = flops / (prefill_ms * 1e-3) / 1e12
     roofline = {
         "kernel": "based_prefill (state-increment launch + main chunked launch)",
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_PREFILL_TRAFFIC_BYTES,
         "avg_ms": round(prefill_ms, 4), "flops_per_launch": flops,
+        # the same duration priced with the 273-row (unpacked) formulation's flop count
+        "flops_per_launch_unpacked_state": flops_full_d,
+        "achieved_unpacked_state_tflops": round(flops_full_d / (prefill_ms * 1e-3) / 1e12, 2),
         "algorithmic_bytes_per_launch": (2 * dp + 2 * dv) * 2 * U * N,
     }
 

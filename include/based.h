@@ -89,6 +89,11 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
  *   y      [B][H][N][d_v]      out, dtype
  *   state  state buffer (layout above) or NULL.  has_init != 0: read as (S0, z0) (must be
  *          non-NULL).  If non-NULL it receives the state after the last token.
+ *          A state of this recurrence has equal rows for the feature pairs (a, b) and (b, a)
+ *          (x_a x_b = x_b x_a in Eq. 4), and y depends only on their sum.  The bf16 d' = 16
+ *          path carries one row per unordered pair: it reads an initial state as the mean of
+ *          the two rows and writes both rows equal.  For a state produced by this library, or
+ *          imported from the canonical arrays of such a state, that changes nothing.
  *   workspace  scratch of at least based_prefill_workspace_bytes(...) bytes, 256-byte aligned;
  *          may be NULL when that size is 0.  Contents on return are unspecified.
  *

@@ -149,38 +149,6 @@ __device__ __forceinline__ size_t ws_slot_off(int slot, int j, int lane)
     return (((size_t)slot * 4 + j) * 64 + lane) * 4;
 }
 
-// Loads four workspace slots (16 x 16 bytes per lane) with all loads in flight at once and the
-// wait inside the same statement, so that every output register is valid as far as the compiler
-// can tell.  (Separate load statements whose results the compiler believes complete would let
-// it reuse those registers before the data has arrived.)
-__device__ __forceinline__ void load_slots(const float *p0, const float *p1, const float *p2,
-                                           const float *p3, f32x4 (&t)[16])
-{
-    asm volatile(
-        "global_load_dwordx4 %0, %16, off offset:0\n\t"
-        "global_load_dwordx4 %1, %16, off offset:1024\n\t"
-        "global_load_dwordx4 %2, %16, off offset:2048\n\t"
-        "global_load_dwordx4 %3, %16, off offset:3072\n\t"
-        "global_load_dwordx4 %4, %17, off offset:0\n\t"
-        "global_load_dwordx4 %5, %17, off offset:1024\n\t"
-        "global_load_dwordx4 %6, %17, off offset:2048\n\t"
-        "global_load_dwordx4 %7, %17, off offset:3072\n\t"
-        "global_load_dwordx4 %8, %18, off offset:0\n\t"
-        "global_load_dwordx4 %9, %18, off offset:1024\n\t"
-        "global_load_dwordx4 %10, %18, off offset:2048\n\t"
-        "global_load_dwordx4 %11, %18, off offset:3072\n\t"
-        "global_load_dwordx4 %12, %19, off offset:0\n\t"
-        "global_load_dwordx4 %13, %19, off offset:1024\n\t"
-        "global_load_dwordx4 %14, %19, off offset:2048\n\t"
-        "global_load_dwordx4 %15, %19, off offset:3072\n\t"
-        "s_waitcnt vmcnt(0)"
-        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]),
-          "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]),
-          "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15])
-        : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
-        : "memory");
-}
-
 // Canonical state rows (Eq. 4 order: row 0 constant, 1 + a linear, 1 + d' + a d' + b the pair
 // (a, b)) of a packed row.  A pair row has two canonical rows (equal for delta = 0).
 struct CanonRows { int r1, r2; };   // r1 < 0: the packed row is padding
@@ -203,6 +171,10 @@ __device__ __forceinline__ CanonRows canon_rows_extra(int fl)
     return {-1, -1};
 }
 
+constexpr int kMaxSegments = 8;
+// first token of each segment (multiples of the chunk length), and the end of the last one
+struct SegTable { int begin[kMaxSegments + 1]; };
+
 }  // namespace
 
 // MODE 0: full prefill of the segment (readout + update); starts from the sum of workspace entries.
@@ -214,7 +186,7 @@ template <int MODE>
 __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws, int N,
-    int dv, int seg_len, int G)
+    int dv, SegTable segs, int G)
 {
     __shared__ __align__(16) Lds lds;
 
@@ -231,8 +203,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     const int u = bid / slices;
     const int col0 = slice * DVS;
 
-    const int tok_begin = seg * seg_len;
-    const int tok_end = min(N, tok_begin + seg_len);
+    const int tok_begin = segs.begin[seg];
+    const int tok_end = min(N, segs.begin[seg + 1]);
 
     const uint16_t *qu = q + (size_t)u * N * DP;
     const uint16_t *ku = k + (size_t)u * N * DP;
@@ -250,15 +222,24 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     zero16(X[0]); zero16(X[1]);
 
     if (MODE == 0) {
-        // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
-        for (int p = has_init ? 0 : 1; p <= seg; ++p) {
-            const float *e = ws_unit + (size_t)p * kWsEntryFloats;
-            // slots 2w, 2w+1, and for waves 0 / 1 their extra tiles (other waves re-read a main slot)
-            const int x0 = w == 0 ? 8 : (w == 1 ? 10 : 2 * w);
-            const int x1 = w == 0 ? 9 : 2 * w;
-            f32x4 t[16];
-            load_slots(e + ws_slot_off(2 * w + 0, 0, lane), e + ws_slot_off(2 * w + 1, 0, lane),
-                       e + ws_slot_off(x0, 0, lane), e + ws_slot_off(x1, 0, lane), t);
+        // start of segment: initial state (entry 0, if any) plus the increments of earlier segments.
+        // Slots 2w, 2w+1, and for waves 0 / 1 their extra tiles (other waves re-read a main slot).
+        // The loads of entry p + 1 are issued before entry p is added up (they are unconditional:
+        // past the last entry the last one is fetched again and dropped), so the entries stream in
+        // back to back instead of costing one trip to memory each.
+        const int x0 = w == 0 ? 8 : (w == 1 ? 10 : 2 * w);
+        const int x1 = w == 0 ? 9 : 2 * w;
+        const size_t so[4] = {ws_slot_off(2 * w + 0, 0, lane), ws_slot_off(2 * w + 1, 0, lane),
+                              ws_slot_off(x0, 0, lane), ws_slot_off(x1, 0, lane)};
+        auto fetch = [&](int p, f32x4 (&t)[16]) {
+            const float *e = ws_unit + (size_t)min(p, seg) * kWsEntryFloats;
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    t[sl * 4 + j] = *reinterpret_cast<const f32x4 *>(e + so[sl] + (size_t)j * 256);
+        };
+        auto add_in = [&](const f32x4 (&t)[16]) {
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
@@ -271,6 +252,17 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             } else if (w == 1) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) X[0][r] += t[2 * 4 + (r >> 2)][r & 3];
+            }
+        };
+        const int p0 = has_init ? 0 : 1;
+        if (p0 <= seg) {
+            f32x4 ta[16], tb[16];
+            fetch(p0, ta);
+            for (int p = p0; p <= seg; p += 2) {
+                fetch(p + 1, tb);
+                add_in(ta);
+                fetch(p + 2, ta);
+                if (p + 1 <= seg) add_in(tb);
             }
         }
     }
@@ -733,10 +725,32 @@ int pick_segments(int U, int N, int dv)
     return G;
 }
 
-int segment_len(int N, int G)
+// Segment boundaries.  The main launch starts segment g by summing g workspace entries (about 0.6
+// of a chunk's time each) and the last segment also writes the final state, so later segments
+// get fewer chunks: all workgroups of the main launch, which run side by side, end together.
+// Returns the number of segments actually used (a short sequence may leave trailing ones empty).
+int make_segments(int N, int G, SegTable &t)
 {
-    const int per = (N + G - 1) / G;
-    return (per + C - 1) / C * C;
+    const int T = (N + C - 1) / C;   // chunks
+    if (G > T) G = T;
+    int len[kMaxSegments];
+    int sum = 0;
+    for (int g = 0; g < G; ++g) {
+        float off = 0.6f * (0.5f * (G - 1) - g);
+        if (g == G - 1 && G > 1) off -= 0.5f;
+        len[g] = T / G + (int)(off >= 0.f ? off + 0.5f : off - 0.5f);
+        if (len[g] < 1) len[g] = 1;
+        sum += len[g];
+    }
+    // hand the rounding remainder to (or take it from) the early segments, one chunk at a time
+    for (int g = 0; sum != T; g = (g + 1) % G) {
+        if (sum < T) { ++len[g]; ++sum; }
+        else if (len[g] > 1) { --len[g]; --sum; }
+    }
+    int pos = 0;
+    for (int g = 0; g < G; ++g) { t.begin[g] = pos * C; pos += len[g]; }
+    for (int g = G; g <= kMaxSegments; ++g) t.begin[g] = pos * C;
+    return G;
 }
 
 }  // namespace
@@ -759,26 +773,24 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
 {
     (void)dp;
     const int slices = dv / DVS;
-    int G = pick_segments(U, N, dv);
-    const int seg_len = segment_len(N, G);
-    // rounding the segment length up to whole chunks can leave trailing segments empty; a smaller
-    // G only uses a prefix of the workspace that was sized for pick_segments()
-    while (G > 1 && (G - 1) * seg_len >= N) --G;
+    SegTable segs;
+    // a smaller G only uses a prefix of the workspace that was sized for pick_segments()
+    const int G = make_segments(N, pick_segments(U, N, dv), segs);
     const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)k, *v16 = (const uint16_t *)v;
     hipError_t e;
     if (has_init) {
         hipLaunchKernelGGL((prefill_mfma_kernel<2>), dim3((unsigned)(U * slices)), dim3(NT), 0, s, q16, k16,
-                           v16, (uint16_t *)y, state, 1, (float *)workspace, N, dv, seg_len, G);
+                           v16, (uint16_t *)y, state, 1, (float *)workspace, N, dv, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {
         hipLaunchKernelGGL((prefill_mfma_kernel<1>), dim3((unsigned)(U * slices * (G - 1))), dim3(NT), 0, s,
                            q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv,
-                           seg_len, G);
+                           segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     hipLaunchKernelGGL((prefill_mfma_kernel<0>), dim3((unsigned)(U * slices * G)), dim3(NT), 0, s, q16, k16,
-                       v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv, seg_len, G);
+                       v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv, segs, G);
     return hipGetLastError();
 }
 

@@ -106,6 +106,38 @@ def test_prefill_split_with_state(based, dtype, dp, dv, N, N1):
     check_close(down(z2).reshape(zw.shape), zw, TOL[dtype], "split prefill final z")
 
 
+@pytest.mark.parametrize("dtype,dp,dv", [("bf16", 16, 64), ("bf16", 16, 128), ("f32", 16, 64)])
+def test_prefill_initial_state_symmetric_part(based, dtype, dp, dv):
+    """y depends only on the sum of the state rows (a, b) and (b, a): an antisymmetric
+    perturbation of the initial state leaves y (and the symmetric part of the final state) unchanged."""
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, N, N1 = 1, 2, 700, 90
+    q, k, v = lin_case(wl, B, H, N)
+    want = oracle.linattn_quadratic(q, k, v)
+    Sw, zw = oracle.linattn_state(k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    run_prefill(based, wl, B, H, N1, q[:, :N1], k[:, :N1], v[:, :N1], state=state)
+    S, z = based.state_export(state, B, H, dp, dv)
+    D = 1 + dp + dp * dp
+    S2 = S.clone().reshape(B, H, D, dv)
+    pert = torch.linspace(0.5, 2.0, dv, device=S2.device)
+    for a in range(dp):
+        for b in range(a + 1, dp):
+            S2[:, :, 1 + dp + a * dp + b] += pert
+            S2[:, :, 1 + dp + b * dp + a] -= pert
+    state2 = based.alloc_state(B, H, dp, dv)
+    based.state_import(state2, S2.reshape(S.shape), z, dp)
+    y2 = run_prefill(based, wl, B, H, N - N1, q[:, N1:], k[:, N1:], v[:, N1:], state=state2, has_init=True)
+    check_close(rows(y2), rows(want[:, N1:]), TOL[dtype], "y after an antisymmetric perturbation of S0")
+    Sf, zf = based.state_export(state2, B, H, dp, dv)
+    Sf = down(Sf).reshape(B * H, D, dv)
+    pair = Sf[:, 1 + dp:].reshape(B * H, dp, dp, dv)
+    Sf_sym = Sf.copy()
+    Sf_sym[:, 1 + dp:] = (0.5 * (pair + pair.transpose(0, 2, 1, 3))).reshape(B * H, dp * dp, dv)
+    check_close(Sf_sym.reshape(Sw.shape), Sw, TOL[dtype], "symmetric part of the final S")
+    check_close(down(zf).reshape(zw.shape), zw, TOL[dtype], "final z")
+
+
 def test_prefill_deterministic(based):
     wl = synth.WORKLOADS["prefill_360m"]
     B, H, N = 2, 4, 512
