@@ -19,8 +19,9 @@
 // Work split.  One workgroup of four waves per (unit, 64-column slice of d_v, sequence segment).
 // Wave w owns the 32 rows delta in {2w, 2w+1} (its "main tile"), whose 32x32 fp32 state tiles
 // stay in its registers for the whole segment.  The remaining work is spread over the waves:
-// wave 0 owns the "extra tile" [x_0..x_15, 1, 0 x 7, the 8 rows of delta = 8]; wave 1 the moments
-// that give the denominator; waves 2 and 3 the intra-chunk block.  Per chunk each wave produces a
+// the "extra tile" [x_0..x_15, 1, 0 x 7, the 8 rows of delta = 8] is split by column tile between
+// waves 0 and 1; wave 2 owns the moments that give the denominator; the three blocks of the
+// intra-chunk product go to waves 0, 1 (the two cut by the diagonal) and 3.  Per chunk each wave produces a
 // partial Y^T over its feature rows; the partials are exchanged through LDS and wave w finishes
 // the 32x32 output tile (query tile w / 2, column tile w % 2).  Two workgroups (eight waves)
 // share a CU, so one wave's vector-ALU work (feature products, conversions) overlaps another's
@@ -139,7 +140,7 @@ __device__ __forceinline__ void wg_sync()
 // but the compiler lowers it to lane masking and may drop the jump over a short masked block, in
 // which case the other waves would execute the MFMAs inside it.  An inline-asm statement in the
 // block makes the compiler keep the jump (it never runs inline asm with an empty EXEC mask).
-__device__ __forceinline__ void role_guard() { asm volatile("; wave-role block: keep the execz branch" ::: "memory"); }
+__device__ __forceinline__ void role_guard() { asm volatile("; wave-role block: keep the execz branch"); }
 
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -216,47 +217,41 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[2];           // main tile [c2]
-    f32x16 X[2];           // wave 0: extra tile [c2]; wave 1: X[0] = moment tile
-                           // M' = [k, 1]^T [k, 1]; unused by waves 2, 3
+    f32x16 X;              // waves 0, 1: column tile w of the extra tile; wave 2: the moment tile
+                           // M' = [k, 1]^T [k, 1]; unused by wave 3
     zero16(S[0]); zero16(S[1]);
-    zero16(X[0]); zero16(X[1]);
+    zero16(X);
 
     if (MODE == 0) {
         // start of segment: initial state (entry 0, if any) plus the increments of earlier segments.
-        // Slots 2w, 2w+1, and for waves 0 / 1 their extra tiles (other waves re-read a main slot).
+        // Slots 2w, 2w+1, and for waves 0 .. 2 their extra tile (wave 3 re-reads a main slot).
         // The loads of entry p + 1 are issued before entry p is added up (they are unconditional:
         // past the last entry the last one is fetched again and dropped), so the entries stream in
         // back to back instead of costing one trip to memory each.
-        const int x0 = w == 0 ? 8 : (w == 1 ? 10 : 2 * w);
-        const int x1 = w == 0 ? 9 : 2 * w;
-        const size_t so[4] = {ws_slot_off(2 * w + 0, 0, lane), ws_slot_off(2 * w + 1, 0, lane),
-                              ws_slot_off(x0, 0, lane), ws_slot_off(x1, 0, lane)};
-        auto fetch = [&](int p, f32x4 (&t)[16]) {
+        const int x0 = w < 3 ? 8 + w : 2 * w;
+        const size_t so[3] = {ws_slot_off(2 * w + 0, 0, lane), ws_slot_off(2 * w + 1, 0, lane),
+                              ws_slot_off(x0, 0, lane)};
+        auto fetch = [&](int p, f32x4 (&t)[12]) {
             const float *e = ws_unit + (size_t)min(p, seg) * kWsEntryFloats;
 #pragma unroll
-            for (int sl = 0; sl < 4; ++sl)
+            for (int sl = 0; sl < 3; ++sl)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     t[sl * 4 + j] = *reinterpret_cast<const f32x4 *>(e + so[sl] + (size_t)j * 256);
         };
-        auto add_in = [&](const f32x4 (&t)[16]) {
+        auto add_in = [&](const f32x4 (&t)[12]) {
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) S[c2][r] += t[c2 * 4 + (r >> 2)][r & 3];
-            if (w == 0) {
+            if (w < 3) {
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) X[c2][r] += t[(2 + c2) * 4 + (r >> 2)][r & 3];
-            } else if (w == 1) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) X[0][r] += t[2 * 4 + (r >> 2)][r & 3];
+                for (int r = 0; r < 16; ++r) X[r] += t[2 * 4 + (r >> 2)][r & 3];
             }
         };
         const int p0 = has_init ? 0 : 1;
         if (p0 <= seg) {
-            f32x4 ta[16], tb[16];
+            f32x4 ta[12], tb[12];
             fetch(p0, ta);
             for (int p = p0; p <= seg; p += 2) {
                 fetch(p + 1, tb);
@@ -276,22 +271,19 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 const size_t col = (size_t)col0 + 32 * c2 + n;
                 S[c2][r] = 0.5f * (Su[(size_t)cm.r1 * dv + col] + Su[(size_t)cm.r2 * dv + col]);
             }
-            if (w == 0) {
+            if (w < 2) {
                 const CanonRows cx = canon_rows_extra(fl);
                 if (cx.r1 >= 0) {
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) {
-                        const size_t col = (size_t)col0 + 32 * c2 + n;
-                        X[c2][r] = 0.5f * (Su[(size_t)cx.r1 * dv + col] + Su[(size_t)cx.r2 * dv + col]);
-                    }
+                    const size_t col = (size_t)col0 + 32 * w + n;
+                    X[r] = 0.5f * (Su[(size_t)cx.r1 * dv + col] + Su[(size_t)cx.r2 * dv + col]);
                 }
-            } else if (w == 1) {
+            } else if (w == 2) {
                 float m = 0.f;   // M'[fl][n]
                 if (fl < DP && n < DP) m = zu[1 + DP + fl * DP + n] * 1.41421356237309504880f;
                 else if (fl == DP && n < DP) m = zu[1 + n];
                 else if (fl < DP && n == DP) m = zu[1 + fl];
                 else if (fl == DP && n == DP) m = zu[0];
-                X[0][r] = m;
+                X[r] = m;
             }
         }
     }
@@ -387,6 +379,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         const bool more = tok0 + C < tok_end;
         if (more) load_raw(tok0 + C);   // a whole chunk ahead: consumed by stage() at the bottom
 
+        // The finished tile of this wave, (query tile w / 2, column tile w % 2): its own partial, to
+        // which the other waves' partials are added while the update phase runs.
+        f32x4 acc[4];
+        float inv = 0.f;
         if (MODE == 0) {
             // =============================== readout ============================================
             // One query tile (32 tokens) at a time, so that only two partial output tiles are live:
@@ -449,10 +445,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                     u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
                     return as_bf16x8(o);
                 };
-                if (w == 0) {
+                if (w < 2) {
                     role_guard();
-                    // extra tile.  Slab 0: the 1st-order rows (the operand is q itself).  Slab 1: the
-                    // constant row (k-slot 0 of g = 0 = local row 16) and the delta = 8 rows
+                    // extra tile, column tile w.  Slab 0: the 1st-order rows (the operand is q itself).
+                    // Slab 1: the constant row (k-slot 0 of g = 0 = local row 16) and the delta = 8 rows
                     // (k-slots 4 + i = local row 24 + 4g + i: sqrt(2) q_a q_(a+8), a = 4g + i)
                     const bf16x8 qbo = load_qb();
                     float pr[8];
@@ -460,27 +456,32 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) pr[4 + i] = qa[i] * qa[4 + i];
                     const bf16x8 hi = pack8(pr);
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) {
-                        Y[c2] = mfma(pack8_acc(X[c2], 0), qbo, Y[c2]);
-                        Y[c2] = mfma(pack8_acc(X[c2], 1), hi, Y[c2]);
+                    const bf16x8 xlo = pack8_acc(X, 0), xhi = pack8_acc(X, 1);
+                    if (w == 0) {
+                        role_guard();
+                        Y[0] = mfma(xlo, qbo, Y[0]);
+                        Y[0] = mfma(xhi, hi, Y[0]);
+                    } else {
+                        role_guard();
+                        Y[1] = mfma(xlo, qbo, Y[1]);
+                        Y[1] = mfma(xhi, hi, Y[1]);
                     }
-                } else if (w == 1) {
+                } else if (w == 2) {
                     role_guard();
                     const bf16x8 qbo = load_qb();
                     // ---- inter-chunk denominator from the moments: count + q.z1 + q^T M q / 2 ----
                     float mres[8];
-                    const bf16x8 mhi = pack8_acc(X[0], 0);
+                    const bf16x8 mhi = pack8_acc(X, 0);
                     {
                         const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            mres[2 * i] = X[0][2 * i] - bf16lo(hb[i]);
-                            mres[2 * i + 1] = X[0][2 * i + 1] - bf16hi(hb[i]);
+                            mres[2 * i] = X[2 * i] - bf16lo(hb[i]);
+                            mres[2 * i + 1] = X[2 * i + 1] - bf16hi(hb[i]);
                         }
                     }
                     const bf16x8 mlo = pack8(mres);
-                    const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[0][8]), 16));
+                    const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[8]), 16));
                     f32x16 T;
                     zero16(T);
                     T = mfma(mhi, qbo, T);
@@ -491,12 +492,14 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                     const float d = fmaf(d2, kHalfInvCQ, T[8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
                     const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
                     if (g == 0) lds.den_inter[32 * qt + n] = tot;
-                } else if (w == 2 || qt == 1) {
+                }
+                // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
+                // wave 0: key tile 0 against query tile 0; wave 1: key tile 1 against query tile 1 (both
+                // cut by the diagonal); wave 3: key tile 0 against query tile 1
+                if (qt == 0 ? w == 0 : (w == 1 || w == 3)) {
                     role_guard();
-                    // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ------
-                    // wave 2: key tile 0 against query tiles 0 and 1; wave 3: key tile 1 against query tile 1
-                    const int kt = w - 2;
-                    const bool diag = kt == qt;
+                    const int kt = w == 1 ? 1 : 0;
+                    const bool diag = w != 3;
                     bf16x8 vk[2][2];   // V^T operands of key tile kt: [s][c2]
 #pragma unroll
                     for (int s = 0; s < 2; ++s)
@@ -555,55 +558,12 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             }
             wg_sync();
             {
-                const int qt = w >> 1, c2 = w & 1;
-                const int qi = 32 * qt + n;
-                const float inv = 1.f / (lds.den_inter[qi] + lds.den_intra[0][qi] + lds.den_intra[1][qi]);
-                // Sum the partials, normalise, and turn the tile through LDS (the wave's own exchange
-                // slot, which it has finished reading by then): a lane holds 8-byte pieces of its
-                // token's row, and stored directly those become 16-byte write requests that stall the
-                // memory pipeline; from LDS the tile leaves as 64-byte row segments, 16 rows a store.
-                f32x4 acc[4];
+                const int qi = 32 * (w >> 1) + n;
+                inv = 1.f / (lds.den_inter[qi] + lds.den_intra[0][qi] + lds.den_intra[1][qi]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) acc[j][i] = Yown[4 * j + i];
-#pragma unroll
-                    for (int sl = 0; sl < 3; ++sl) {
-                        const f32x4 o = *reinterpret_cast<const f32x4 *>(&lds.xbuf[w][sl][j][lane][0]);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[j][i] += o[i];
-                    }
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[j][i] *= inv;
-                }
-                uint16_t *yt = reinterpret_cast<uint16_t *>(&lds.xbuf[w][0][0][0][0]);   // [32][YT_LD] bf16
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bf16x4 hv = __builtin_convertvector(acc[j], bf16x4);
-                    *reinterpret_cast<u32x2 *>(yt + n * YT_LD + 8 * j + 4 * g) = __builtin_bit_cast(u32x2, hv);
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                uint16_t *yc = yu + (size_t)tok0 * dv;
-                // A full chunk stores without a per-lane condition: stores that are certain to be
-                // issued can be counted, so the later wait for the prefetched rows (issued before
-                // them; the counter retires in order) does not have to wait for the stores as well.
-                u32x4 val[2];
-                uint32_t yoff[2];
-#pragma unroll
-                for (int it = 0; it < 2; ++it) {
-                    const int row = 16 * it + (lane >> 2), c = lane & 3;
-                    val[it] = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * c);
-                    yoff[it] = (uint32_t)(32 * qt + row) * (uint32_t)dv + (uint32_t)(32 * c2 + 8 * c);
-                }
-                if (tok0 + C <= tok_end) {
-#pragma unroll
-                    for (int it = 0; it < 2; ++it) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
-                } else {
-#pragma unroll
-                    for (int it = 0; it < 2; ++it)
-                        if (tok0 + 32 * qt + 16 * it + (lane >> 2) < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                }
             }
         }
 
@@ -612,48 +572,131 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         {
             // main tile: row n is the pair a = n % 16, b = (a + 2w + n / 16) % 16
             const int arow = n & 15, brow = (arow + 2 * w + (n >> 4)) & 15;
+            // LDS operands of one step (16 tokens: slab s of key tile kt).  The operands of step i + 1
+            // are requested before step i is worked on, so their latency hides under its arithmetic.
+            struct StepOps {
+                u32x2 va[2], vb[2];   // V^T operands [c2]: column 32 c2 + n, the two runs of 4 tokens
+                f32x4 ka0, ka1, kb0, kb1;
+                u32x2 ea, eb;         // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand (extra tile, moments)
+            };
+            auto load_step = [&](int i, StepOps &o) {
+                const int tcol = 16 * i + 4 * g;   // first token of this lane's k-slots
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    const uint16_t *p = &st.vt[32 * c2 + n][tcol];
+                    o.va[c2] = *reinterpret_cast<const u32x2 *>(p);
+                    o.vb[c2] = *reinterpret_cast<const u32x2 *>(p + 8);
+                }
+                o.ka0 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol]);
+                o.ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
+                o.kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
+                o.kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
+                const uint16_t *pe = &st.ktb[n][tcol];
+                o.ea = *reinterpret_cast<const u32x2 *>(pe);
+                o.eb = *reinterpret_cast<const u32x2 *>(pe + 8);
+            };
+            auto work_step = [&](const StepOps &o) {
+                bf16x8 vk[2];
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int tcol = 32 * kt + 16 * s + 4 * g;   // first token of this lane's k-slots
-                    bf16x8 vk[2];   // V^T operands [c2]: column 32 c2 + n, tokens of the slab
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    u32x4 t; t[0] = o.va[c2][0]; t[1] = o.va[c2][1]; t[2] = o.vb[c2][0]; t[3] = o.vb[c2][1];
+                    vk[c2] = as_bf16x8(t);
+                }
+                float pr[8];
 #pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) {
-                        const uint16_t *p = &st.vt[32 * c2 + n][tcol];
-                        const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                        const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                        u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                        vk[c2] = as_bf16x8(o);
-                    }
-                    {
-                        const f32x4 ka0 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol]);
-                        const f32x4 ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
-                        const f32x4 kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
-                        const f32x4 kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
-                        float pr[8];
+                for (int i = 0; i < 4; ++i) { pr[i] = o.ka0[i] * o.kb0[i]; pr[4 + i] = o.ka1[i] * o.kb1[i]; }
+                const bf16x8 phik = pack8(pr);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) { pr[i] = ka0[i] * kb0[i]; pr[4 + i] = ka1[i] * kb1[i]; }
-                        const bf16x8 phik = pack8(pr);
-#pragma unroll
-                        for (int c2 = 0; c2 < 2; ++c2) S[c2] = mfma(phik, vk[c2], S[c2]);
-                    }
-                    // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand: the extra tile (wave 0), the moments (wave 1)
-                    if (w < 2) {
+                for (int c2 = 0; c2 < 2; ++c2) S[c2] = mfma(phik, vk[c2], S[c2]);
+                if (w < 3) {
+                    role_guard();
+                    u32x4 t; t[0] = o.ea[0]; t[1] = o.ea[1]; t[2] = o.eb[0]; t[3] = o.eb[1];
+                    const bf16x8 kk = as_bf16x8(t);
+                    if (w == 0) {
                         role_guard();
-                        const uint16_t *p = &st.ktb[n][tcol];
-                        const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                        const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                        u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                        const bf16x8 kk = as_bf16x8(o);
-                        if (w == 0) {
-#pragma unroll
-                            for (int c2 = 0; c2 < 2; ++c2) X[c2] = mfma(kk, vk[c2], X[c2]);
-                        } else {
-                            X[0] = mfma(kk, kk, X[0]);
-                        }
+                        X = mfma(kk, vk[0], X);
+                    } else if (w == 1) {
+                        role_guard();
+                        X = mfma(kk, vk[1], X);
+                    } else {
+                        role_guard();
+                        X = mfma(kk, kk, X);
                     }
                 }
+            };
+            // The other waves' partial output tiles are collected a quarter per step, so that these
+            // LDS reads (the largest block of LDS traffic in a chunk) run underneath the MFMAs
+            // instead of in a burst of all waves at once after the barrier.
+            f32x4 xr[3];
+            auto fetch_partials = [&](int j) {
+                if (MODE == 0) {
+#pragma unroll
+                    for (int sl = 0; sl < 3; ++sl)
+                        xr[sl] = *reinterpret_cast<const f32x4 *>(&lds.xbuf[w][sl][j][lane][0]);
+                }
+            };
+            auto add_partials = [&](int j) {
+                if (MODE == 0) {
+#pragma unroll
+                    for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[j][i] += xr[sl][i];
+                }
+            };
+            StepOps oa, ob;
+            load_step(0, oa);
+            load_step(1, ob);
+            fetch_partials(0);
+            work_step(oa);
+            add_partials(0);
+            load_step(2, oa);
+            fetch_partials(1);
+            work_step(ob);
+            add_partials(1);
+            load_step(3, ob);
+            fetch_partials(2);
+            work_step(oa);
+            add_partials(2);
+            fetch_partials(3);
+            work_step(ob);
+            add_partials(3);
+        }
+        if (MODE == 0) {
+            // Normalise and turn the tile through LDS (the wave's own exchange slot, which it has
+            // finished reading): a lane holds 8-byte pieces of its token's row, and stored directly
+            // those become 16-byte write requests that stall the memory pipeline; from LDS the tile
+            // leaves as 64-byte row segments, 16 rows a store.
+            const int qt = w >> 1, c2 = w & 1;
+            uint16_t *yt = reinterpret_cast<uint16_t *>(&lds.xbuf[w][0][0][0][0]);   // [32][YT_LD] bf16
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[j][i] *= inv;
+                const bf16x4 hv = __builtin_convertvector(acc[j], bf16x4);
+                *reinterpret_cast<u32x2 *>(yt + n * YT_LD + 8 * j + 4 * g) = __builtin_bit_cast(u32x2, hv);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            uint16_t *yc = yu + (size_t)tok0 * dv;
+            // A full chunk stores without a per-lane condition: stores that are certain to be
+            // issued can be counted, so the later wait for the prefetched rows (issued before
+            // them; the counter retires in order) does not have to wait for the stores as well.
+            u32x4 val[2];
+            uint32_t yoff[2];
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int row = 16 * it + (lane >> 2), c = lane & 3;
+                val[it] = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * c);
+                yoff[it] = (uint32_t)(32 * qt + row) * (uint32_t)dv + (uint32_t)(32 * c2 + 8 * c);
+            }
+            if (tok0 + C <= tok_end) {
+#pragma unroll
+                for (int it = 0; it < 2; ++it) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+            } else {
+#pragma unroll
+                for (int it = 0; it < 2; ++it)
+                    if (tok0 + 32 * qt + 16 * it + (lane >> 2) < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
         }
         if (more) {
             wg_sync();   // every wave is done reading this chunk's staging
@@ -675,8 +718,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         };
 #pragma unroll
         for (int c2 = 0; c2 < 2; ++c2) put(2 * w + c2, S[c2]);
-        if (w == 0) { put(8, X[0]); put(9, X[1]); }
-        if (w == 1) put(10, X[0]);
+        if (w < 3) put(8 + w, X);
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -688,18 +730,15 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 Su[(size_t)cm.r1 * dv + col] = S[c2][r];
                 if (cm.r2 != cm.r1) Su[(size_t)cm.r2 * dv + col] = S[c2][r];
             }
-            if (w == 0) {
+            if (w < 2) {
                 const CanonRows cx = canon_rows_extra(fl);
                 if (cx.r1 >= 0) {
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) {
-                        const size_t col = (size_t)col0 + 32 * c2 + n;
-                        Su[(size_t)cx.r1 * dv + col] = X[c2][r];
-                        if (cx.r2 != cx.r1) Su[(size_t)cx.r2 * dv + col] = X[c2][r];
-                    }
+                    const size_t col = (size_t)col0 + 32 * w + n;
+                    Su[(size_t)cx.r1 * dv + col] = X[r];
+                    if (cx.r2 != cx.r1) Su[(size_t)cx.r2 * dv + col] = X[r];
                 }
-            } else if (w == 1 && slice == 0) {
-                const float m = X[0][r];
+            } else if (w == 2 && slice == 0) {
+                const float m = X[r];
                 if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
                 else if (fl == DP && n < DP) zu[1 + n] = m;
                 else if (fl == DP && n == DP) zu[0] = m;
