@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 214576087     # based_prefill, both launches (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 578799519      # decode_step_kernel (decode_1p3b)
+MEASURED_PREFILL_TRAFFIC_BYTES = 178053987     # based_prefill, both launches (prefill_360m)
+MEASURED_DECODE_TRAFFIC_BYTES = 579102043      # decode_step_kernel (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
