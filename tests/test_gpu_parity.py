@@ -319,3 +319,96 @@ def test_full_size_prefill_sampled_rows(based, name):
     lo = np.minimum.accumulate(v[units].astype(np.float64), axis=1)
     slack = TOL[wl.dtype] * np.abs(v).max()
     assert (y[units] <= hi + slack).all() and (y[units] >= lo - slack).all()
+
+
+def test_full_size_decode_sampled_units(based):
+    """The batch-128 decode workload in the launch shape the benchmark times (2048 units): a short
+    prefill builds state and ring, then fused decode steps; sampled units against the oracle."""
+    wl = synth.WORKLOADS["decode_1p3b"]
+    B, H, U = wl.B, wl.H, wl.units
+    dp, dv, dh, w, dtype = wl.d_feat, wl.d_v, wl.d_h, wl.w, wl.dtype
+    N0, T = 80, 3
+    q, k, v = lin_case(wl, B, H, N0)
+    sq, sk, sv = synth.swa_inputs(wl, units=U, N=N0)
+    dec = synth.decode_inputs(wl, T)
+    scale = 1.0 / math.sqrt(dh)
+    state = based.alloc_state(B, H, dp, dv)
+    run_prefill(based, wl, B, H, N0, q, k, v, state=state)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    based.swa_prefill(up(sq, dtype, (B, H, N0, dh)), up(sk, dtype, (B, H, N0, dh)), up(sv, dtype, (B, H, N0, dh)),
+                      w, scale, ring=ring)
+    units = np.array([0, 1, 777, U // 2, U - 2, U - 1])
+    cat = lambda a, b: np.concatenate([a[units], b.transpose(1, 0, 2)[units]], axis=1)
+    steps = np.arange(N0, N0 + T)
+    want_lin = oracle.linattn_rows(cat(q, dec["q"]), cat(k, dec["k"]), cat(v, dec["v"]), steps)
+    want_swa = oracle.swa_rows(cat(sq, dec["swa_q"]), cat(sk, dec["swa_k"]), cat(sv, dec["swa_v"]), w, scale, steps)
+    for t in range(T):
+        args = [up(dec[n][t], dtype, (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+        f1, f2 = based.decode_fused(args[0], args[1], args[2], state, args[3], args[4], args[5], ring,
+                                    N0 + t + 1, w, scale)
+        torch.cuda.synchronize()
+        check_close(down(f1).reshape(U, dv)[units], want_lin[:, t], TOL[dtype], f"full-size fused lin step {t}")
+        check_close(down(f2).reshape(U, dh)[units], want_swa[:, t], TOL[dtype], f"full-size fused swa step {t}")
+    # state after the steps, sampled units
+    S, z = based.state_export(state, B, H, dp, dv)
+    kk, vv = cat(k, dec["k"]), cat(v, dec["v"])
+    Sw, zw = oracle.linattn_state(kk, vv)
+    D = Sw.shape[1]
+    check_close(down(S).reshape(U, D, dv)[units], Sw, TOL[dtype], "full-size decode final S")
+    check_close(down(z).reshape(U, D)[units], zw, TOL[dtype], "full-size decode final z")
+
+
+@pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100)])
+def test_swa_prefill_segmented(based, dh, w, N):
+    """Sequences long enough to be cut into segments (ragged last step), every element checked."""
+    wl = make_wl("prefill_360m", d_h=dh, w=w, dtype="bf16")
+    B, H = 1, 2
+    q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
+    scale = 1.0 / math.sqrt(dh)
+    ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    y = based.swa_prefill(up(q, "bf16", (B, H, N, dh)), up(k, "bf16", (B, H, N, dh)), up(v, "bf16", (B, H, N, dh)),
+                          w, scale, ring=ring)
+    torch.cuda.synchronize()
+    want = oracle.swa(q, k, v, w, scale)
+    check_close(down(y).reshape(B * H * N, dh), rows(want), TOL["bf16"], f"segmented swa dh={dh} w={w} N={N}")
+    r = down(ring).reshape(B * H, 2, w, dh)
+    for j in range(N - w, N):
+        assert np.array_equal(r[:, 0, j % w], k[:, j].astype(np.float64))
+        assert np.array_equal(r[:, 1, j % w], v[:, j].astype(np.float64))
+
+
+@pytest.mark.parametrize("scale", [-0.11, 0.0])
+def test_swa_prefill_non_positive_scale(based, scale):
+    """A non-positive softmax scale is legal (Eq. 1 with any temperature) and takes the vector-ALU kernel."""
+    wl = make_wl("prefill_360m", d_h=64, w=64, dtype="bf16")
+    B, H, N = 1, 2, 200
+    q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
+    y = based.swa_prefill(up(q, "bf16", (B, H, N, 64)), up(k, "bf16", (B, H, N, 64)), up(v, "bf16", (B, H, N, 64)),
+                          64, scale)
+    torch.cuda.synchronize()
+    want = oracle.swa(q, k, v, 64, scale)
+    check_close(down(y).reshape(B * H * N, 64), rows(want), TOL["bf16"], f"swa scale {scale}")
+
+
+def test_long_sequence_sampled_rows(based):
+    """Few units, long sequences (8 segments in the linear-attention prefill, window 128): sampled rows."""
+    wl = make_wl("prefill_long", d_feat=16, d_v=64, dtype="bf16")
+    B, H, N = 1, 4, 16384
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N)
+    state = based.alloc_state(B, H, 16, 64)
+    y = run_prefill(based, wl, B, H, N, q, k, v, state=state)
+    sample = np.array([0, 63, 64, 2047, 2048, 2112, 4095, 4096, 8191, 8192, 12287, 12288, N - 65, N - 1])
+    want = oracle.linattn_rows(q, k, v, sample)
+    check_close(rows(y[:, sample]), rows(want), TOL["bf16"], "long sequence sampled rows")
+    S, z = based.state_export(state, B, H, 16, 64)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(S).reshape(Sw.shape), Sw, TOL["bf16"], "long sequence final S")
+    check_close(down(z).reshape(zw.shape), zw, TOL["bf16"], "long sequence final z")
+    sq, sk, sv = synth.swa_inputs(wl, units=U, N=N)
+    scale = 1.0 / math.sqrt(wl.d_h)
+    ys = based.swa_prefill(up(sq, "bf16", (B, H, N, wl.d_h)), up(sk, "bf16", (B, H, N, wl.d_h)),
+                           up(sv, "bf16", (B, H, N, wl.d_h)), wl.w, scale)
+    torch.cuda.synchronize()
+    want = oracle.swa_rows(sq, sk, sv, wl.w, scale, sample)
+    check_close(rows(down(ys).reshape(U, N, wl.d_h)[:, sample]), rows(want), TOL["bf16"], "long sequence swa rows")
