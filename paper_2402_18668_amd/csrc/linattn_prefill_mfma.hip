@@ -56,6 +56,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int DP = 16;            // d'
 constexpr int C = 64;             // chunk length (tokens)
@@ -69,7 +71,7 @@ constexpr float kHalfInvCQ = 0.42044820762685725f;   // 0.5 / kCQ
 // LDS strides (elements)
 constexpr int KTS_LD = C + 4;     // fp32 K^T rows
 constexpr int KTB_LD = C + 4;     // bf16 [K^T; ones; 0] rows (8-byte aligned reads)
-constexpr int VT_LD = C + 4;      // bf16 V^T rows
+constexpr int VR_LD = DVS + 16;   // bf16 V rows (160-byte stride: the transposing reads below are conflict-free)
 constexpr int QS_LD = DP + 4;     // fp32 Q rows
 constexpr int RB_LD = DP + 8;     // bf16 row-major Q / K rows (48-byte stride)
 constexpr int YT_LD = 32 + 8;     // bf16 rows of a finished output tile on its way out (80-byte stride)
@@ -85,7 +87,7 @@ struct Stage {
     float kts[DP][KTS_LD];        // c_k * K^T
     uint16_t ktb[32][KTB_LD];     // rows 0..15 K^T (bf16), row 16 token-valid ones, rows 17..23 zero,
                                   // rows 24..31 k_a k_(a+8) / sqrt(2) (the delta = 8 feature rows)
-    uint16_t vt[DVS][VT_LD];      // V^T (bf16)
+    uint16_t vrow[C][VR_LD];      // V rows, bf16 as given (operands are read transposed)
     float qs[C][QS_LD];           // c_q * Q
     uint16_t qrow[C][RB_LD];      // Q rows, bf16 as given
     uint16_t krow[C][RB_LD];      // K rows, bf16 as given
@@ -358,13 +360,26 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             }
         }
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4 *>(&st.vrow[s_tok][16 * s_q + 8 * j]) = raw_v[j];
+    };
+
+    // V^T operand of an MFMA (lane (g, n): column 32 c2 + n at the 8 tokens of its k-slots, two runs
+    // of 4 consecutive tokens starting at tok4 and tok4 + 8) from the row-major V rows: the
+    // transposing LDS read.  In each group of 16 lanes, lane k supplies the address of 4 consecutive
+    // columns (4 (k % 4) ..) of row k / 4 of the group's 16-column block and receives column k of
+    // that block at the 4 rows.
+    const int tr_kk = lane & 15, tr_grp = (lane >> 4) & 1;
+    const uint16_t *tr_base = &lds.st.vrow[tr_kk >> 2][16 * tr_grp + 4 * (tr_kk & 3)];
+    auto load_vt = [&](int tok4, int c2, s16x4 &a, s16x4 &b) {
+        const uint16_t *p = tr_base + tok4 * VR_LD + 32 * c2;
+        a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+        b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 8 * VR_LD));
+    };
+    auto join_vt = [](s16x4 a, s16x4 b) {
+        s16x8 o;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t wd = raw_v[j][i];
-                st.vt[16 * s_q + 8 * j + 2 * i][s_tok] = (uint16_t)(wd & 0xffffu);
-                st.vt[16 * s_q + 8 * j + 2 * i + 1][s_tok] = (uint16_t)(wd >> 16);
-            }
+        for (int i = 0; i < 4; ++i) { o[i] = a[i]; o[4 + i] = b[i]; }
+        return __builtin_bit_cast(bf16x8, o);
     };
 
     // Pipeline: the rows of chunk c+1 are fetched from global memory into registers at the top of
@@ -505,11 +520,9 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                     for (int s = 0; s < 2; ++s)
 #pragma unroll
                         for (int c2 = 0; c2 < 2; ++c2) {
-                            const uint16_t *p = &st.vt[32 * c2 + n][32 * kt + 16 * s + 4 * g];
-                            const u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-                            const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-                            u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-                            vk[s][c2] = as_bf16x8(o);
+                            s16x4 a, b;
+                            load_vt(32 * kt + 16 * s + 4 * g, c2, a, b);
+                            vk[s][c2] = join_vt(a, b);
                         }
                     f32x16 P;
                     zero16(P);
@@ -575,18 +588,14 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             // LDS operands of one step (16 tokens: slab s of key tile kt).  The operands of step i + 1
             // are requested before step i is worked on, so their latency hides under its arithmetic.
             struct StepOps {
-                u32x2 va[2], vb[2];   // V^T operands [c2]: column 32 c2 + n, the two runs of 4 tokens
+                s16x4 va[2], vb[2];   // V^T operands [c2]: column 32 c2 + n, the two runs of 4 tokens
                 f32x4 ka0, ka1, kb0, kb1;
                 u32x2 ea, eb;         // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand (extra tile, moments)
             };
             auto load_step = [&](int i, StepOps &o) {
                 const int tcol = 16 * i + 4 * g;   // first token of this lane's k-slots
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    const uint16_t *p = &st.vt[32 * c2 + n][tcol];
-                    o.va[c2] = *reinterpret_cast<const u32x2 *>(p);
-                    o.vb[c2] = *reinterpret_cast<const u32x2 *>(p + 8);
-                }
+                for (int c2 = 0; c2 < 2; ++c2) load_vt(tcol, c2, o.va[c2], o.vb[c2]);
                 o.ka0 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol]);
                 o.ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
                 o.kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
@@ -598,10 +607,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             auto work_step = [&](const StepOps &o) {
                 bf16x8 vk[2];
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    u32x4 t; t[0] = o.va[c2][0]; t[1] = o.va[c2][1]; t[2] = o.vb[c2][0]; t[3] = o.vb[c2][1];
-                    vk[c2] = as_bf16x8(t);
-                }
+                for (int c2 = 0; c2 < 2; ++c2) vk[c2] = join_vt(o.va[c2], o.vb[c2]);
                 float pr[8];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) { pr[i] = o.ka0[i] * o.kb0[i]; pr[4 + i] = o.ka1[i] * o.kb1[i]; }
