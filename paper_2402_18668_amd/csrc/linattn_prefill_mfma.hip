@@ -70,10 +70,10 @@ constexpr float kHalfInvCQ = 0.42044820762685725f;   // 0.5 / kCQ
 
 // LDS strides (elements)
 constexpr int KTS_LD = C + 4;     // fp32 K^T rows
-constexpr int KTB_LD = C + 4;     // bf16 [K^T; ones; 0] rows (8-byte aligned reads)
 constexpr int VR_LD = DVS + 16;   // bf16 V rows (160-byte stride: the transposing reads below are conflict-free)
 constexpr int QS_LD = DP + 4;     // fp32 Q rows
-constexpr int RB_LD = DP + 8;     // bf16 row-major Q / K rows (48-byte stride)
+constexpr int RB_LD = DP + 8;     // bf16 row-major Q rows (48-byte stride)
+constexpr int KR_LD = 32 + 16;    // bf16 row-major extended K rows (96-byte stride)
 constexpr int YT_LD = 32 + 8;     // bf16 rows of a finished output tile on its way out (80-byte stride)
 
 // Workspace entry (one segment's state in accumulator layout): 11 slots of 16 registers x 64
@@ -85,12 +85,12 @@ constexpr size_t kWsEntryFloats = (size_t)WS_SLOTS * 16 * 64;
 
 struct Stage {
     float kts[DP][KTS_LD];        // c_k * K^T
-    uint16_t ktb[32][KTB_LD];     // rows 0..15 K^T (bf16), row 16 token-valid ones, rows 17..23 zero,
-                                  // rows 24..31 k_a k_(a+8) / sqrt(2) (the delta = 8 feature rows)
     uint16_t vrow[C][VR_LD];      // V rows, bf16 as given (operands are read transposed)
     float qs[C][QS_LD];           // c_q * Q
     uint16_t qrow[C][RB_LD];      // Q rows, bf16 as given
-    uint16_t krow[C][RB_LD];      // K rows, bf16 as given
+    uint16_t krow[C][KR_LD];      // extended K rows: [k_0..k_15 as given, 1 (0 past the end), 0 x 7,
+                                  // k_a k_(a+8) / sqrt(2) for a < 8]: read row-wise by the intra-chunk
+                                  // block and transposed as the operand of the extra tile and the moments
 };
 
 struct Lds {
@@ -290,8 +290,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         }
     }
 
-    // zero rows 17..23 of the K'^T staging rows and the unused half of den_intra[1] once
-    for (int i = tid; i < 7 * KTB_LD; i += NT) lds.st.ktb[17 + i / KTB_LD][i % KTB_LD] = 0;
+    // zero the unused half of den_intra[1] once
     if (tid < C) lds.den_intra[1][tid] = 0.f;
 
     // ---- staging: global -> registers -> LDS ----------------------------------------------------
@@ -334,8 +333,6 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                     kf[j][2 * i + 1] = bf16hi(wd) * kCK;
                     st.kts[a][s_tok] = kf[j][2 * i];
                     st.kts[a + 1][s_tok] = kf[j][2 * i + 1];
-                    st.ktb[a][s_tok] = (uint16_t)(wd & 0xffffu);
-                    st.ktb[a + 1][s_tok] = (uint16_t)(wd >> 16);
                 }
                 *reinterpret_cast<u32x2 *>(&st.krow[s_tok][8 * j + 4 * s_h]) = raw_x[j];
             }
@@ -343,12 +340,12 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) pr[i] = kf[0][i] * kf[1][i];
             const u32x2 pb = __builtin_bit_cast(u32x2, __builtin_convertvector(pr, bf16x4));
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                st.ktb[24 + 4 * s_h + 2 * i][s_tok] = (uint16_t)(pb[i] & 0xffffu);
-                st.ktb[24 + 4 * s_h + 2 * i + 1][s_tok] = (uint16_t)(pb[i] >> 16);
+            *reinterpret_cast<u32x2 *>(&st.krow[s_tok][24 + 4 * s_h]) = pb;
+            if (s_q == 0) {
+                u32x4 one = {0u, 0u, 0u, 0u};
+                if (tok0 + s_tok < tok_end) one[0] = 0x3F80u;
+                *reinterpret_cast<u32x4 *>(&st.krow[s_tok][16]) = one;
             }
-            if (s_q == 0) st.ktb[16][s_tok] = (tok0 + s_tok < tok_end) ? (uint16_t)0x3F80u : (uint16_t)0u;
         } else if (MODE == 0) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -370,6 +367,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     // that block at the 4 rows.
     const int tr_kk = lane & 15, tr_grp = (lane >> 4) & 1;
     const uint16_t *tr_base = &lds.st.vrow[tr_kk >> 2][16 * tr_grp + 4 * (tr_kk & 3)];
+    const uint16_t *tr_kbase = &lds.st.krow[tr_kk >> 2][16 * tr_grp + 4 * (tr_kk & 3)];
     auto load_vt = [&](int tok4, int c2, s16x4 &a, s16x4 &b) {
         const uint16_t *p = tr_base + tok4 * VR_LD + 32 * c2;
         a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
@@ -590,7 +588,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             struct StepOps {
                 s16x4 va[2], vb[2];   // V^T operands [c2]: column 32 c2 + n, the two runs of 4 tokens
                 f32x4 ka0, ka1, kb0, kb1;
-                u32x2 ea, eb;         // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand (extra tile, moments)
+                s16x4 ea, eb;         // [k_0..k_15, 1, 0 x 7, delta = 8 rows]^T operand (extra tile, moments)
             };
             auto load_step = [&](int i, StepOps &o) {
                 const int tcol = 16 * i + 4 * g;   // first token of this lane's k-slots
@@ -600,9 +598,9 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 o.ka1 = *reinterpret_cast<const f32x4 *>(&st.kts[arow][tcol + 8]);
                 o.kb0 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol]);
                 o.kb1 = *reinterpret_cast<const f32x4 *>(&st.kts[brow][tcol + 8]);
-                const uint16_t *pe = &st.ktb[n][tcol];
-                o.ea = *reinterpret_cast<const u32x2 *>(pe);
-                o.eb = *reinterpret_cast<const u32x2 *>(pe + 8);
+                const uint16_t *pe = tr_kbase + tcol * KR_LD;
+                o.ea = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)pe);
+                o.eb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(pe + 8 * KR_LD));
             };
             auto work_step = [&](const StepOps &o) {
                 bf16x8 vk[2];
@@ -616,8 +614,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 for (int c2 = 0; c2 < 2; ++c2) S[c2] = mfma(phik, vk[c2], S[c2]);
                 if (w < 3) {
                     role_guard();
-                    u32x4 t; t[0] = o.ea[0]; t[1] = o.ea[1]; t[2] = o.eb[0]; t[3] = o.eb[1];
-                    const bf16x8 kk = as_bf16x8(t);
+                    const bf16x8 kk = join_vt(o.ea, o.eb);
                     if (w == 0) {
                         role_guard();
                         X = mfma(kk, vk[0], X);
