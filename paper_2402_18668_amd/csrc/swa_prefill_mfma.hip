@@ -150,18 +150,38 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qop[s]));
     __syncthreads();
 
-    for (int sq0 = q0; sq0 < q_end; sq0 += BQ) {
-        const bool more = sq0 + BQ < q_end;
-        if (more) {   // prefetch the BQ rows of the next step and its queries
+    // One step of BQ queries.  Steps that have a successor are instantiated apart from the last one
+    // of the segment, so that inside them every prefetch and every store is unconditional code and
+    // the number of memory operations in flight is known exactly wherever one has to be waited for.
+    auto step = [&](const int sq0, auto more_c) {
+        constexpr bool more = decltype(more_c)::value;
+        // The BQ rows of the next step and its queries are requested in three portions, before the
+        // scores, the softmax and the P.V product: all waves of a CU asking for everything at once
+        // would queue behind each other at the memory pipeline with nothing else to issue.
+        auto prefetch_k = [&]() {
+            if constexpr (more) {
 #pragma unroll
-            for (int it = 0; it < NEWIT; ++it) {
-                const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
-                const int key = min(sq0 + BQ + r, N - 1);
-                nk[it] = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
-                nv[it] = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
+                for (int it = 0; it < NEWIT; ++it) {
+                    const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+                    const int key = min(sq0 + BQ + r, N - 1);
+                    nk[it] = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
+                }
             }
-            load_q(sq0 + BQ, qnext);
-        }
+        };
+        auto prefetch_v = [&]() {
+            if constexpr (more) {
+#pragma unroll
+                for (int it = 0; it < NEWIT; ++it) {
+                    const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+                    const int key = min(sq0 + BQ + r, N - 1);
+                    nv[it] = *reinterpret_cast<const u32x4 *>(v + base + (size_t)key * DH + c * 8);
+                }
+            }
+        };
+        auto prefetch_q = [&]() {
+            if constexpr (more) load_q(sq0 + BQ, qnext);
+        };
+        prefetch_q();
 
         const int qbase = sq0 + 32 * wv;          // first query of this wave's tile
         const int query = qbase + n;
@@ -185,6 +205,8 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                     P[t] = mfma(as_bf16x8(kop), as_bf16x8(qop[s]), P[t]);
                 }
             }
+
+            prefetch_k();
 
             // ---- mask, softmax statistics (lane = query; its keys sit in registers and in lane ^ 32) --
             // Raw scores are masked and their maximum taken; the scale (times log2 e) is applied inside
@@ -224,6 +246,8 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                     sum += pe;
                 }
             sum += __shfl_xor(sum, 32, 64);
+
+            prefetch_v();
 
             // ---- Y^T = V^T P^T ----------------------------------------------------------------------------
             f32x16 Y[CT];
@@ -294,7 +318,7 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                     // A full step stores without a per-lane condition, so that the stores can be
                     // counted and the wait for the prefetched rows (older, retired in order) is not
                     // also a wait for these stores.
-                    if (sq0 + BQ <= q_end) {
+                    if (more || sq0 + BQ <= q_end) {
 #pragma unroll
                         for (int it = 0; it < 4; ++it) *reinterpret_cast<u32x4 *>(dst[it]) = val[it];
                     } else {
@@ -307,7 +331,7 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             }
         }
 
-        if (more) {
+        if constexpr (more) {
             __syncthreads();   // every wave is done with the rows that are overwritten now
             const int rel_new = (sq0 + BQ) - (q0 - W);   // ring position of the first new key
 #pragma unroll
@@ -331,7 +355,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             for (int s = 0; s < SLABS; ++s) qop[s] = qnext[s];
             __syncthreads();
         }
-    }
+    };
+    int sq0 = q0;
+    for (; sq0 + BQ < q_end; sq0 += BQ) step(sq0, std::true_type{});
+    step(sq0, std::false_type{});
 }
 
 template <int DH, int W>
