@@ -44,6 +44,8 @@
 // the sum of the increments before it.
 #include "common.h"
 
+#include <atomic>
+
 namespace based {
 
 namespace {
@@ -174,7 +176,43 @@ __device__ __forceinline__ CanonRows canon_rows_extra(int fl)
     return {-1, -1};
 }
 
-constexpr int kMaxSegments = 8;
+// Workspace accesses that cross workgroups inside one launch.  Each XCD has its own L2, and memory
+// written by a workgroup on one XCD is only guaranteed to be seen by another XCD's workgroups at a
+// kernel boundary, unless the accesses are marked system-coherent (sc0 sc1: written through to, and
+// read from, the memory side of the L2s).  All loads of an entry are in flight at once and the wait
+// sits in the same statement, so that every output register is valid as far as the compiler can tell.
+__device__ __forceinline__ void store16_coherent(float *p, const f32x4 &v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void load_entry_coherent(const float *p0, const float *p1, const float *p2,
+                                                    f32x4 (&t)[12])
+{
+    asm volatile(
+        "global_load_dwordx4 %0, %12, off offset:0 sc0 sc1\n\t"
+        "global_load_dwordx4 %1, %12, off offset:1024 sc0 sc1\n\t"
+        "global_load_dwordx4 %2, %12, off offset:2048 sc0 sc1\n\t"
+        "global_load_dwordx4 %3, %12, off offset:3072 sc0 sc1\n\t"
+        "global_load_dwordx4 %4, %13, off offset:0 sc0 sc1\n\t"
+        "global_load_dwordx4 %5, %13, off offset:1024 sc0 sc1\n\t"
+        "global_load_dwordx4 %6, %13, off offset:2048 sc0 sc1\n\t"
+        "global_load_dwordx4 %7, %13, off offset:3072 sc0 sc1\n\t"
+        "global_load_dwordx4 %8, %14, off offset:0 sc0 sc1\n\t"
+        "global_load_dwordx4 %9, %14, off offset:1024 sc0 sc1\n\t"
+        "global_load_dwordx4 %10, %14, off offset:2048 sc0 sc1\n\t"
+        "global_load_dwordx4 %11, %14, off offset:3072 sc0 sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]),
+          "=&v"(t[7]), "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11])
+        : "v"(p0), "v"(p1), "v"(p2)
+        : "memory");
+}
+
+// Upper bound on the polls of a segment-ready flag (each poll sleeps ~0.25 us): a workgroup never
+// waits forever, whatever happens to the workgroup it waits for.
+constexpr int kMaxFlagPolls = 1 << 20;
+
+constexpr int kMaxSegments = 16;
 // first token of each segment (multiples of the chunk length), and the end of the last one
 struct SegTable { int begin[kMaxSegments + 1]; };
 
@@ -185,25 +223,23 @@ struct SegTable { int begin[kMaxSegments + 1]; };
 // MODE 2: the caller's initial state, converted to accumulator layout, written to entry 0.
 // The main launch never reads the caller's state buffer, so writing the final state back into it
 // cannot race with another workgroup still starting up.
-template <int MODE>
-__global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws, int N,
-    int dv, SegTable segs, int G)
+// FUSED: the increments and the main pass run in ONE launch.  Increment workgroups come first in the
+// grid and wait for nothing; a main-pass workgroup of segment g > 0 waits (bounded) for the flags
+// of the increments before it.  flags[(unit slice) * G + p] == epoch says that entry p of this call
+// is complete.
+template <int MODE, bool FUSED>
+__device__ __forceinline__ void prefill_body(
+    Lds &lds, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
+    const uint16_t *__restrict__ v, uint16_t *__restrict__ y, float *__restrict__ state, int has_init,
+    float *__restrict__ ws, unsigned *__restrict__ flags, unsigned epoch, int N, int dv,
+    const SegTable &segs, int G, int seg, int slice, int u)
 {
-    __shared__ __align__(16) Lds lds;
-
     const int tid = threadIdx.x;
     const int w = tid >> 6;   // wave index: owns the main tile delta in {2w, 2w+1}
     const int lane = tid & 63;
     const int g = lane >> 5, n = lane & 31;
 
     const int slices = dv / DVS;
-    const int gseg = MODE == 1 ? G - 1 : (MODE == 2 ? 1 : G);   // segments this launch covers
-    int bid = blockIdx.x;
-    const int seg = bid % gseg; bid /= gseg;
-    const int slice = bid % slices;
-    const int u = bid / slices;
     const int col0 = slice * DVS;
 
     const int tok_begin = segs.begin[seg];
@@ -216,6 +252,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
     float *zu = Su ? Su + (size_t)feature_dim(DP) * dv : nullptr;
     float *ws_unit = ws ? ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats : nullptr;
+    unsigned *flags_unit = flags ? flags + (size_t)(u * slices + slice) * G : nullptr;
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[2];           // main tile [c2]
@@ -233,14 +270,6 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
         const int x0 = w < 3 ? 8 + w : 2 * w;
         const size_t so[3] = {ws_slot_off(2 * w + 0, 0, lane), ws_slot_off(2 * w + 1, 0, lane),
                               ws_slot_off(x0, 0, lane)};
-        auto fetch = [&](int p, f32x4 (&t)[12]) {
-            const float *e = ws_unit + (size_t)min(p, seg) * kWsEntryFloats;
-#pragma unroll
-            for (int sl = 0; sl < 3; ++sl)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    t[sl * 4 + j] = *reinterpret_cast<const f32x4 *>(e + so[sl] + (size_t)j * 256);
-        };
         auto add_in = [&](const f32x4 (&t)[12]) {
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
@@ -252,14 +281,41 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
             }
         };
         const int p0 = has_init ? 0 : 1;
-        if (p0 <= seg) {
-            f32x4 ta[12], tb[12];
-            fetch(p0, ta);
-            for (int p = p0; p <= seg; p += 2) {
-                fetch(p + 1, tb);
-                add_in(ta);
-                fetch(p + 2, ta);
-                if (p + 1 <= seg) add_in(tb);
+        if (FUSED) {
+            // wait for the increments of this call (entry 0 comes from an earlier launch)
+            if (tid == 0) {
+                for (int p = 1; p <= seg; ++p) {
+                    int polls = 0;
+                    while (__hip_atomic_load(flags_unit + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch &&
+                           ++polls < kMaxFlagPolls)
+                        __builtin_amdgcn_s_sleep(8);
+                }
+            }
+            __syncthreads();
+            for (int p = p0; p <= seg; ++p) {
+                const float *e = ws_unit + (size_t)p * kWsEntryFloats;
+                f32x4 t[12];
+                load_entry_coherent(e + so[0], e + so[1], e + so[2], t);
+                add_in(t);
+            }
+        } else {
+            auto fetch = [&](int p, f32x4 (&t)[12]) {
+                const float *e = ws_unit + (size_t)min(p, seg) * kWsEntryFloats;
+#pragma unroll
+                for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        t[sl * 4 + j] = *reinterpret_cast<const f32x4 *>(e + so[sl] + (size_t)j * 256);
+            };
+            if (p0 <= seg) {
+                f32x4 ta[12], tb[12];
+                fetch(p0, ta);
+                for (int p = p0; p <= seg; p += 2) {
+                    fetch(p + 1, tb);
+                    add_in(ta);
+                    fetch(p + 2, ta);
+                    if (p + 1 <= seg) add_in(tb);
+                }
             }
         }
     }
@@ -716,12 +772,20 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
                 f32x4 o;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) o[i] = a[4 * j + i];
-                *reinterpret_cast<f32x4 *>(e + ws_slot_off(slot, j, lane)) = o;
+                if (FUSED) store16_coherent(e + ws_slot_off(slot, j, lane), o);
+                else *reinterpret_cast<f32x4 *>(e + ws_slot_off(slot, j, lane)) = o;
             }
         };
 #pragma unroll
         for (int c2 = 0; c2 < 2; ++c2) put(2 * w + c2, S[c2]);
         if (w < 3) put(8 + w, X);
+        if (FUSED) {
+            // the entry has reached memory (the stores are written through) before the flag is raised
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0)
+                __hip_atomic_store(flags_unit + 1 + seg, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     } else if (Su && seg == G - 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -750,6 +814,45 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     }
 }
 
+template <int MODE>
+__global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws, int N,
+    int dv, SegTable segs, int G)
+{
+    __shared__ __align__(16) Lds lds;
+    const int slices = dv / DVS;
+    const int gseg = MODE == 1 ? G - 1 : (MODE == 2 ? 1 : G);   // segments this launch covers
+    int bid = blockIdx.x;
+    const int seg = bid % gseg; bid /= gseg;
+    prefill_body<MODE, false>(lds, q, k, v, y, state, has_init, ws, nullptr, 0u, N, dv, segs, G, seg,
+                              bid % slices, bid / slices);
+}
+
+// Increments and main pass in one launch.  Grid: first the (G - 1) increments of every unit slice,
+// then the main-pass workgroups segment by segment (all segment-0 workgroups first: they depend
+// on nothing and fill the slots the increment workgroups leave free).
+__global__ __launch_bounds__(NT, 2) void prefill_mfma_fused_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws,
+    unsigned *__restrict__ flags, unsigned epoch, int N, int dv, SegTable segs, int G, int groups)
+{
+    __shared__ __align__(16) Lds lds;
+    const int slices = dv / DVS;
+    const int n_inc = groups * (G - 1);
+    int bid = blockIdx.x;
+    if (bid < n_inc) {
+        const int seg = bid % (G - 1); bid /= (G - 1);
+        prefill_body<1, true>(lds, q, k, v, y, state, has_init, ws, flags, epoch, N, dv, segs, G, seg,
+                              bid % slices, bid / slices);
+    } else {
+        bid -= n_inc;
+        const int seg = bid / groups; bid %= groups;
+        prefill_body<0, true>(lds, q, k, v, y, state, has_init, ws, flags, epoch, N, dv, segs, G, seg,
+                              bid % slices, bid / slices);
+    }
+}
+
 // ---- host side ----------------------------------------------------------------------------------
 namespace {
 
@@ -762,7 +865,7 @@ int pick_segments(int U, int N, int dv)
     int G = (int)((want + groups - 1) / groups);
     const int max_by_len = N / 512;
     if (G > max_by_len) G = max_by_len;
-    if (G > 8) G = 8;
+    if (G > kMaxSegments) G = kMaxSegments;
     if (G < 1) G = 1;
     return G;
 }
@@ -802,11 +905,17 @@ bool prefill_mfma_supported(int dp, int dv, int dtype)
     return dtype == BASED_BF16 && dp == DP && (dv == 64 || dv == 128);
 }
 
+// Workspace: G entries per unit slice, then one ready flag per entry (256-byte aligned).
+static size_t ws_entry_bytes(int U, int N, int dv)
+{
+    return (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
+}
+
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv)
 {
     (void)dp;
-    const int G = pick_segments(U, N, dv);
-    return (size_t)U * (dv / DVS) * G * kWsEntryFloats * sizeof(float);
+    const size_t flags = (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * sizeof(unsigned);
+    return ws_entry_bytes(U, N, dv) + (flags + 255) / 256 * 256;
 }
 
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
@@ -826,10 +935,16 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {
-        hipLaunchKernelGGL((prefill_mfma_kernel<1>), dim3((unsigned)(U * slices * (G - 1))), dim3(NT), 0, s,
-                           q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv,
-                           segs, G);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        // Every call raises its flags to a value no earlier call used (the flag words keep whatever
+        // the last call, or nobody, left in them).
+        static std::atomic<unsigned> calls{0};
+        const unsigned epoch = 0x5EED0000u + calls.fetch_add(1u) + 1u;
+        unsigned *flags = reinterpret_cast<unsigned *>((char *)workspace + ws_entry_bytes(U, N, dv));
+        const int groups = U * slices;
+        hipLaunchKernelGGL(prefill_mfma_fused_kernel, dim3((unsigned)(groups * (2 * G - 1))), dim3(NT), 0, s,
+                           q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, flags, epoch, N,
+                           dv, segs, G, groups);
+        return hipGetLastError();
     }
     hipLaunchKernelGGL((prefill_mfma_kernel<0>), dim3((unsigned)(U * slices * G)), dim3(NT), 0, s, q16, k16,
                        v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv, segs, G);
