@@ -225,8 +225,10 @@ struct SegTable { int begin[kMaxSegments + 1]; };
 // cannot race with another workgroup still starting up.
 // FUSED: the increments and the main pass run in ONE launch.  Increment workgroups come first in the
 // grid and wait for nothing; a main-pass workgroup of segment g > 0 waits (bounded) for the flags
-// of the increments before it.  flags[(unit slice) * G + p] == epoch says that entry p of this call
-// is complete.
+// of the increments before it.  Flag word F[unit slice][p][g] == epoch tells the main-pass workgroup
+// of segment g that entry p of this call is complete: every word has one writer and one reader, and
+// the reader zeroes it once it has seen it, so the words are clear again when the launch ends (a
+// replay of a captured launch, which repeats the same epoch, starts from cleared flags).
 template <int MODE, bool FUSED>
 __device__ __forceinline__ void prefill_body(
     Lds &lds, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
@@ -252,7 +254,7 @@ __device__ __forceinline__ void prefill_body(
     float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
     float *zu = Su ? Su + (size_t)feature_dim(DP) * dv : nullptr;
     float *ws_unit = ws ? ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats : nullptr;
-    unsigned *flags_unit = flags ? flags + (size_t)(u * slices + slice) * G : nullptr;
+    unsigned *flags_unit = flags ? flags + (size_t)(u * slices + slice) * G * G : nullptr;
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[2];           // main tile [c2]
@@ -285,10 +287,12 @@ __device__ __forceinline__ void prefill_body(
             // wait for the increments of this call (entry 0 comes from an earlier launch)
             if (tid == 0) {
                 for (int p = 1; p <= seg; ++p) {
+                    unsigned *f = flags_unit + p * G + seg;
                     int polls = 0;
-                    while (__hip_atomic_load(flags_unit + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch &&
+                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch &&
                            ++polls < kMaxFlagPolls)
                         __builtin_amdgcn_s_sleep(8);
+                    __hip_atomic_store(f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                 }
             }
             __syncthreads();
@@ -783,8 +787,10 @@ __device__ __forceinline__ void prefill_body(
             // the entry has reached memory (the stores are written through) before the flag is raised
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (tid == 0)
-                __hip_atomic_store(flags_unit + 1 + seg, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            // entry 1 + seg is read by the main-pass workgroups of segments 1 + seg .. G - 1
+            if (tid >= 1 + seg && tid < G)
+                __hip_atomic_store(flags_unit + (1 + seg) * G + tid, epoch, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
         }
     } else if (Su && seg == G - 1) {
 #pragma unroll
@@ -905,7 +911,7 @@ bool prefill_mfma_supported(int dp, int dv, int dtype)
     return dtype == BASED_BF16 && dp == DP && (dv == 64 || dv == 128);
 }
 
-// Workspace: G entries per unit slice, then one ready flag per entry (256-byte aligned).
+// Workspace: G entries per unit slice, then G x G ready-flag words per unit slice (256-byte aligned).
 static size_t ws_entry_bytes(int U, int N, int dv)
 {
     return (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
@@ -914,7 +920,8 @@ static size_t ws_entry_bytes(int U, int N, int dv)
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv)
 {
     (void)dp;
-    const size_t flags = (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * sizeof(unsigned);
+    const size_t Gmax = (size_t)pick_segments(U, N, dv);
+    const size_t flags = (size_t)U * (dv / DVS) * Gmax * Gmax * sizeof(unsigned);
     return ws_entry_bytes(U, N, dv) + (flags + 255) / 256 * 256;
 }
 
@@ -935,8 +942,8 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {
-        // Every call raises its flags to a value no earlier call used (the flag words keep whatever
-        // the last call, or nobody, left in them).
+        // Every call raises its flags to a value no earlier call used: the flag words of a workspace
+        // that has never been used hold whatever was in that memory.
         static std::atomic<unsigned> calls{0};
         const unsigned epoch = 0x5EED0000u + calls.fetch_add(1u) + 1u;
         unsigned *flags = reinterpret_cast<unsigned *>((char *)workspace + ws_entry_bytes(U, N, dv));

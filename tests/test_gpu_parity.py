@@ -412,3 +412,36 @@ def test_long_sequence_sampled_rows(based):
     torch.cuda.synchronize()
     want = oracle.swa_rows(sq, sk, sv, wl.w, scale, sample)
     check_close(rows(down(ys).reshape(U, N, wl.d_h)[:, sample]), rows(want), TOL["bf16"], "long sequence swa rows")
+
+
+def test_prefill_graph_replay(based):
+    """A captured segmented prefill (increments and main pass in one launch, ready flags in the
+    workspace) gives the eager result on every replay, with eager work and synchronisation between."""
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, N = 1, 2, 1600
+    q, k, v = lin_case(wl, B, H, N)
+    tq, tk, tv = (up(a, "bf16", (B, H, N, a.shape[-1])) for a in (q, k, v))
+    ws = based.alloc_prefill_workspace(B, H, N, wl.d_feat, wl.d_v, based.BF16)
+    y_eager = based.prefill(tq, tk, tv, workspace=ws)
+    torch.cuda.synchronize()
+    want = oracle.linattn_quadratic(q, k, v)
+    check_close(rows(down(y_eager).reshape(B * H, N, wl.d_v)), rows(want), TOL["bf16"], "eager segmented prefill")
+    y_graph = torch.empty_like(y_eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        based.prefill(tq, tk, tv, y=y_graph, workspace=ws)   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        based.prefill(tq, tk, tv, y=y_graph, workspace=ws)
+    for rep in range(3):
+        y_graph.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {rep} differs from the eager result"
+        # eager work on the same workspace between replays
+        y2 = based.prefill(tq, tk, tv, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_eager)
