@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 178053987     # based_prefill, both launches (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 579102043      # decode_step_kernel (decode_1p3b)
+MEASURED_PREFILL_TRAFFIC_BYTES = 158715108     # based_prefill (prefill_360m)
+MEASURED_DECODE_TRAFFIC_BYTES = 579100526      # decode_step_kernel (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
@@ -145,7 +145,7 @@ def main() -> int:
     flops_full_d = lin_prefill_flops_per_token_head(dp, dv, packed=False) * U * N
     achieved = flops / (prefill_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "based_prefill (state-increment launch + main chunked launch)",
+        "kernel": "based_prefill (prefill_mfma_fused_kernel: segment increments + main chunked pass in one launch)",
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_PREFILL_TRAFFIC_BYTES,
         "avg_ms": round(prefill_ms, 4), "flops_per_launch": flops,
