@@ -35,6 +35,7 @@ PEAK_HBM_GBS = 8000.0
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
 MEASURED_PREFILL_TRAFFIC_BYTES = 158715108     # based_prefill (prefill_360m)
+MEASURED_SWA_TRAFFIC_BYTES = 142819555         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
 MEASURED_DECODE_TRAFFIC_BYTES = 579100526      # decode_step_kernel (decode_1p3b)
 
 
@@ -115,6 +116,7 @@ def main() -> int:
 
     ev_a = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ev_b = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
 
     def step(i, timed_index=None):
         s = sets[i % NSETS]
@@ -124,6 +126,8 @@ def main() -> int:
         if timed_index is not None:
             ev_b[timed_index].record()
         based.swa_prefill(s["sq"], s["sk"], s["sv"], w, scale, y=s["sy"], ring=s["ring"])
+        if timed_index is not None:
+            ev_c[timed_index].record()
         based.decode_fused(s["dq"], s["dk"], s["dv"], s["state"], s["dsq"], s["dsk"], s["dsv"], s["ring"],
                            N + 1, w, scale, y_lin=s["yl"], y_swa=s["ys"])
 
@@ -155,6 +159,15 @@ def main() -> int:
         "algorithmic_bytes_per_launch": (2 * dp + 2 * dv) * 2 * U * N,
     }
 
+    swa_ms = float(np.mean([b.elapsed_time(c) for b, c in zip(ev_b, ev_c)]))
+    swa_bytes = 4 * dh * 2 * U * N
+    swa_roofline = {
+        "kernel": "based_swa_prefill (swa_prefill_mfma_kernel)", "bound": "hbm",
+        "achieved": round(swa_bytes / (swa_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": round(swa_bytes / (swa_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "avg_ms": round(swa_ms, 4),
+        "algorithmic_bytes_per_launch": swa_bytes, "traffic": MEASURED_SWA_TRAFFIC_BYTES,
+    }
+
     out = {
         "metric": "prefill tokens/s + decode tokens/s per layer; % MFMA / % HBM peak",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -165,6 +178,7 @@ def main() -> int:
                    "buffer_sets": NSETS},
         "prefill_tokens_per_s_linear_attention_only": round(B * N / (prefill_ms * 1e-3), 1),
         "roofline": roofline,
+        "swa_prefill": {"tokens_per_s": round(B * N / (swa_ms * 1e-3), 1), "roofline": swa_roofline},
     }
 
     # ---- decode leg: 1.3B-shaped, batch 128, fused state update/readout + ring attention ---------
