@@ -153,6 +153,33 @@ int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                        const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
                        float scale, int B, int H, int dtype, void *stream);
 
+/*
+ * Packed state (variant).  The rows (a, b) and (b, a) of the 2nd-order block of a state of this
+ * recurrence are equal (x_a x_b = x_b x_a in Eq. 4; the paper's own state-size count uses one row
+ * per unordered pair), so a decode step that carries one row per pair moves 44 % fewer bytes at
+ * d' = 16.  D_packed = 1 + d' + d'(d'+1)/2 (153 at d' = 16, 561 at d' = 32).
+ *
+ * Packed layout, per unit at float offset u * stride: Sp[D_packed][d_v] then zp[D_packed];
+ * row 0 constant, 1 + a linear, 1 + d' + a d' - a(a-1)/2 + (b - a) the pair a <= b, holding the
+ * value of the canonical row (a, b).  stride = D_packed * d_v + D_packed rounded up to 64 floats.
+ *
+ * based_state_pack reads a state buffer (layout at the top of this file) and writes the packed
+ * one, taking the mean of the two rows of a pair; based_state_unpack writes both rows of a pair.
+ * based_decode_step_packed and based_decode_fused_packed are based_decode_step and
+ * based_decode_fused on a packed state (same y up to rounding order).
+ */
+int based_packed_feature_dim(int d_feat);
+size_t based_packed_state_stride_floats(int d_feat, int d_v);
+size_t based_packed_state_bytes(int B, int H, int d_feat, int d_v);
+int based_state_pack(const void *state, void *packed, int B, int H, int d_feat, int d_v, void *stream);
+int based_state_unpack(const void *packed, void *state, int B, int H, int d_feat, int d_v, void *stream);
+int based_decode_step_packed(const void *q, const void *k, const void *v, void *y, void *packed, int B,
+                             int H, int d_feat, int d_v, int dtype, void *stream);
+int based_decode_fused_packed(const void *q, const void *k, const void *v, void *y_lin, void *packed,
+                              int d_feat, int d_v, const void *swa_q, const void *swa_k,
+                              const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
+                              float scale, int B, int H, int dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,8 @@ EXPORTS = [
     "based_state_stride_floats", "based_state_export", "based_state_import",
     "based_prefill_workspace_bytes", "based_prefill", "based_decode_step", "based_swa_ring_bytes",
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
+    "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
+    "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
 ]
 
 
@@ -66,6 +68,20 @@ def _load() -> ctypes.CDLL:
     lib.based_swa_decode.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
     lib.based_decode_fused.restype = i
     lib.based_decode_fused.argtypes = [vp, vp, vp, vp, vp, i, i, vp, vp, vp, vp, vp, i, i, i, f, i, i, i, vp]
+    lib.based_packed_feature_dim.restype = i
+    lib.based_packed_feature_dim.argtypes = [i]
+    lib.based_packed_state_stride_floats.restype = sz
+    lib.based_packed_state_stride_floats.argtypes = [i, i]
+    lib.based_packed_state_bytes.restype = sz
+    lib.based_packed_state_bytes.argtypes = [i, i, i, i]
+    lib.based_state_pack.restype = i
+    lib.based_state_pack.argtypes = [vp, vp, i, i, i, i, vp]
+    lib.based_state_unpack.restype = i
+    lib.based_state_unpack.argtypes = [vp, vp, i, i, i, i, vp]
+    lib.based_decode_step_packed.restype = i
+    lib.based_decode_step_packed.argtypes = lib.based_decode_step.argtypes
+    lib.based_decode_fused_packed.restype = i
+    lib.based_decode_fused_packed.argtypes = lib.based_decode_fused.argtypes
     return lib
 
 
@@ -181,19 +197,52 @@ def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None):
     return y
 
 
-def decode_step(q, k, v, state, y=None):
-    """based_decode_step.  q, k ``[B,H,d']``; v ``[B,H,d_v]``; state updated in place."""
+def packed_state_bytes(B, H, d_feat, d_v) -> int:
+    return int(lib.based_packed_state_bytes(B, H, d_feat, d_v))
+
+
+def alloc_packed_state(B, H, d_feat, d_v, device="cuda") -> torch.Tensor:
+    """Zeroed packed-state buffer ``[B*H, stride]`` (fp32)."""
+    stride = int(lib.based_packed_state_stride_floats(d_feat, d_v))
+    if stride == 0:
+        raise BasedError(ERR_UNSUPPORTED, "based_packed_state_stride_floats")
+    return torch.zeros((B * H, stride), dtype=torch.float32, device=device)
+
+
+def state_pack(state, packed, B, H, d_feat, d_v):
+    """based_state_pack: state buffer -> packed state buffer."""
+    _dev(state, packed)
+    if state.numel() * 4 < state_bytes(B, H, d_feat, d_v) or packed.numel() * 4 < packed_state_bytes(B, H, d_feat, d_v):
+        raise ValueError("state buffer too small")
+    _check(lib.based_state_pack(_ptr(state), _ptr(packed), B, H, d_feat, d_v, _stream()), "based_state_pack")
+    return packed
+
+
+def state_unpack(packed, state, B, H, d_feat, d_v):
+    """based_state_unpack: packed state buffer -> state buffer."""
+    _dev(state, packed)
+    if state.numel() * 4 < state_bytes(B, H, d_feat, d_v) or packed.numel() * 4 < packed_state_bytes(B, H, d_feat, d_v):
+        raise ValueError("state buffer too small")
+    _check(lib.based_state_unpack(_ptr(packed), _ptr(state), B, H, d_feat, d_v, _stream()), "based_state_unpack")
+    return state
+
+
+def decode_step(q, k, v, state, y=None, packed=False):
+    """based_decode_step (``packed=True``: based_decode_step_packed on a packed state).
+    q, k ``[B,H,d']``; v ``[B,H,d_v]``; state updated in place."""
     _dev(q, k, v, y, state)
     B, H, dp = q.shape
     dv = v.shape[-1]
     if k.shape != q.shape or tuple(v.shape[:2]) != (B, H) or k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("q, k, v shapes / dtypes disagree")
-    if state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv):
+    need = packed_state_bytes(B, H, dp, dv) if packed else state_bytes(B, H, dp, dv)
+    if state.dtype != torch.float32 or state.numel() * 4 < need:
         raise ValueError("state buffer too small or not fp32")
     if y is None:
         y = torch.empty_like(v)
-    _check(lib.based_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), B, H, dp, dv,
-                                 _dtype_code(q), _stream()), "based_decode_step")
+    fn = lib.based_decode_step_packed if packed else lib.based_decode_step
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), B, H, dp, dv, _dtype_code(q), _stream()),
+           "based_decode_step_packed" if packed else "based_decode_step")
     return y
 
 
@@ -240,8 +289,9 @@ def swa_decode(q, k, v, ring, pos: int, w: int, scale: float, y=None):
 
 
 def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, scale: float,
-                 y_lin=None, y_swa=None):
-    """based_decode_fused: both decode steps in one launch; returns ``(y_lin, y_swa)``."""
+                 y_lin=None, y_swa=None, packed=False):
+    """based_decode_fused (``packed=True``: based_decode_fused_packed): both decode steps in one
+    launch; returns ``(y_lin, y_swa)``."""
     _dev(q, k, v, state, swa_q, swa_k, swa_v, ring, y_lin, y_swa)
     B, H, dp = q.shape
     dv = v.shape[-1]
@@ -253,7 +303,8 @@ def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, sc
     for t in (k, v, swa_q, swa_k, swa_v, ring):
         if t.dtype != q.dtype:
             raise ValueError("dtypes disagree")
-    if state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv):
+    need = packed_state_bytes(B, H, dp, dv) if packed else state_bytes(B, H, dp, dv)
+    if state.dtype != torch.float32 or state.numel() * 4 < need:
         raise ValueError("state buffer too small or not fp32")
     if ring.numel() != B * H * 2 * w * dh:
         raise ValueError("ring must be [B,H,2,w,d_h]")
@@ -261,8 +312,9 @@ def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, sc
         y_lin = torch.empty_like(v)
     if y_swa is None:
         y_swa = torch.empty_like(swa_v)
-    _check(lib.based_decode_fused(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), dp, dv,
-                                  _ptr(swa_q), _ptr(swa_k), _ptr(swa_v), _ptr(y_swa), _ptr(ring),
-                                  int(pos), dh, int(w), float(scale), B, H, _dtype_code(q), _stream()),
-           "based_decode_fused")
+    fn = lib.based_decode_fused_packed if packed else lib.based_decode_fused
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), dp, dv, _ptr(swa_q), _ptr(swa_k),
+              _ptr(swa_v), _ptr(y_swa), _ptr(ring), int(pos), dh, int(w), float(scale), B, H,
+              _dtype_code(q), _stream()),
+           "based_decode_fused_packed" if packed else "based_decode_fused")
     return y_lin, y_swa

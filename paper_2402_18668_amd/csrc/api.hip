@@ -105,7 +105,51 @@ int based_decode_step(const void *q, const void *k, const void *v, void *y, void
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
-                                        dtype, (hipStream_t)stream));
+                                        dtype, 0, (hipStream_t)stream));
+}
+
+int based_packed_feature_dim(int d_feat) { return d_feat >= 1 ? packed_feature_dim(d_feat) : 0; }
+
+size_t based_packed_state_stride_floats(int d_feat, int d_v)
+{
+    return ok_lin_dims(d_feat, d_v) ? packed_state_stride(d_feat, d_v) : 0;
+}
+
+size_t based_packed_state_bytes(int B, int H, int d_feat, int d_v)
+{
+    if (!ok_lin_dims(d_feat, d_v) || !ok_counts(B, H, 1)) return 0;
+    return (size_t)B * H * packed_state_stride(d_feat, d_v) * sizeof(float);
+}
+
+int based_state_pack(const void *state, void *packed, int B, int H, int d_feat, int d_v, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(state) || !ok_ptr(packed)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_state_repack(const_cast<float *>(static_cast<const float *>(state)),
+                                         static_cast<float *>(packed), B * H, d_feat, d_v, 1,
+                                         (hipStream_t)stream));
+}
+
+int based_state_unpack(const void *packed, void *state, int B, int H, int d_feat, int d_v, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(state) || !ok_ptr(packed)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_state_repack(static_cast<float *>(state),
+                                         const_cast<float *>(static_cast<const float *>(packed)), B * H,
+                                         d_feat, d_v, 0, (hipStream_t)stream));
+}
+
+int based_decode_step_packed(const void *q, const void *k, const void *v, void *y, void *packed, int B,
+                             int H, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(packed))
+        return BASED_ERR_INVALID_ARG;
+    return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(packed), B * H, d_feat, d_v,
+                                        dtype, 1, (hipStream_t)stream));
 }
 
 size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype)
@@ -147,10 +191,10 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
                                        (hipStream_t)stream));
 }
 
-int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin, void *state,
-                       int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
-                       void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
-                       int dtype, void *stream)
+static int decode_fused_any(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                            int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
+                            void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
+                            int dtype, int packed, void *stream)
 {
     if (!ok_counts(B, H, 1) || pos < 1) return BASED_ERR_INVALID_ARG;
     if (!ok_lin_dims(d_feat, d_v) || !ok_swa_dims(d_h, w) || !ok_dtype(dtype))
@@ -161,7 +205,25 @@ int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
     if ((unsigned long long)B * H * 2ull >= (1ull << 31)) return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_fused(q, k, v, y_lin, static_cast<float *>(state), d_feat, d_v,
                                          swa_q, swa_k, swa_v, y_swa, ring, pos, d_h, w, scale, B * H,
-                                         dtype, (hipStream_t)stream));
+                                         dtype, packed, (hipStream_t)stream));
+}
+
+int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                       int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
+                       void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
+                       int dtype, void *stream)
+{
+    return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring, pos, d_h,
+                            w, scale, B, H, dtype, 0, stream);
+}
+
+int based_decode_fused_packed(const void *q, const void *k, const void *v, void *y_lin, void *packed,
+                              int d_feat, int d_v, const void *swa_q, const void *swa_k,
+                              const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
+                              float scale, int B, int H, int dtype, void *stream)
+{
+    return decode_fused_any(q, k, v, y_lin, packed, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring, pos, d_h,
+                            w, scale, B, H, dtype, 1, stream);
 }
 
 }  // extern "C"

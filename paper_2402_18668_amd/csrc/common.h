@@ -38,6 +38,19 @@ __host__ __device__ constexpr size_t state_stride(int dp, int dv)
     return ((size_t)feature_dim(dp) * dv + feature_dim(dp) + 63) / 64 * 64;
 }
 
+// Packed state variant: one row per unordered feature pair (the rows (a, b) and (b, a) of Eq. 4 are
+// equal).  Row 0 constant, 1 + a linear, 1 + d' + tri(a, b) for a <= b with
+// tri(a, b) = a d' - a (a - 1) / 2 + (b - a); the stored value is the canonical row (a, b).
+__host__ __device__ constexpr int packed_feature_dim(int dp) { return 1 + dp + dp * (dp + 1) / 2; }
+__host__ __device__ constexpr size_t packed_state_stride(int dp, int dv)
+{
+    return ((size_t)packed_feature_dim(dp) * dv + packed_feature_dim(dp) + 63) / 64 * 64;
+}
+__host__ __device__ constexpr int packed_pair_row(int dp, int a, int b)   // a <= b
+{
+    return 1 + dp + a * dp - a * (a - 1) / 2 + (b - a);
+}
+
 // Sum over the 64 lanes of a wave; every lane gets the total.
 __device__ __forceinline__ float wave_sum(float x)
 {
@@ -62,7 +75,7 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
                                int has_init, void *workspace, int U, int N, int dp, int dv,
                                hipStream_t s);
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
-                              int U, int dp, int dv, int dtype, hipStream_t s);
+                              int U, int dp, int dv, int dtype, int packed, hipStream_t s);
 hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
                                   int dh, int w, float scale, int dtype, hipStream_t s);
 bool swa_prefill_mfma_supported(int dh, int w, int dtype);
@@ -75,8 +88,11 @@ hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *
 hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                                float *state, int dp, int dv, const void *sq, const void *sk,
                                const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
-                               float scale, int U, int dtype, hipStream_t s);
+                               float scale, int U, int dtype, int packed, hipStream_t s);
 hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, int dv, int to_state,
                              hipStream_t s);
+// canonical state buffer <-> packed state buffer (to_packed: symmetric part; else both rows of a pair)
+hipError_t launch_state_repack(float *state, float *packed, int U, int dp, int dv, int to_packed,
+                               hipStream_t s);
 
 }  // namespace based

@@ -15,12 +15,15 @@ constexpr int kDecodeThreads = 256;
 // ---------------------------------------------------------------------------------------------
 // Linear attention: z += phi(k); S += phi(k) v^T; y = phi(q) S / (phi(q).z)      one unit / block
 // ---------------------------------------------------------------------------------------------
-template <int DP, int DV, typename T>
+// PACKED: the state holds one row per unordered feature pair (packed_feature_dim rows); the k side
+// of a pair row is k_a k_b / sqrt(2) (the canonical row), the q side sqrt(2) q_a q_b for a < b (the
+// pair occurs twice in the sum over ordered pairs) and q_a^2 / sqrt(2) for a = b.
+template <int DP, int DV, typename T, bool PACKED>
 __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const T *__restrict__ k,
                                                  const T *__restrict__ v, T *__restrict__ y,
                                                  float *__restrict__ state, int u)
 {
-    constexpr int D = feature_dim(DP);
+    constexpr int D = PACKED ? packed_feature_dim(DP) : feature_dim(DP);
     constexpr int NT = kDecodeThreads;
     constexpr int LPR = DV / 4;      // lanes per state row (float4 each)
     constexpr int RPS = NT / LPR;    // rows per sweep step
@@ -40,7 +43,7 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
     __shared__ float dred[NT / 64];
 
     const int tid = threadIdx.x;
-    float *Su = state + (size_t)u * state_stride(DP, DV);
+    float *Su = state + (size_t)u * (PACKED ? packed_state_stride(DP, DV) : state_stride(DP, DV));
     float *zu = Su + (size_t)D * DV;
 
     if (tid < DP) {
@@ -75,8 +78,17 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
         if (f == 0) { a = 1.f; b = 1.f; }
         else if (f <= DP) { a = qs[f - 1]; b = ks[f - 1]; }
         else if (f < D) {
-            const int i = (f - 1 - DP) / DP, j = (f - 1 - DP) % DP;
-            a = qs[i] * qs[j] * kRsqrt2; b = ks[i] * ks[j] * kRsqrt2;
+            int i, j;
+            if (PACKED) {
+                int t = f - 1 - DP;   // row i of the triangle holds the DP - i pairs (i, i .. DP - 1)
+                i = 0;
+                while (t >= DP - i) { t -= DP - i; ++i; }
+                j = i + t;
+            } else {
+                i = (f - 1 - DP) / DP; j = (f - 1 - DP) % DP;
+            }
+            b = ks[i] * ks[j] * kRsqrt2;
+            a = qs[i] * qs[j] * ((PACKED && i != j) ? 1.41421356237309504880f : kRsqrt2);
         } else { a = 0.f; b = 0.f; }
         pq[f] = a; pk[f] = b;
     }
@@ -272,11 +284,11 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
 // ---------------------------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------------------------
-template <int DP, int DV, typename T>
+template <int DP, int DV, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q, const T *k,
                                                                      const T *v, T *y, float *state)
 {
-    decode_step_body<DP, DV, T>(q, k, v, y, state, blockIdx.x);
+    decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state, blockIdx.x);
 }
 
 template <int DH, int W, typename T>
@@ -289,13 +301,13 @@ __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, 
 
 // Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
 // the window attention step.  (Interleaving the two kinds block by block measured 15 % slower.)
-template <int DP, int DV, int DH, int W, typename T>
+template <int DP, int DV, int DH, int W, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
     const T *q, const T *k, const T *v, T *y_lin, float *state, const T *sq, const T *sk,
     const T *sv, T *y_swa, T *ring, int pos, float scale, int U)
 {
     if ((int)blockIdx.x < U)
-        decode_step_body<DP, DV, T>(q, k, v, y_lin, state, blockIdx.x);
+        decode_step_body<DP, DV, T, PACKED>(q, k, v, y_lin, state, blockIdx.x);
     else
         swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, blockIdx.x - U);
 }
@@ -311,18 +323,24 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
         else { CALL(a1, b1); }                                    \
     } while (0)
 
+template <int DP, int DV, typename T>
+static void step_pick(const void *q, const void *k, const void *v, void *y, float *state, int U,
+                      int packed, hipStream_t s)
+{
+    if (packed)
+        hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, true>), dim3(U), dim3(kDecodeThreads), 0, s,
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state);
+    else
+        hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, false>), dim3(U), dim3(kDecodeThreads), 0, s,
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state);
+}
+
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
-                              int U, int dp, int dv, int dtype, hipStream_t s)
+                              int U, int dp, int dv, int dtype, int packed, hipStream_t s)
 {
 #define CALL_LIN(DP_, DV_)                                                                        \
-    if (dtype == BASED_F32)                                                                       \
-        hipLaunchKernelGGL((decode_step_kernel<DP_, DV_, float>), dim3(U), dim3(kDecodeThreads),  \
-                           0, s, (const float *)q, (const float *)k, (const float *)v,            \
-                           (float *)y, state);                                                    \
-    else                                                                                          \
-        hipLaunchKernelGGL((decode_step_kernel<DP_, DV_, bf16_t>), dim3(U), dim3(kDecodeThreads), \
-                           0, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,         \
-                           (bf16_t *)y, state)
+    if (dtype == BASED_F32) step_pick<DP_, DV_, float>(q, k, v, y, state, U, packed, s);          \
+    else step_pick<DP_, DV_, bf16_t>(q, k, v, y, state, U, packed, s)
     BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_LIN);
 #undef CALL_LIN
     return hipGetLastError();
@@ -345,13 +363,13 @@ hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *
     return hipGetLastError();
 }
 
-template <int DP, int DV, typename T>
+template <int DP, int DV, typename T, bool PACKED>
 static void fused_pick(const void *q, const void *k, const void *v, void *y_lin, float *state,
                        const void *sq, const void *sk, const void *sv, void *y_swa, void *ring,
                        int pos, int dh, int w, float scale, int U, hipStream_t s)
 {
 #define CALL_F(DH_, W_)                                                                           \
-    hipLaunchKernelGGL((decode_fused_kernel<DP, DV, DH_, W_, T>), dim3(2 * U),                    \
+    hipLaunchKernelGGL((decode_fused_kernel<DP, DV, DH_, W_, T, PACKED>), dim3(2 * U),            \
                        dim3(kDecodeThreads), 0, s, (const T *)q, (const T *)k, (const T *)v,      \
                        (T *)y_lin, state, (const T *)sq, (const T *)sk, (const T *)sv,            \
                        (T *)y_swa, (T *)ring, pos, scale, U)
@@ -362,16 +380,19 @@ static void fused_pick(const void *q, const void *k, const void *v, void *y_lin,
 hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                                float *state, int dp, int dv, const void *sq, const void *sk,
                                const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
-                               float scale, int U, int dtype, hipStream_t s)
+                               float scale, int U, int dtype, int packed, hipStream_t s)
 {
+#define FUSED_ARGS q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w, scale, U, s
 #define CALL_L(DP_, DV_)                                                                          \
-    if (dtype == BASED_F32)                                                                       \
-        fused_pick<DP_, DV_, float>(q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w,   \
-                                    scale, U, s);                                                 \
-    else                                                                                          \
-        fused_pick<DP_, DV_, bf16_t>(q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w,  \
-                                     scale, U, s)
+    if (dtype == BASED_F32) {                                                                     \
+        if (packed) fused_pick<DP_, DV_, float, true>(FUSED_ARGS);                                \
+        else fused_pick<DP_, DV_, float, false>(FUSED_ARGS);                                      \
+    } else {                                                                                      \
+        if (packed) fused_pick<DP_, DV_, bf16_t, true>(FUSED_ARGS);                               \
+        else fused_pick<DP_, DV_, bf16_t, false>(FUSED_ARGS);                                     \
+    }
     BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_L);
+#undef FUSED_ARGS
 #undef CALL_L
     return hipGetLastError();
 }

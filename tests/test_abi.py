@@ -40,6 +40,13 @@ def test_size_queries(based):
     assert based.swa_ring_bytes(2, 3, 48, 128, based.BF16) == 0
     assert based.prefill_workspace_bytes(1, 1, 100, 16, 64, based.F32) >= 0
     assert based.lib.based_version() >= 100
+    # packed state: the paper's own state-size count (one row per unordered feature pair)
+    assert based.lib.based_packed_feature_dim(16) == 153 and based.lib.based_packed_feature_dim(32) == 561
+    assert based.lib.based_packed_feature_dim(0) == 0
+    pstride = based.lib.based_packed_state_stride_floats(16, 128)
+    assert pstride % 64 == 0 and pstride >= 153 * 129
+    assert based.packed_state_bytes(2, 3, 16, 128) == 6 * pstride * 4
+    assert based.packed_state_bytes(2, 3, 16, 100) == 0
     assert based.strerror(0) == "ok" and "unknown" in based.strerror(77)
 
 
@@ -72,6 +79,12 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_decode_fused(p, p, p, p, p, 16, 64, p, p, p, p, p, 0, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_decode_fused(p, p, p, p, p, 16, 64, p, p, p, p, null, 1, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_decode_fused(p, p, p, p, p, 8, 64, p, p, p, p, p, 1, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_UNSUPPORTED
+    # packed-state variant
+    assert lib.based_decode_step_packed(p, p, p, p, null, 1, 1, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_step_packed(p, p, p, p, p, 1, 1, 16, 32, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_decode_fused_packed(p, p, p, p, p, 16, 64, p, p, p, p, p, 0, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_state_pack(p, null, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
+    assert lib.based_state_unpack(p, p, 1, 1, 12, 64, st) == based.ERR_UNSUPPORTED
     # state copies
     assert lib.based_state_export(null, p, p, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_import(p, p, p, 1, 1, 16, 100, st) == based.ERR_UNSUPPORTED

@@ -445,3 +445,73 @@ def test_prefill_graph_replay(based):
         y2 = based.prefill(tq, tk, tv, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(y2, y_eager)
+
+
+# ------------------------------------------------------------------------------------------------
+# packed state (one row per unordered feature pair)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 32, 64), ("f32", 32, 128)])
+def test_decode_steps_packed_state(based, dtype, dp, dv):
+    """Decode on the packed state gives the oracle's rows; unpacking it gives the oracle's state."""
+    wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, N0, T = 2, 3, 40, 12
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N0)
+    dec = synth.decode_inputs(wl, T, units=U)
+    S, z = oracle.linattn_state(k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    based.state_import(state, up(S, "f32", (B, H, S.shape[1], dv)), up(z, "f32", (B, H, z.shape[1])), dp)
+    packed = based.alloc_packed_state(B, H, dp, dv)
+    based.state_pack(state, packed, B, H, dp, dv)
+    # round trip through the packed layout is exact for a state of the recurrence
+    back = based.alloc_state(B, H, dp, dv)
+    based.state_unpack(packed, back, B, H, dp, dv)
+    torch.cuda.synchronize()
+    assert torch.equal(back, state)
+    Sd, zd = S.astype(np.float32).astype(np.float64), z.astype(np.float32).astype(np.float64)
+    for t in range(T):
+        qt, kt, vt = dec["q"][t], dec["k"][t], dec["v"][t]
+        y = based.decode_step(up(qt, dtype, (B, H, dp)), up(kt, dtype, (B, H, dp)), up(vt, dtype, (B, H, dv)),
+                              packed, packed=True)
+        yw, Sd, zd = oracle.linattn_recurrent(qt[:, None], kt[:, None], vt[:, None], Sd, zd)
+        check_close(down(y).reshape(U, dv), yw[:, 0], TOL[dtype], f"packed decode step {t}")
+    based.state_unpack(packed, back, B, H, dp, dv)
+    Sg, zg = based.state_export(back, B, H, dp, dv)
+    check_close(down(Sg).reshape(Sd.shape), Sd, TOL["f32"], "packed decode final S")
+    check_close(down(zg).reshape(zd.shape), zd, TOL["f32"], "packed decode final z")
+
+
+def test_decode_fused_packed_equals_separate(based):
+    wl = make_wl("decode_1p3b", dtype="bf16")
+    B, H, N0, T = 2, 2, 70, 4
+    dp, dv, dh, w = wl.d_feat, wl.d_v, wl.d_h, wl.w
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N0)
+    sq, sk, sv = synth.swa_inputs(wl, units=U, N=N0)
+    dec = synth.decode_inputs(wl, T, units=U)
+    scale = 1.0 / math.sqrt(dh)
+
+    def fresh():
+        state = based.alloc_state(B, H, dp, dv)
+        run_prefill(based, wl, B, H, N0, q, k, v, state=state)
+        packed = based.alloc_packed_state(B, H, dp, dv)
+        based.state_pack(state, packed, B, H, dp, dv)
+        ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+        based.swa_prefill(up(sq, "bf16", (B, H, N0, dh)), up(sk, "bf16", (B, H, N0, dh)),
+                          up(sv, "bf16", (B, H, N0, dh)), w, scale, ring=ring)
+        return packed, ring
+
+    pa, ra = fresh()
+    pb, rb = fresh()
+    cat = lambda a, b: np.concatenate([a, b.transpose(1, 0, 2)], axis=1)
+    want_lin = oracle.linattn_rows(cat(q, dec["q"]), cat(k, dec["k"]), cat(v, dec["v"]), np.arange(N0, N0 + T))
+    for t in range(T):
+        args = [up(dec[n][t], "bf16", (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+        y1 = based.decode_step(args[0], args[1], args[2], pa, packed=True)
+        y2 = based.swa_decode(args[3], args[4], args[5], ra, N0 + t + 1, w, scale)
+        f1, f2 = based.decode_fused(args[0], args[1], args[2], pb, args[3], args[4], args[5], rb,
+                                    N0 + t + 1, w, scale, packed=True)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, f1) and torch.equal(y2, f2)
+        check_close(down(f1).reshape(U, dv), want_lin[:, t], TOL["bf16"], f"fused packed lin step {t}")
+    assert torch.equal(pa, pb) and torch.equal(ra, rb)
