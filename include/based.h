@@ -5,7 +5,8 @@
  *
  * General contract (all entry points)
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
- *     allocates, frees or keeps device memory, and keeps no global state.
+ *     allocates, frees or keeps device memory.  Its only process-wide state is a counter of
+ *     segmented prefill calls, used to tag the ready flags it keeps in the caller's workspace.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on it and never synchronise; buffers must stay alive until the work
  *     has run.
@@ -95,7 +96,11 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
  *          the two rows and writes both rows equal.  For a state produced by this library, or
  *          imported from the canonical arrays of such a state, that changes nothing.
  *   workspace  scratch of at least based_prefill_workspace_bytes(...) bytes, 256-byte aligned;
- *          may be NULL when that size is 0.  Contents on return are unspecified.
+ *          may be NULL when that size is 0.  Contents on return are unspecified and need no
+ *          initialisation.  For few units and long sequences the sequence is cut into segments
+ *          that run side by side in one launch; workgroups then hand state increments to each
+ *          other through the workspace and wait for them with a bounded number of polls (about
+ *          a second), after which they proceed: a launch always terminates.
  *
  * Calls sharing a workspace or a state buffer must be ordered on one stream.
  */

@@ -39,9 +39,10 @@
 // accumulator tile), i.e. sum k_a k_b, sum k_a and the token count; phi(q).z =
 // count + q.z1 + q^T M q / 2 is evaluated with two small MFMAs (M' split into bf16 hi + lo).
 //
-// Long sequences / few units: the sequence is cut into G segments; a first launch computes each
-// segment's state increment (update GEMMs only), and the main launch starts each segment from
-// the sum of the increments before it.
+// Long sequences / few units: the sequence is cut into G segments.  Update-only workgroups compute
+// each segment's state increment, and the main-pass workgroup of a segment starts from the sum of
+// the increments before it.  Both kinds run in one launch: the increment workgroups come first in
+// the grid, the main-pass workgroups wait (bounded) on per-entry ready flags in the workspace.
 #include "common.h"
 
 #include <atomic>
@@ -221,7 +222,7 @@ struct SegTable { int begin[kMaxSegments + 1]; };
 // MODE 0: full prefill of the segment (readout + update); starts from the sum of workspace entries.
 // MODE 1: state increment of the segment only (update GEMMs), written to workspace entry 1 + seg.
 // MODE 2: the caller's initial state, converted to accumulator layout, written to entry 0.
-// The main launch never reads the caller's state buffer, so writing the final state back into it
+// The main pass never reads the caller's state buffer, so writing the final state back into it
 // cannot race with another workgroup still starting up.
 // FUSED: the increments and the main pass run in ONE launch.  Increment workgroups come first in the
 // grid and wait for nothing; a main-pass workgroup of segment g > 0 waits (bounded) for the flags
@@ -876,9 +877,9 @@ int pick_segments(int U, int N, int dv)
     return G;
 }
 
-// Segment boundaries.  The main launch starts segment g by summing g workspace entries (about 0.6
+// Segment boundaries.  The main pass starts segment g by summing g workspace entries (about 0.6
 // of a chunk's time each) and the last segment also writes the final state, so later segments
-// get fewer chunks: all workgroups of the main launch, which run side by side, end together.
+// get fewer chunks, so that the main-pass workgroups, which run side by side, end close together.
 // Returns the number of segments actually used (a short sequence may leave trailing ones empty).
 int make_segments(int N, int G, SegTable &t)
 {
