@@ -185,6 +185,22 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
                               const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
                               float scale, int B, int H, int dtype, void *stream);
 
+/*
+ * Ragged batches: the position of the decoded token is read per batch element from DEVICE memory
+ * (pos[b] for all heads of sequence b; int32).  pos[b] >= 1 as in based_swa_decode; pos[b] < 1
+ * marks a sequence that does not take part in the step: its ring and state are left untouched and
+ * its y rows are written as zeros.  Because the positions live in device memory, a captured launch
+ * (HIP graph) can be replayed for token after token while another kernel advances pos.
+ * based_decode_fused_ragged: packed != 0 selects the packed state layout.
+ */
+int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
+                            const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
+                            void *stream);
+int based_decode_fused_ragged(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                              int packed, int d_feat, int d_v, const void *swa_q, const void *swa_k,
+                              const void *swa_v, void *y_swa, void *ring, const int *pos, int d_h, int w,
+                              float scale, int B, int H, int dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,6 +26,7 @@ EXPORTS = [
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
+    "based_swa_decode_ragged", "based_decode_fused_ragged",
 ]
 
 
@@ -82,6 +83,10 @@ def _load() -> ctypes.CDLL:
     lib.based_decode_step_packed.argtypes = lib.based_decode_step.argtypes
     lib.based_decode_fused_packed.restype = i
     lib.based_decode_fused_packed.argtypes = lib.based_decode_fused.argtypes
+    lib.based_swa_decode_ragged.restype = i
+    lib.based_swa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
+    lib.based_decode_fused_ragged.restype = i
+    lib.based_decode_fused_ragged.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, f, i, i, i, vp]
     return lib
 
 
@@ -273,8 +278,14 @@ def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
     return y
 
 
-def swa_decode(q, k, v, ring, pos: int, w: int, scale: float, y=None):
-    """based_swa_decode.  q, k, v ``[B,H,d_h]``; ring updated in place."""
+def _check_pos(pos, B):
+    if pos.dtype != torch.int32 or pos.numel() != B or not pos.is_cuda or not pos.is_contiguous():
+        raise ValueError("per-sequence positions must be a contiguous int32 device tensor of B elements")
+
+
+def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None):
+    """based_swa_decode (``pos`` an int) or based_swa_decode_ragged (``pos`` an int32 device tensor
+    ``[B]``).  q, k, v ``[B,H,d_h]``; ring updated in place."""
     _dev(q, k, v, y, ring)
     B, H, dh = q.shape
     if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
@@ -283,12 +294,18 @@ def swa_decode(q, k, v, ring, pos: int, w: int, scale: float, y=None):
         raise ValueError("ring must be [B,H,2,w,d_h] of the input dtype")
     if y is None:
         y = torch.empty_like(v)
+    if isinstance(pos, torch.Tensor):   # per-sequence positions in device memory
+        _check_pos(pos, B)
+        _check(lib.based_swa_decode_ragged(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), _ptr(pos), B, H, dh,
+                                           int(w), float(scale), _dtype_code(q), _stream()),
+               "based_swa_decode_ragged")
+        return y
     _check(lib.based_swa_decode(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), int(pos), B, H, dh,
                                 int(w), float(scale), _dtype_code(q), _stream()), "based_swa_decode")
     return y
 
 
-def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, scale: float,
+def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos, w: int, scale: float,
                  y_lin=None, y_swa=None, packed=False):
     """based_decode_fused (``packed=True``: based_decode_fused_packed): both decode steps in one
     launch; returns ``(y_lin, y_swa)``."""
@@ -312,6 +329,13 @@ def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos: int, w: int, sc
         y_lin = torch.empty_like(v)
     if y_swa is None:
         y_swa = torch.empty_like(swa_v)
+    if isinstance(pos, torch.Tensor):   # per-sequence positions in device memory
+        _check_pos(pos, B)
+        _check(lib.based_decode_fused_ragged(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), int(bool(packed)),
+                                             dp, dv, _ptr(swa_q), _ptr(swa_k), _ptr(swa_v), _ptr(y_swa), _ptr(ring),
+                                             _ptr(pos), dh, int(w), float(scale), B, H, _dtype_code(q), _stream()),
+               "based_decode_fused_ragged")
+        return y_lin, y_swa
     fn = lib.based_decode_fused_packed if packed else lib.based_decode_fused
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), dp, dv, _ptr(swa_q), _ptr(swa_k),
               _ptr(swa_v), _ptr(y_swa), _ptr(ring), int(pos), dh, int(w), float(scale), B, H,

@@ -180,10 +180,10 @@ int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void
     return status_of(e);
 }
 
-int based_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring, int pos, int B,
-                     int H, int d_h, int w, float scale, int dtype, void *stream)
+static int swa_decode_any(const void *q, const void *k, const void *v, void *y, void *ring, PosArg pos,
+                          int B, int H, int d_h, int w, float scale, int dtype, void *stream)
 {
-    if (!ok_counts(B, H, 1) || pos < 1) return BASED_ERR_INVALID_ARG;
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
     if (!ok_swa_dims(d_h, w) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(ring))
         return BASED_ERR_INVALID_ARG;
@@ -191,12 +191,27 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
                                        (hipStream_t)stream));
 }
 
+int based_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring, int pos, int B,
+                     int H, int d_h, int w, float scale, int dtype, void *stream)
+{
+    if (pos < 1) return BASED_ERR_INVALID_ARG;
+    return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H}, B, H, d_h, w, scale, dtype, stream);
+}
+
+int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
+                            const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
+                            void *stream)
+{
+    if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u)) return BASED_ERR_INVALID_ARG;
+    return swa_decode_any(q, k, v, y, ring, PosArg{0, pos, H}, B, H, d_h, w, scale, dtype, stream);
+}
+
 static int decode_fused_any(const void *q, const void *k, const void *v, void *y_lin, void *state,
                             int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
-                            void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
+                            void *y_swa, void *ring, PosArg pos, int d_h, int w, float scale, int B, int H,
                             int dtype, int packed, void *stream)
 {
-    if (!ok_counts(B, H, 1) || pos < 1) return BASED_ERR_INVALID_ARG;
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
     if (!ok_lin_dims(d_feat, d_v) || !ok_swa_dims(d_h, w) || !ok_dtype(dtype))
         return BASED_ERR_UNSUPPORTED;
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y_lin) || !ok_ptr(state) || !ok_ptr(swa_q) ||
@@ -213,8 +228,9 @@ int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                        void *y_swa, void *ring, int pos, int d_h, int w, float scale, int B, int H,
                        int dtype, void *stream)
 {
-    return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring, pos, d_h,
-                            w, scale, B, H, dtype, 0, stream);
+    if (pos < 1) return BASED_ERR_INVALID_ARG;
+    return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
+                            PosArg{pos, nullptr, H}, d_h, w, scale, B, H, dtype, 0, stream);
 }
 
 int based_decode_fused_packed(const void *q, const void *k, const void *v, void *y_lin, void *packed,
@@ -222,8 +238,19 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
                               const void *swa_v, void *y_swa, void *ring, int pos, int d_h, int w,
                               float scale, int B, int H, int dtype, void *stream)
 {
-    return decode_fused_any(q, k, v, y_lin, packed, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring, pos, d_h,
-                            w, scale, B, H, dtype, 1, stream);
+    if (pos < 1) return BASED_ERR_INVALID_ARG;
+    return decode_fused_any(q, k, v, y_lin, packed, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
+                            PosArg{pos, nullptr, H}, d_h, w, scale, B, H, dtype, 1, stream);
+}
+
+int based_decode_fused_ragged(const void *q, const void *k, const void *v, void *y_lin, void *state,
+                              int packed, int d_feat, int d_v, const void *swa_q, const void *swa_k,
+                              const void *swa_v, void *y_swa, void *ring, const int *pos, int d_h, int w,
+                              float scale, int B, int H, int dtype, void *stream)
+{
+    if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u)) return BASED_ERR_INVALID_ARG;
+    return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
+                            PosArg{0, pos, H}, d_h, w, scale, B, H, dtype, packed ? 1 : 0, stream);
 }
 
 }  // extern "C"

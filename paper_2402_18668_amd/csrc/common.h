@@ -83,11 +83,18 @@ hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, 
                                    int N, int dh, int w, float scale, hipStream_t s);
 hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, int U, int N, int dh, int w,
                                 int dtype, hipStream_t s);
+// Position of the decoded token: one value for every sequence, or (per_seq != NULL) one per batch
+// element in device memory, where a value < 1 marks a sequence that does not take part in the step.
+struct PosArg {
+    int pos;
+    const int *per_seq;
+    int H;
+};
 hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
-                             int pos, int U, int dh, int w, float scale, int dtype, hipStream_t s);
+                             PosArg pos, int U, int dh, int w, float scale, int dtype, hipStream_t s);
 hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                                float *state, int dp, int dv, const void *sq, const void *sk,
-                               const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
+                               const void *sv, void *y_swa, void *ring, PosArg pos, int dh, int w,
                                float scale, int U, int dtype, int packed, hipStream_t s);
 hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, int dv, int to_state,
                              hipStream_t s);

@@ -12,6 +12,18 @@ namespace based {
 
 constexpr int kDecodeThreads = 256;
 
+__device__ __forceinline__ int resolve_pos(const PosArg &p, int u)
+{
+    return p.per_seq ? p.per_seq[u / p.H] : p.pos;
+}
+
+// y of a sequence that does not take part in the step
+template <typename T>
+__device__ __forceinline__ void zero_row(T *y, int n)
+{
+    for (int i = threadIdx.x; i < n; i += kDecodeThreads) y[i] = from_f32<T>(0.f);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Linear attention: z += phi(k); S += phi(k) v^T; y = phi(q) S / (phi(q).z)      one unit / block
 // ---------------------------------------------------------------------------------------------
@@ -294,9 +306,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q,
 template <int DH, int W, typename T>
 __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, const T *k,
                                                                     const T *v, T *y, T *ring,
-                                                                    int pos, float scale)
+                                                                    PosArg pa, float scale)
 {
-    swa_decode_body<DH, W, T>(q, k, v, y, ring, pos, scale, blockIdx.x);
+    const int u = blockIdx.x, pos = resolve_pos(pa, u);
+    if (pos < 1) { zero_row(y + (size_t)u * DH, DH); return; }
+    swa_decode_body<DH, W, T>(q, k, v, y, ring, pos, scale, u);
 }
 
 // Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
@@ -304,12 +318,20 @@ __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, 
 template <int DP, int DV, int DH, int W, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
     const T *q, const T *k, const T *v, T *y_lin, float *state, const T *sq, const T *sk,
-    const T *sv, T *y_swa, T *ring, int pos, float scale, int U)
+    const T *sv, T *y_swa, T *ring, PosArg pa, float scale, int U)
 {
-    if ((int)blockIdx.x < U)
-        decode_step_body<DP, DV, T, PACKED>(q, k, v, y_lin, state, blockIdx.x);
+    const bool lin = (int)blockIdx.x < U;
+    const int u = lin ? blockIdx.x : blockIdx.x - U;
+    const int pos = resolve_pos(pa, u);
+    if (pos < 1) {
+        if (lin) zero_row(y_lin + (size_t)u * DV, DV);
+        else zero_row(y_swa + (size_t)u * DH, DH);
+        return;
+    }
+    if (lin)
+        decode_step_body<DP, DV, T, PACKED>(q, k, v, y_lin, state, u);
     else
-        swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, blockIdx.x - U);
+        swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -347,7 +369,7 @@ hipError_t launch_decode_step(const void *q, const void *k, const void *v, void 
 }
 
 hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
-                             int pos, int U, int dh, int w, float scale, int dtype, hipStream_t s)
+                             PosArg pos, int U, int dh, int w, float scale, int dtype, hipStream_t s)
 {
 #define CALL_SWA(DH_, W_)                                                                         \
     if (dtype == BASED_F32)                                                                       \
@@ -366,7 +388,7 @@ hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *
 template <int DP, int DV, typename T, bool PACKED>
 static void fused_pick(const void *q, const void *k, const void *v, void *y_lin, float *state,
                        const void *sq, const void *sk, const void *sv, void *y_swa, void *ring,
-                       int pos, int dh, int w, float scale, int U, hipStream_t s)
+                       PosArg pos, int dh, int w, float scale, int U, hipStream_t s)
 {
 #define CALL_F(DH_, W_)                                                                           \
     hipLaunchKernelGGL((decode_fused_kernel<DP, DV, DH_, W_, T, PACKED>), dim3(2 * U),            \
@@ -379,7 +401,7 @@ static void fused_pick(const void *q, const void *k, const void *v, void *y_lin,
 
 hipError_t launch_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
                                float *state, int dp, int dv, const void *sq, const void *sk,
-                               const void *sv, void *y_swa, void *ring, int pos, int dh, int w,
+                               const void *sv, void *y_swa, void *ring, PosArg pos, int dh, int w,
                                float scale, int U, int dtype, int packed, hipStream_t s)
 {
 #define FUSED_ARGS q, k, v, y_lin, state, sq, sk, sv, y_swa, ring, pos, dh, w, scale, U, s

@@ -515,3 +515,85 @@ def test_decode_fused_packed_equals_separate(based):
         assert torch.equal(y1, f1) and torch.equal(y2, f2)
         check_close(down(f1).reshape(U, dv), want_lin[:, t], TOL["bf16"], f"fused packed lin step {t}")
     assert torch.equal(pa, pb) and torch.equal(ra, rb)
+
+
+# ------------------------------------------------------------------------------------------------
+# ragged batches: per-sequence positions in device memory
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("packed", [False, True])
+def test_decode_fused_ragged_positions(based, packed):
+    """Sequences that start at different steps: every sequence, on its own token stream, matches the
+    oracle; a sequence whose position is < 1 is left untouched and gets zero rows."""
+    wl = make_wl("decode_1p3b", dtype="bf16")
+    B, H, T = 4, 2, 70                      # 70 > w: the ring wraps for the early starters
+    dp, dv, dh, w = wl.d_feat, wl.d_v, wl.d_h, wl.w
+    U = B * H
+    start = np.array([0, 3, 40, 69])        # first step at which sequence b is active
+    dec = synth.decode_inputs(wl, T, units=U)
+    scale = 1.0 / math.sqrt(dh)
+    state = (based.alloc_packed_state if packed else based.alloc_state)(B, H, dp, dv)
+    ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    ylin = np.zeros((T, U, dv)); yswa = np.zeros((T, U, dh))
+    for t in range(T):
+        pos = torch.tensor(np.maximum(t - start + 1, 0), dtype=torch.int32, device="cuda")
+        args = [up(dec[n][t], "bf16", (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+        f1, f2 = based.decode_fused(args[0], args[1], args[2], state, args[3], args[4], args[5], ring,
+                                    pos, w, scale, packed=packed)
+        torch.cuda.synchronize()
+        ylin[t] = down(f1).reshape(U, dv); yswa[t] = down(f2).reshape(U, dh)
+    for b in range(B):
+        units = np.arange(b * H, (b + 1) * H)
+        s0 = start[b]
+        assert not ylin[:s0, units].any() and not yswa[:s0, units].any()
+        seq = lambda name: dec[name][s0:, units].transpose(1, 0, 2)
+        want_lin = oracle.linattn_quadratic(seq("q"), seq("k"), seq("v"))
+        want_swa = oracle.swa(seq("swa_q"), seq("swa_k"), seq("swa_v"), w, scale)
+        check_close(rows(ylin[s0:, units].transpose(1, 0, 2)), rows(want_lin), TOL["bf16"], f"ragged lin seq {b}")
+        check_close(rows(yswa[s0:, units].transpose(1, 0, 2)), rows(want_swa), TOL["bf16"], f"ragged swa seq {b}")
+
+
+def test_decode_step_graph_replay_with_device_positions(based):
+    """One captured fused decode step, replayed token after token while a device tensor holds the
+    positions: every replay equals the eager step (eager work and synchronisation in between)."""
+    wl = make_wl("decode_1p3b", dtype="bf16")
+    B, H, T = 2, 2, 6
+    dp, dv, dh, w = wl.d_feat, wl.d_v, wl.d_h, wl.w
+    dec = synth.decode_inputs(wl, T, units=B * H)
+    scale = 1.0 / math.sqrt(dh)
+    names = ("q", "k", "v", "swa_q", "swa_k", "swa_v")
+    toks = [[up(dec[n][t], "bf16", (B, H, -1)) for n in names] for t in range(T)]
+
+    def eager():
+        state = based.alloc_state(B, H, dp, dv)
+        ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+        outs = []
+        for t in range(T):
+            pos = torch.full((B,), t + 1, dtype=torch.int32, device="cuda")
+            outs.append(based.decode_fused(*toks[t][:3], state, *toks[t][3:], ring, pos, w, scale))
+        torch.cuda.synchronize()
+        return outs, state, ring
+
+    want, state_w, ring_w = eager()
+    state = based.alloc_state(B, H, dp, dv)
+    ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    inputs = [torch.empty_like(x) for x in toks[0]]
+    y_lin = torch.empty((B, H, dv), dtype=torch.bfloat16, device="cuda")
+    y_swa = torch.empty((B, H, dh), dtype=torch.bfloat16, device="cuda")
+    pos = torch.zeros((B,), dtype=torch.int32, device="cuda")   # every sequence inactive: warm-up touches nothing
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        based.decode_fused(*inputs[:3], state, *inputs[3:], ring, pos, w, scale, y_lin=y_lin, y_swa=y_swa)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        based.decode_fused(*inputs[:3], state, *inputs[3:], ring, pos, w, scale, y_lin=y_lin, y_swa=y_swa)
+    for t in range(T):
+        for dst, src in zip(inputs, toks[t]):
+            dst.copy_(src)
+        pos.add_(1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_lin, want[t][0]) and torch.equal(y_swa, want[t][1]), f"replay {t}"
+    assert torch.equal(state, state_w) and torch.equal(ring, ring_w)
