@@ -34,9 +34,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 158715108     # based_prefill (prefill_360m)
+MEASURED_PREFILL_TRAFFIC_BYTES = 158700206     # based_prefill (prefill_360m)
 MEASURED_SWA_TRAFFIC_BYTES = 142819555         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 579100526      # decode_step_kernel (decode_1p3b)
+MEASURED_DECODE_TRAFFIC_BYTES = 579069551      # decode_step_kernel (decode_1p3b)
+MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325378815   # decode_step_kernel on the packed state (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
@@ -276,7 +277,8 @@ def decode_leg(torch, based, synth, dev, steps: int):
             "roofline": {"kernel": "based_decode_step_packed (decode_step_kernel, packed rows)", "bound": "hbm",
                          "achieved": round(lin_bytes_p / (ms_lin_p * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "frac": round(lin_bytes_p / (ms_lin_p * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                         "algorithmic_bytes_per_launch": lin_bytes_p, "traffic": None},
+                         "algorithmic_bytes_per_launch": lin_bytes_p,
+                         "traffic": MEASURED_PACKED_DECODE_TRAFFIC_BYTES},
         },
     }
 
