@@ -73,7 +73,7 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
 size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype)
 {
     if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype) || !ok_counts(B, H, N)) return 0;
-    if (!prefill_mfma_supported(d_feat, d_v, dtype)) return 0;
+    if (!prefill_mfma_supported(d_feat, d_v, dtype)) return prefill_ref_workspace_bytes(B * H, N, d_feat, d_v);
     return prefill_mfma_workspace_bytes(B * H, N, d_feat, d_v);
 }
 
@@ -93,8 +93,10 @@ int based_prefill(const void *q, const void *k, const void *v, void *y, void *st
         return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0,
                                              workspace, U, N, d_feat, d_v, (hipStream_t)stream));
     }
-    return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, U, N,
-                                        d_feat, d_v, dtype, (hipStream_t)stream));
+    const size_t need = prefill_ref_workspace_bytes(U, N, d_feat, d_v);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, workspace, U,
+                                        N, d_feat, d_v, dtype, (hipStream_t)stream));
 }
 
 int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,

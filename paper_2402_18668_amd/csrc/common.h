@@ -68,7 +68,9 @@ __device__ __forceinline__ float wave_max(float x)
 // ---- launchers implemented in the kernel translation units ---------------------------------
 // Each returns a hipError_t from the launch (hipGetLastError), never synchronises.
 hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void *y, float *state,
-                              int has_init, int U, int N, int dp, int dv, int dtype, hipStream_t s);
+                              int has_init, void *workspace, int U, int N, int dp, int dv, int dtype,
+                              hipStream_t s);
+size_t prefill_ref_workspace_bytes(int U, int N, int dp, int dv);
 bool prefill_mfma_supported(int dp, int dv, int dtype);
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv);
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,

@@ -82,7 +82,9 @@ def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
 
 @pytest.mark.parametrize("dtype,dp,dv,N,N1", [("f32", 16, 64, 300, 130), ("bf16", 16, 64, 300, 130),
                                                ("bf16", 16, 128, 300, 130), ("bf16", 32, 64, 300, 130),
-                                               ("bf16", 16, 64, 1400, 130), ("bf16", 16, 128, 1300, 1100)])
+                                               ("bf16", 16, 64, 1400, 130), ("bf16", 16, 128, 1300, 1100),
+                                               # segmented second part on the fp32 vector-ALU path
+                                               ("f32", 16, 64, 1400, 130), ("bf16", 32, 64, 1200, 100)])
 def test_prefill_split_with_state(based, dtype, dp, dv, N, N1):
     """prefill(N) == prefill(N1) then prefill(N - N1 | state); state import/export round trip."""
     wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
@@ -597,3 +599,24 @@ def test_decode_step_graph_replay_with_device_positions(based):
         torch.cuda.synchronize()
         assert torch.equal(y_lin, want[t][0]) and torch.equal(y_swa, want[t][1]), f"replay {t}"
     assert torch.equal(state, state_w) and torch.equal(ring, ring_w)
+
+
+def test_full_size_long_config_sampled_rows(based):
+    """The long-sequence / larger-state workload at full size (B2 H16 N16384, d' = 32: the segmented
+    fp32 vector-ALU path; window 128): sampled rows of sampled units against the oracle."""
+    wl = synth.WORKLOADS["prefill_long"]
+    B, H, N, U = wl.B, wl.H, wl.N, wl.units
+    q, k, v = synth.linattn_inputs(wl)
+    y = run_prefill(based, wl, B, H, N, q, k, v)
+    units = np.array([0, 1, U // 2, U - 1])
+    sample = np.array([0, 1, 255, 256, 511, 512, 513, 4095, 4096, 8192, 12345, N - 2, N - 1])
+    want = oracle.linattn_rows(q[units], k[units], v[units], sample)
+    check_close(rows(y[units][:, sample]), rows(want), TOL[wl.dtype], "prefill_long sampled rows")
+    sq, sk, sv = synth.swa_inputs(wl)
+    scale = 1.0 / math.sqrt(wl.d_h)
+    ys = based.swa_prefill(up(sq, wl.dtype, (B, H, N, wl.d_h)), up(sk, wl.dtype, (B, H, N, wl.d_h)),
+                           up(sv, wl.dtype, (B, H, N, wl.d_h)), wl.w, scale)
+    torch.cuda.synchronize()
+    want = oracle.swa_rows(sq[units], sk[units], sv[units], wl.w, scale, sample)
+    check_close(rows(down(ys).reshape(U, N, wl.d_h)[units][:, sample]), rows(want), TOL[wl.dtype],
+                "prefill_long swa sampled rows")
