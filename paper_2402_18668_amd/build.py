@@ -16,6 +16,7 @@ SOURCES = [
     "decode.hip",
     "linattn_prefill_ref.hip",
     "linattn_prefill_mfma.hip",
+    "linattn_prefill_mfma32.hip",
     "swa_prefill_ref.hip",
     "swa_prefill_mfma.hip",
 ]

@@ -73,6 +73,7 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
 size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype)
 {
     if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype) || !ok_counts(B, H, N)) return 0;
+    if (prefill_mfma32_supported(d_feat, d_v, dtype)) return prefill_mfma32_workspace_bytes(B * H, N, d_feat, d_v);
     if (!prefill_mfma_supported(d_feat, d_v, dtype)) return prefill_ref_workspace_bytes(B * H, N, d_feat, d_v);
     return prefill_mfma_workspace_bytes(B * H, N, d_feat, d_v);
 }
@@ -86,6 +87,12 @@ int based_prefill(const void *q, const void *k, const void *v, void *y, void *st
     if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
     if (has_init && !state) return BASED_ERR_INVALID_ARG;
     const int U = B * H;
+    if (prefill_mfma32_supported(d_feat, d_v, dtype)) {
+        // d' = 32 always needs the workspace (it carries the denominators between launches)
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return BASED_ERR_INVALID_ARG;
+        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0,
+                                               workspace, U, N, d_feat, d_v, (hipStream_t)stream));
+    }
     if (prefill_mfma_supported(d_feat, d_v, dtype)) {
         const size_t need = prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
         if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)))

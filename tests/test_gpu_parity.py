@@ -66,6 +66,7 @@ def test_prefill_tiny_fp32(based):
     (16, 64, 1, 1, 1), (16, 64, 1, 2, 63), (16, 64, 1, 2, 64), (16, 128, 1, 1, 65),
     # long enough for the sequence to be cut into segments (ragged last segment and chunk)
     (16, 64, 1, 2, 1100), (16, 128, 1, 1, 1500), (16, 64, 1, 1, 2048),
+    (32, 64, 1, 2, 1100), (32, 128, 1, 1, 1500), (32, 64, 1, 1, 1), (32, 128, 1, 2, 64), (32, 64, 2, 1, 65),
 ])
 def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
     wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
@@ -84,7 +85,8 @@ def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
                                                ("bf16", 16, 128, 300, 130), ("bf16", 32, 64, 300, 130),
                                                ("bf16", 16, 64, 1400, 130), ("bf16", 16, 128, 1300, 1100),
                                                # segmented second part on the fp32 vector-ALU path
-                                               ("f32", 16, 64, 1400, 130), ("bf16", 32, 64, 1200, 100)])
+                                               ("f32", 16, 64, 1400, 130), ("bf16", 32, 64, 1200, 100),
+                                               ("bf16", 32, 128, 1700, 1100)])
 def test_prefill_split_with_state(based, dtype, dp, dv, N, N1):
     """prefill(N) == prefill(N1) then prefill(N - N1 | state); state import/export round trip."""
     wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
@@ -108,7 +110,8 @@ def test_prefill_split_with_state(based, dtype, dp, dv, N, N1):
     check_close(down(z2).reshape(zw.shape), zw, TOL[dtype], "split prefill final z")
 
 
-@pytest.mark.parametrize("dtype,dp,dv", [("bf16", 16, 64), ("bf16", 16, 128), ("f32", 16, 64)])
+@pytest.mark.parametrize("dtype,dp,dv", [("bf16", 16, 64), ("bf16", 16, 128), ("f32", 16, 64), ("bf16", 32, 64),
+                                          ("bf16", 32, 128)])
 def test_prefill_initial_state_symmetric_part(based, dtype, dp, dv):
     """y depends only on the sum of the state rows (a, b) and (b, a): an antisymmetric
     perturbation of the initial state leaves y (and the symmetric part of the final state) unchanged."""
@@ -603,7 +606,7 @@ def test_decode_step_graph_replay_with_device_positions(based):
 
 def test_full_size_long_config_sampled_rows(based):
     """The long-sequence / larger-state workload at full size (B2 H16 N16384, d' = 32: the segmented
-    fp32 vector-ALU path; window 128): sampled rows of sampled units against the oracle."""
+    matrix-core path with the K-state slice; window 128): sampled rows of sampled units against the oracle."""
     wl = synth.WORKLOADS["prefill_long"]
     B, H, N, U = wl.B, wl.H, wl.N, wl.units
     q, k, v = synth.linattn_inputs(wl)
