@@ -17,9 +17,10 @@
 // intra-chunk product go to waves 2 (two blocks) and 3.  Per chunk each wave produces a partial
 // Y^T over its feature rows for both query tiles; wave 0 finishes query tile 0, wave 1 tile 1.
 //
-// Denominator.  The K-state is carried as one more slice whose "values" are all ones: the same
-// code then produces phi(q).z per token (written as fp32 to the workspace by a first launch) and
-// the K-state itself; the slices of the real values divide by it.
+// Denominator.  Wave 3 carries the K-state as moments: M[a][b] = sum_t k_a k_b (one tile, an MFMA
+// of the K rows with themselves), z1[a] = sum_t k_a (vector adds) and the token count.  Per query
+// phi(q).z = z0 + sum_a q_a (z1[a] + (M q)[a] / 2); the part from inside the chunk is the column
+// sum of the masked block P the intra-chunk waves hold anyway.
 //
 // Long sequences / few units: G segments; a first launch computes each segment's state increment
 // (update GEMMs only), the later launches start each segment from the sum of the entries before it.
@@ -56,9 +57,10 @@ constexpr int QR_LD = DP + 8;     // bf16 Q rows as given (80-byte stride)
 constexpr int KR_LD = 64 + 16;    // bf16 extended K rows (160-byte stride)
 constexpr int YT_LD = 32 + 8;     // bf16 rows of a finished output tile on its way out
 
-// Workspace entry (one segment's state in accumulator layout): 18 slots of 16 registers x 64 lanes:
-// slot 4w + tt = main tile tt of wave w; 16 = E1; 17 = E2.  Within a slot: [r / 4][lane][r % 4].
-constexpr int WS_SLOTS = 18;
+// Workspace entry (one segment's state in accumulator layout): 20 slots of 16 registers x 64 lanes:
+// slot 4w + tt = main tile tt of wave w; 16 = E1; 17 = E2; 18 = M; 19 = [z1, z0] in the first two
+// registers.  Within a slot: [r / 4][lane][r % 4].
+constexpr int WS_SLOTS = 20;
 constexpr size_t kWsEntryFloats = (size_t)WS_SLOTS * 16 * 64;
 
 struct Stage {
@@ -73,6 +75,9 @@ struct Stage {
 struct Lds {
     Stage st;
     float xbuf[2][3][4][64][4];   // partial Y^T tiles: [query tile][sender slot][r / 4][lane][r % 4]
+    float z1s[DP];                // z1, for wave 3's own broadcast reads
+    float dint[2][32];            // denominators: the part from before the chunk, [query tile][query]
+    float dsum[3][32];            // ... and from inside it: column sums of the blocks (k0,q0), (k0,q1), (k1,q1)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -145,13 +150,12 @@ struct SegTable { int begin[kMaxSegments + 1]; };
 
 // MODE 0: full prefill of the segment; MODE 1: state increment only, to workspace entry 1 + seg;
 // MODE 2: the caller's initial state, converted, to entry 0.
-// slice < vslices: columns [32 slice, 32 slice + 32) of v / y.  slice == vslices: the K-state slice
-// (values are ones; MODE 0 writes the denominators to den instead of y).
+// Slice: columns [32 slice, 32 slice + 32) of v / y.
 template <int MODE>
 __global__ __launch_bounds__(NT, 2) void prefill_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws,
-    float *__restrict__ den, int N, int dv, SegTable segs, int G, int slice_begin, int slice_count)
+    int N, int dv, SegTable segs, int G)
 {
     __shared__ __align__(16) Lds lds;
 
@@ -160,13 +164,12 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
     const int lane = tid & 63;
     const int g = lane >> 5, n = lane & 31;
 
-    const int vslices = dv / DVS, slices = vslices + 1;
+    const int slices = dv / DVS;
     const int gseg = MODE == 1 ? G - 1 : (MODE == 2 ? 1 : G);
     int bid = blockIdx.x;
     const int seg = bid % gseg; bid /= gseg;
-    const int slice = slice_begin + bid % slice_count;
-    const int u = bid / slice_count;
-    const bool ones = slice == vslices;
+    const int slice = bid % slices;
+    const int u = bid / slices;
     const int col0 = slice * DVS;
 
     const int tok_begin = segs.begin[seg];
@@ -174,23 +177,23 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 
     const uint16_t *qu = q + (size_t)u * N * DP;
     const uint16_t *ku = k + (size_t)u * N * DP;
-    const uint16_t *vu = v + (size_t)u * N * dv + (ones ? 0 : col0);
-    uint16_t *yu = y + (size_t)u * N * dv + (ones ? 0 : col0);
-    float *denu = den + (size_t)u * N;
+    const uint16_t *vu = v + (size_t)u * N * dv + col0;
+    uint16_t *yu = y + (size_t)u * N * dv + col0;
     float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
     float *zu = Su ? Su + (size_t)feature_dim(DP) * dv : nullptr;
     float *ws_unit = ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats;
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[TPW];         // main tiles delta = 4w + tt
-    f32x16 X;              // wave 0: E1; wave 1: E2; unused by waves 2, 3
+    f32x16 X;              // wave 0: E1; wave 1: E2; wave 3: M; unused by wave 2
+    float z1 = 0.f, z0 = 0.f;   // wave 3: z1[n] (both halves of the wave), tokens before this call's first
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) zero16(S[tt]);
     zero16(X);
 
     if (MODE == 0) {
         // start of segment: entry 0 (the initial state, if any) plus the increments before it
-        const int xs = w < 2 ? 16 + w : 4 * w;
+        const int xs = w < 2 ? 16 + w : 18;
         for (int p = has_init ? 0 : 1; p <= seg; ++p) {
             const float *e = ws_unit + (size_t)p * kWsEntryFloats;
 #pragma unroll
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) S[tt][4 * j + i] += t[i];
                 }
-            if (w < 2) {
+            if (w != 2) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const f32x4 t = *reinterpret_cast<const f32x4 *>(e + ws_slot_off(xs, j, lane));
@@ -209,13 +212,17 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                     for (int i = 0; i < 4; ++i) X[4 * j + i] += t[i];
                 }
             }
+            if (w == 3) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(e + ws_slot_off(19, 0, lane));
+                z1 += t[0];
+                z0 += t[1];
+            }
         }
     }
     if (MODE == 2) {
         // canonical rows -> accumulator layout (the symmetric part of a pair's two rows)
         auto fetch = [&](CanonRows cr) -> float {
             if (cr.r1 < 0) return 0.f;
-            if (ones) return 0.5f * (zu[cr.r1] + zu[cr.r2]);
             const size_t col = (size_t)col0 + n;
             return 0.5f * (Su[(size_t)cr.r1 * dv + col] + Su[(size_t)cr.r2 * dv + col]);
         };
@@ -226,14 +233,19 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             for (int tt = 0; tt < TPW; ++tt) S[tt][r] = fetch(canon_rows_main(4 * w + tt, fl));
             if (w == 0) X[r] = fetch(canon_rows_e1(fl));
             else if (w == 1) X[r] = fetch(canon_rows_e2(fl));
+            else if (w == 3) {   // M[a][b] = sqrt(2) x the symmetric part of z's pair rows, a = fl, b = n
+                const CanonRows cr = canon_pair(fl, n);
+                X[r] = kRsqrt2 * (zu[cr.r1] + zu[cr.r2]);
+            }
         }
+        if (w == 3) { z1 = zu[1 + n]; z0 = zu[0]; }
     }
 
     // ---- staging: global -> registers -> LDS ----------------------------------------------------
     // Thread (s_tok, s_q) stages, of token s_tok: elements 8h .. 8h+7 and 16+8h .. 16+8h+7 (h = s_q % 2)
     // of the K row (waves 0, 1) or of the Q row (waves 2, 3), and a quarter of the slice's V row.
     const int s_tok = tid & 63, s_q = tid >> 6, s_h = s_q & 1;
-    u32x4 raw_x[2];
+    u32x4 raw_x[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
     u32x4 raw_v;
     auto load_raw = [&](int tok0) {
         const int tok = min(tok0 + s_tok, tok_end - 1);
@@ -242,16 +254,12 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
             for (int j = 0; j < 2; ++j) raw_x[j] = *reinterpret_cast<const u32x4 *>(xc + 16 * j);
         }
-        if (!ones) raw_v = *reinterpret_cast<const u32x4 *>(vu + (size_t)tok * dv + 8 * s_q);
+        raw_v = *reinterpret_cast<const u32x4 *>(vu + (size_t)tok * dv + 8 * s_q);
     };
     auto stage = [&](int tok0) {
         Stage &st = lds.st;
         const bool valid = tok0 + s_tok < tok_end;
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
-        if (ones) {
-            const uint32_t one2 = valid ? 0x3F803F80u : 0u;
-            raw_v[0] = one2; raw_v[1] = one2; raw_v[2] = one2; raw_v[3] = one2;
-        }
         if (!valid) { raw_x[0] = zero4; raw_x[1] = zero4; raw_v = zero4; }
         if (s_q < 2) {
             float kf[2][8];   // c_k * k: [j][i] = element 16 j + 8 h + i
@@ -314,6 +322,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
     if (MODE != 2) {
         load_raw(tok_begin);
         stage(tok_begin);
+        if (w == 3 && g == 0) lds.z1s[n] = z1;
     }
     for (int tok0 = tok_begin; MODE != 2 && tok0 < tok_end; tok0 += C) {
         const Stage &st = lds.st;
@@ -324,20 +333,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
         f32x4 acc[4];     // the output tile this wave finishes (waves 0, 1)
         float inv = 1.f;
         if (MODE == 0) {
-            // denominator of this lane's query (written by the K-state slice's launch)
-            if (w < 2 && !ones) {
-                const int tok = min(tok0 + 32 * w + n, tok_end - 1);
-                inv = denu[tok];
-            }
             // =============================== readout ============================================
             f32x16 Yown;
             zero16(Yown);
-            bf16x8 Sb[TPW][2];   // bf16 copies of the state tiles: [tile][slab]
-#pragma unroll
-            for (int tt = 0; tt < TPW; ++tt)
-#pragma unroll
-                for (int sl = 0; sl < 2; ++sl) Sb[tt][sl] = pack8_acc(S[tt], sl);
-#pragma unroll
+#pragma unroll 1
             for (int qt = 0; qt < 2; ++qt) {
                 f32x16 Y;
                 zero16(Y);
@@ -373,7 +372,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
                                 pr[4 * jj + i] = qa[4 * (2 * sl + jj) + i] * dw * qr[(16 * sl + 8 * jj + i + tt) & 31];
-                        Y = mfma(Sb[tt][sl], pack8(pr), Y);
+                        Y = mfma(pack8_acc(S[tt], sl), pack8(pr), Y);
                     }
                 }
                 if (w < 2) {
@@ -407,6 +406,31 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                         Y = mfma(xhi, pack8(c1), Y);
                     }
                 }
+                if (w == 3) {
+                    role_guard();
+                    // denominator from before the chunk: T[b][query] = sum_a M[a][b] q_a, then
+                    // z0 + sum_b q_b (z1[b] + T[b] / 2) over this lane's 16 rows b and the other half's
+                    f32x16 T;
+                    zero16(T);
+                    const uint16_t *p = &st.qrow[32 * qt + n][4 * g];
+#pragma unroll
+                    for (int sl = 0; sl < 2; ++sl) {
+                        const u32x2 a = *reinterpret_cast<const u32x2 *>(p + 16 * sl);
+                        const u32x2 b = *reinterpret_cast<const u32x2 *>(p + 16 * sl + 8);
+                        u32x4 o; o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+                        T = mfma(pack8_acc(X, sl), as_bf16x8(o), T);
+                    }
+                    float d = 0.f;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const f32x4 zv = *reinterpret_cast<const f32x4 *>(&lds.z1s[8 * m + 4 * g]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) d = fmaf(qa[4 * m + i], fmaf(0.5f, T[4 * m + i], zv[i]), d);
+                    }
+                    d *= 1.f / kCQ;
+                    d += __shfl_xor(d, 32, 64);
+                    if (g == 0) lds.dint[qt][n] = z0 + (float)(tok0) + d;
+                }
                 // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
                 // wave 2: key tile 0 against query tiles 0 and 1; wave 3: key tile 1 against query tile 1
                 if (w == 2 || (w == 3 && qt == 1)) {
@@ -427,6 +451,13 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                         const float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
                         const int key = 8 * (r >> 2) + 4 * g + (r & 3);
                         P[r] = (!diag || key <= n) ? pv : 0.f;
+                    }
+                    {   // this block's share of the denominators: sum over its keys
+                        float cs = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) cs += P[r];
+                        cs += __shfl_xor(cs, 32, 64);
+                        if (g == 0) lds.dsum[w == 2 ? qt : 2][n] = cs;
                     }
 #pragma unroll
                     for (int sl = 0; sl < 2; ++sl) {
@@ -454,11 +485,13 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[j][i] = Yown[4 * j + i];
+            if (w < 2) inv = lds.dint[w][n] + lds.dsum[w][n] + (w == 1 ? lds.dsum[2][n] : 0.f);
         }
 
         // =================================== update =============================================
         {
             const int arow = n;
+            float z1c = 0.f;   // wave 3: this chunk's share of z1[n] from this half's tokens
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const int tcol = 16 * i4 + 4 * g;   // first token of this lane's k-slots
@@ -483,6 +516,18 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                     tr_read(tr_kbase + tcol * KR_LD + 32 * w, KR_LD, ea, eb);
                     X = mfma(join(ea, eb), vk, X);
                 }
+                if (w == 3) {
+                    role_guard();
+                    // the K rows against themselves: lane (g, n) holds k_n at its 8 tokens, which is both
+                    // the row n of K^T and the column n of K
+                    s16x4 ea, eb;
+                    tr_read(tr_kbase + tcol * KR_LD, KR_LD, ea, eb);
+                    const bf16x8 ek = join(ea, eb);
+                    X = mfma(ek, ek, X);
+                    const u32x4 kw = __builtin_bit_cast(u32x4, ek);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) z1c += bf16lo(kw[i]) + bf16hi(kw[i]);
+                }
                 if (MODE == 0 && w < 2) {
                     // collect a quarter of the other waves' partial tiles under this step's MFMAs
 #pragma unroll
@@ -493,14 +538,14 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                     }
                 }
             }
+            if (w == 3) {
+                z1 += z1c + __shfl_xor(z1c, 32, 64);
+                if (g == 0) lds.z1s[n] = z1;
+            }
         }
         if (MODE == 0 && w < 2) {
             const int qt = w;
-            if (ones) {
-                // the K-state slice: every column holds phi(q).z; column 0 sits in register 0 of g = 0
-                const int tok = tok0 + 32 * qt + n;
-                if (g == 0 && tok < tok_end) denu[tok] = acc[0][0];
-            } else {
+            {
                 // normalise and turn the tile through LDS (this wave's own exchange slots, which it has
                 // finished reading): the tile leaves as 64-byte row segments, 16 rows a store
                 const float rinv = 1.f / inv;
@@ -554,17 +599,18 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
         for (int tt = 0; tt < TPW; ++tt) put(4 * w + tt, S[tt]);
         if (w < 2) put(16 + w, X);
+        if (w == 3) {
+            put(18, X);
+            const f32x4 o = {z1, MODE == 2 ? z0 : 0.f, 0.f, 0.f};
+            *reinterpret_cast<f32x4 *>(e + ws_slot_off(19, 0, lane)) = o;
+        }
     } else if (Su && seg == G - 1) {
-        // final state in the canonical layout (both rows of a pair); the K-state slice writes z
+        // final state in the canonical layout (both rows of a pair); slice 0 writes z
         auto emit = [&](CanonRows cr, float val) {
             if (cr.r1 < 0) return;
-            if (ones) {
-                if (n == 0) { zu[cr.r1] = val; if (cr.r2 != cr.r1) zu[cr.r2] = val; }
-            } else {
-                const size_t col = (size_t)col0 + n;
-                Su[(size_t)cr.r1 * dv + col] = val;
-                if (cr.r2 != cr.r1) Su[(size_t)cr.r2 * dv + col] = val;
-            }
+            const size_t col = (size_t)col0 + n;
+            Su[(size_t)cr.r1 * dv + col] = val;
+            if (cr.r2 != cr.r1) Su[(size_t)cr.r2 * dv + col] = val;
         };
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -573,6 +619,11 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             for (int tt = 0; tt < TPW; ++tt) emit(canon_rows_main(4 * w + tt, fl), S[tt][r]);
             if (w == 0) emit(canon_rows_e1(fl), X[r]);
             else if (w == 1) emit(canon_rows_e2(fl), X[r]);
+            else if (w == 3 && slice == 0) zu[1 + DP + fl * DP + n] = kRsqrt2 * X[r];
+        }
+        if (w == 3 && slice == 0 && g == 0) {
+            zu[1 + n] = z1;
+            if (n == 0) zu[0] = z0 + (float)N;
         }
     }
 }
@@ -580,7 +631,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 // Segments: enough workgroups for two per CU, segments of at least 512 tokens.
 static int pick_segments(int U, int N, int dv)
 {
-    const long groups = (long)U * (dv / DVS + 1);
+    const long groups = (long)U * (dv / DVS);
     int G = (int)((512 + groups - 1) / groups);
     if (G > N / 512) G = N / 512;
     if (G > kMaxSegments) G = kMaxSegments;
@@ -602,7 +653,7 @@ static int make_segments(int N, int G, SegTable &t)
 
 static size_t entry_bytes(int U, int N, int dv)
 {
-    return (size_t)U * (dv / DVS + 1) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
+    return (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
 }
 
 }  // namespace dp32
@@ -612,12 +663,11 @@ bool prefill_mfma32_supported(int dp, int dv, int dtype)
     return dtype == BASED_BF16 && dp == dp32::DP && (dv == 64 || dv == 128);
 }
 
-// Workspace: the entries, then the denominators den[U][N] (fp32).
+// Workspace: one entry per (unit, slice, segment).
 size_t prefill_mfma32_workspace_bytes(int U, int N, int dp, int dv)
 {
     (void)dp;
-    const size_t den = ((size_t)U * N * sizeof(float) + 255) / 256 * 256;
-    return (dp32::entry_bytes(U, N, dv) + 255) / 256 * 256 + den;
+    return (dp32::entry_bytes(U, N, dv) + 255) / 256 * 256;
 }
 
 hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, void *y, float *state,
@@ -626,29 +676,24 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, vo
 {
     using namespace dp32;
     (void)dp;
-    const int vslices = dv / DVS, slices = vslices + 1;
+    const int slices = dv / DVS;
     SegTable segs;
     const int G = make_segments(N, pick_segments(U, N, dv), segs);
     const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)k, *v16 = (const uint16_t *)v;
     float *ws = static_cast<float *>(workspace);
-    float *den = reinterpret_cast<float *>((char *)workspace + (entry_bytes(U, N, dv) + 255) / 256 * 256);
     hipError_t e;
     if (has_init) {
         hipLaunchKernelGGL((prefill_kernel<2>), dim3((unsigned)(U * slices)), dim3(NT), 0, s, q16, k16, v16,
-                           (uint16_t *)y, state, 1, ws, den, N, dv, segs, G, 0, slices);
+                           (uint16_t *)y, state, 1, ws, N, dv, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {
         hipLaunchKernelGGL((prefill_kernel<1>), dim3((unsigned)(U * slices * (G - 1))), dim3(NT), 0, s, q16, k16,
-                           v16, (uint16_t *)y, state, has_init, ws, den, N, dv, segs, G, 0, slices);
+                           v16, (uint16_t *)y, state, has_init, ws, N, dv, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    // the K-state slice first: it writes the denominators the other slices divide by
-    hipLaunchKernelGGL((prefill_kernel<0>), dim3((unsigned)(U * G)), dim3(NT), 0, s, q16, k16, v16, (uint16_t *)y,
-                       state, has_init, ws, den, N, dv, segs, G, vslices, 1);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_kernel<0>), dim3((unsigned)(U * vslices * G)), dim3(NT), 0, s, q16, k16, v16,
-                       (uint16_t *)y, state, has_init, ws, den, N, dv, segs, G, 0, vslices);
+    hipLaunchKernelGGL((prefill_kernel<0>), dim3((unsigned)(U * slices * G)), dim3(NT), 0, s, q16, k16, v16,
+                       (uint16_t *)y, state, has_init, ws, N, dv, segs, G);
     return hipGetLastError();
 }
 
