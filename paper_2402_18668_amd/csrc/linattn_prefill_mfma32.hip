@@ -360,9 +360,11 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                         for (int i = 0; i < 4; ++i) qr[4 * m + i] = t[i];
                     }
                 }
-                // inter-chunk: Y^T += S^T phi(Q)^T over this wave's feature rows
+                // inter-chunk: Y^T += S^T phi(Q)^T over this wave's feature rows.  (The empty asm keeps the
+                // bf16 copies of the state from being made once per chunk and held in 32 registers.)
 #pragma unroll
                 for (int tt = 0; tt < TPW; ++tt) {
+                    asm volatile("" : "+v"(S[tt]));
                     const float dw = (w == 0 && tt == 0) ? 0.5f : 1.f;   // delta = 0: x_a^2 / sqrt(2)
 #pragma unroll
                     for (int sl = 0; sl < 2; ++sl) {
