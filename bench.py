@@ -251,6 +251,7 @@ def decode_leg(torch, based, synth, dev, steps: int):
     run(20, True, use_packed=True)
     ms_fused_p = run(steps, True, use_packed=True)
     ms_lin_p = run(steps, False, lin_only=True, use_packed=True)
+    graph = graph_replay_leg(torch, based, synth, dev, steps)
     D = 1 + dp + dp * dp
     Dp = 1 + dp + dp * (dp + 1) // 2
     lin_bytes = (2 * (D * dv + D) * 4 + (2 * dp + dv) * 2 + dv * 2) * U
@@ -268,6 +269,8 @@ def decode_leg(torch, based, synth, dev, steps: int):
         "roofline": {"kernel": "based_decode_step (decode_step_kernel)", "bound": "hbm", "achieved": round(gbs_lin, 1),
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs_lin / PEAK_HBM_GBS, 4),
                      "algorithmic_bytes_per_launch": lin_bytes, "traffic": MEASURED_DECODE_TRAFFIC_BYTES},
+        # the decode loop captured once as a HIP graph ([fused step, advance positions] x 64) and replayed
+        "graph_replay": graph,
         # variant: packed state (153 rows instead of 273), credited with its own, smaller byte count
         "packed_state": {
             "fused_ms_per_step": round(ms_fused_p, 4),
@@ -281,6 +284,66 @@ def decode_leg(torch, based, synth, dev, steps: int):
                          "traffic": MEASURED_PACKED_DECODE_TRAFFIC_BYTES},
         },
     }
+
+
+def graph_replay_leg(torch, based, synth, dev, steps: int):
+    """Fused decode for the next `steps` tokens, stream-ordered launches against one captured graph of
+    64 [fused step, positions_advance] pairs replayed steps / 64 times.  Two shapes: the 360M-shaped batch
+    of 8 (launch-bound: the step's kernel is a few microseconds) and the 1.3B-shaped batch of 128."""
+    bf = torch.bfloat16
+    T = 64
+    reps = max(1, steps // T)
+    out = {"tokens_per_graph": T, "replays": reps}
+    for name in ("prefill_360m", "decode_1p3b"):
+        wl = synth.WORKLOADS[name]
+        B, H, dp, dv, dh, w = wl.B, wl.H, wl.d_feat, wl.d_v, wl.d_h, wl.w
+        scale = 1.0 / math.sqrt(dh)
+        state = based.alloc_state(B, H, dp, dv, dev)
+        ring = based.alloc_swa_ring(B, H, w, dh, bf, dev)
+        g = torch.Generator(device="cpu").manual_seed(7)
+        mk = lambda d: (torch.randn((T, B, H, d), generator=g) * 0.5).to(bf).to(dev)
+        tq, tk, tv, tsq, tsk, tsv = mk(dp), mk(dp), mk(dv), mk(dh), mk(dh), mk(dh)
+        yl = torch.empty((T, B, H, dv), dtype=bf, device=dev)
+        ys = torch.empty((T, B, H, dh), dtype=bf, device=dev)
+        pos = torch.zeros((B,), dtype=torch.int32, device=dev)
+
+        def loop():
+            for t in range(T):
+                based.decode_fused(tq[t], tk[t], tv[t], state, tsq[t], tsk[t], tsv[t], ring, pos, w, scale,
+                                   y_lin=yl[t], y_swa=ys[t])
+                based.positions_advance(pos)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            loop()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            loop()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+
+        def timed(fn):
+            pos.fill_(1)
+            fn()
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / (reps * T)
+
+        ms_eager = timed(loop)
+        ms_graph = timed(graph.replay)
+        out[name] = {
+            "batch": B,
+            "eager_ms_per_step": round(ms_eager, 5), "graph_ms_per_step": round(ms_graph, 5),
+            "eager_tokens_per_s": round(B / (ms_eager * 1e-3), 1), "graph_tokens_per_s": round(B / (ms_graph * 1e-3), 1),
+        }
+        del graph
+    return out
 
 
 def cpu_baseline(wl, q, k, v, sq, sk, sv, scale):

@@ -192,7 +192,13 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
  * its y rows are written as zeros.  Because the positions live in device memory, a captured launch
  * (HIP graph) can be replayed for token after token while another kernel advances pos.
  * based_decode_fused_ragged: packed != 0 selects the packed state layout.
+ *
+ * based_positions_advance is that other kernel: pos[b] += 1 for every b with pos[b] >= 1 (sequences
+ * that sit out stay out).  pos: device, B int32 values.  A loop of [decode launch, advance] can be
+ * captured once and replayed for every token (the cache position bookkeeping of Alg. 3 kept on the
+ * device).  Errors: BASED_ERR_INVALID_ARG for a null pointer or B < 1.
  */
+int based_positions_advance(int *pos, int B, void *stream);
 int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
                             const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
                             void *stream);

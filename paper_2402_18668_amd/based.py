@@ -26,7 +26,7 @@ EXPORTS = [
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
-    "based_swa_decode_ragged", "based_decode_fused_ragged",
+    "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance",
 ]
 
 
@@ -87,6 +87,8 @@ def _load() -> ctypes.CDLL:
     lib.based_swa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.based_decode_fused_ragged.restype = i
     lib.based_decode_fused_ragged.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, f, i, i, i, vp]
+    lib.based_positions_advance.restype = i
+    lib.based_positions_advance.argtypes = [vp, i, vp]
     return lib
 
 
@@ -281,6 +283,12 @@ def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
 def _check_pos(pos, B):
     if pos.dtype != torch.int32 or pos.numel() != B or not pos.is_cuda or not pos.is_contiguous():
         raise ValueError("per-sequence positions must be a contiguous int32 device tensor of B elements")
+
+
+def positions_advance(pos):
+    """based_positions_advance: pos[b] += 1 where pos[b] >= 1, on the current stream."""
+    _check_pos(pos, pos.numel())
+    _check(lib.based_positions_advance(_ptr(pos), pos.numel(), _stream()), "based_positions_advance")
 
 
 def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None):

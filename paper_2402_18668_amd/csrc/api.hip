@@ -207,6 +207,12 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
     return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H}, B, H, d_h, w, scale, dtype, stream);
 }
 
+int based_positions_advance(int *pos, int B, void *stream)
+{
+    if (!pos || B < 1) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_positions_advance(pos, B, (hipStream_t)stream));
+}
+
 int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
                             const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
                             void *stream)

@@ -108,5 +108,6 @@ hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, in
 // canonical state buffer <-> packed state buffer (to_packed: symmetric part; else both rows of a pair)
 hipError_t launch_state_repack(float *state, float *packed, int U, int dp, int dv, int to_packed,
                                hipStream_t s);
+hipError_t launch_positions_advance(int *pos, int B, hipStream_t s);
 
 }  // namespace based

@@ -69,4 +69,19 @@ hipError_t launch_state_repack(float *state, float *packed, int U, int dp, int d
     return hipGetLastError();
 }
 
+__global__ void positions_advance_kernel(int *__restrict__ pos, int B)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) {
+        const int p = pos[b];
+        if (p >= 1) pos[b] = p + 1;
+    }
+}
+
+hipError_t launch_positions_advance(int *pos, int B, hipStream_t s)
+{
+    hipLaunchKernelGGL(positions_advance_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s, pos, B);
+    return hipGetLastError();
+}
+
 }  // namespace based

@@ -85,6 +85,11 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_decode_fused_packed(p, p, p, p, p, 16, 64, p, p, p, p, p, 0, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_state_pack(p, null, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_unpack(p, p, 1, 1, 12, 64, st) == based.ERR_UNSUPPORTED
+    # position bookkeeping
+    assert lib.based_positions_advance(null, 4, st) == based.ERR_INVALID_ARG
+    assert lib.based_positions_advance(p, 0, st) == based.ERR_INVALID_ARG
+    # d' = 32 in bf16 always needs the workspace
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 32, 64, 1, st) == based.ERR_INVALID_ARG
     # state copies
     assert lib.based_state_export(null, p, p, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_import(p, p, p, 1, 1, 16, 100, st) == based.ERR_UNSUPPORTED

@@ -604,9 +604,65 @@ def test_decode_step_graph_replay_with_device_positions(based):
     assert torch.equal(state, state_w) and torch.equal(ring, ring_w)
 
 
+def test_decode_loop_captured_whole(based):
+    """A whole decode loop in one graph: [fused step on token slot t, positions_advance] for T tokens,
+    captured once, replayed for two batches of T tokens; ragged start positions, one sequence sitting out.
+    State, ring and every output equal the eager loop's."""
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, dp, dv, dh, w, T = 4, 2, wl.d_feat, wl.d_v, wl.d_h, wl.w, 6
+    dec = synth.decode_inputs(wl, 2 * T, units=B * H)
+    scale = 1.0 / math.sqrt(dh)
+    names = ("q", "k", "v", "swa_q", "swa_k", "swa_v")
+    toks = [[up(dec[n][t], "bf16", (B, H, -1)) for n in names] for t in range(2 * T)]
+    start = [1, 60, 0, 7]   # sequence 2 takes no part
+
+    state_w = based.alloc_state(B, H, dp, dv)
+    ring_w = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    pos_w = torch.tensor(start, dtype=torch.int32, device="cuda")
+    want = []
+    for t in range(2 * T):
+        want.append(based.decode_fused(*toks[t][:3], state_w, *toks[t][3:], ring_w, pos_w, w, scale))
+        based.positions_advance(pos_w)
+    torch.cuda.synchronize()
+    assert pos_w.tolist() == [1 + 2 * T, 60 + 2 * T, 0, 7 + 2 * T]
+
+    state = based.alloc_state(B, H, dp, dv)
+    ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    slots = [[torch.empty_like(x) for x in toks[0]] for _ in range(T)]
+    y_lin = [torch.empty((B, H, dv), dtype=torch.bfloat16, device="cuda") for _ in range(T)]
+    y_swa = [torch.empty((B, H, dh), dtype=torch.bfloat16, device="cuda") for _ in range(T)]
+    pos = torch.zeros((B,), dtype=torch.int32, device="cuda")   # warm-up: nobody takes part
+
+    def loop():
+        for t in range(T):
+            based.decode_fused(*slots[t][:3], state, *slots[t][3:], ring, pos, w, scale, y_lin=y_lin[t], y_swa=y_swa[t])
+            based.positions_advance(pos)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        loop()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        loop()
+    pos.copy_(torch.tensor(start, dtype=torch.int32, device="cuda"))
+    for half in range(2):
+        for t in range(T):
+            for dst, src in zip(slots[t], toks[half * T + t]):
+                dst.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        for t in range(T):
+            assert torch.equal(y_lin[t], want[half * T + t][0]), f"y_lin replay {half} token {t}"
+            assert torch.equal(y_swa[t], want[half * T + t][1]), f"y_swa replay {half} token {t}"
+    assert torch.equal(state, state_w) and torch.equal(ring, ring_w) and torch.equal(pos, pos_w)
+
+
 def test_full_size_long_config_sampled_rows(based):
     """The long-sequence / larger-state workload at full size (B2 H16 N16384, d' = 32: the segmented
-    matrix-core path with the K-state slice; window 128): sampled rows of sampled units against the oracle."""
+    matrix-core path with the K-state kept as moments; window 128): sampled rows of sampled units against the oracle."""
     wl = synth.WORKLOADS["prefill_long"]
     B, H, N, U = wl.B, wl.H, wl.N, wl.units
     q, k, v = synth.linattn_inputs(wl)
