@@ -91,16 +91,17 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
  *   state  state buffer (layout above) or NULL.  has_init != 0: read as (S0, z0) (must be
  *          non-NULL).  If non-NULL it receives the state after the last token.
  *          A state of this recurrence has equal rows for the feature pairs (a, b) and (b, a)
- *          (x_a x_b = x_b x_a in Eq. 4), and y depends only on their sum.  The bf16 d' = 16
- *          path carries one row per unordered pair: it reads an initial state as the mean of
+ *          (x_a x_b = x_b x_a in Eq. 4), and y depends only on their sum.  The bf16 paths
+ *          carry one row per unordered pair: it reads an initial state as the mean of
  *          the two rows and writes both rows equal.  For a state produced by this library, or
  *          imported from the canonical arrays of such a state, that changes nothing.
  *   workspace  scratch of at least based_prefill_workspace_bytes(...) bytes, 256-byte aligned;
- *          may be NULL when that size is 0.  Contents on return are unspecified and need no
- *          initialisation.  For few units and long sequences the sequence is cut into segments
- *          that run side by side in one launch; workgroups then hand state increments to each
- *          other through the workspace and wait for them with a bounded number of polls (about
- *          a second), after which they proceed: a launch always terminates.
+ *          may be NULL when that size is 0 (it never is for bf16 at d' = 32).  Contents on
+ *          return are unspecified and need no initialisation.  For few units and long sequences
+ *          the sequence is cut into segments that run side by side; state increments of the
+ *          segments travel through the workspace.  At d' = 16 (bf16) that is one launch, in
+ *          which workgroups wait for each other's increments with a bounded number of polls
+ *          (about a second), after which they proceed: a launch always terminates.
  *
  * Calls sharing a workspace or a state buffer must be ordered on one stream.
  */
