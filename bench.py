@@ -8,6 +8,9 @@ fused decode step (state update/readout + ring attention) for the next token of 
 Inputs are seeded synthetic tensors already resident in HBM; several distinct buffer sets are
 rotated so that no step finds its inputs in the 256 MB last-level cache.
 
+``--workload`` times the same step on the 1.3B-layer-shaped or the long-sequence (d' = 32) prefill
+workload instead; the metric is quoted on the default.
+
 Prints ONE JSON line.  ``value`` is tokens/s over the timed steps (B * (N + 1) tokens per step).
 The line also carries the roofline of the dominant kernel (the linear-attention prefill, timed
 with events on its own stream), the decode-state-update roofline on the 1.3B-shaped decode
@@ -55,6 +58,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--decode-steps", type=int, default=1024, help="steps of the batch-128 decode leg")
+    ap.add_argument("--workload", default="prefill_360m", choices=["prefill_360m", "prefill_1p3b", "prefill_long"],
+                    help="prefill workload of the step; the metric is quoted on the default, the others are "
+                         "the parity-test shapes, timed the same way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-leg", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -75,7 +81,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    wl = synth.WORKLOADS["prefill_360m"]
+    wl = synth.WORKLOADS[args.workload]
+    default_wl = args.workload == "prefill_360m"   # the measured-traffic constants hold for this one only
     B, H, N, dp, dv, dh, w = wl.B, wl.H, wl.N, wl.d_feat, wl.d_v, wl.d_h, wl.w
     U = B * H
     scale = 1.0 / math.sqrt(dh)
@@ -150,9 +157,11 @@ def main() -> int:
     flops_full_d = lin_prefill_flops_per_token_head(dp, dv, packed=False) * U * N
     achieved = flops / (prefill_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "based_prefill (prefill_mfma_fused_kernel: segment increments + main chunked pass in one launch)",
+        "kernel": ("based_prefill (prefill_mfma_fused_kernel: segment increments + main chunked pass in one launch)"
+                   if dp == 16 else "based_prefill (dp32::prefill_kernel: increment launch + main launch)"),
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_PREFILL_TRAFFIC_BYTES,
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+        "traffic": MEASURED_PREFILL_TRAFFIC_BYTES if default_wl else None,
         "avg_ms": round(prefill_ms, 4), "flops_per_launch": flops,
         # the same duration priced with the 273-row (unpacked) formulation's flop count
         "flops_per_launch_unpacked_state": flops_full_d,
@@ -166,7 +175,7 @@ def main() -> int:
         "kernel": "based_swa_prefill (swa_prefill_mfma_kernel)", "bound": "hbm",
         "achieved": round(swa_bytes / (swa_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(swa_bytes / (swa_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "avg_ms": round(swa_ms, 4),
-        "algorithmic_bytes_per_launch": swa_bytes, "traffic": MEASURED_SWA_TRAFFIC_BYTES,
+        "algorithmic_bytes_per_launch": swa_bytes, "traffic": MEASURED_SWA_TRAFFIC_BYTES if default_wl else None,
     }
 
     out = {
@@ -174,7 +183,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "prefill_360m: B8 N2048 H16 d'16 d_v64 + window-64 attention d_h64, "
+        "config": {"workload": f"{wl.name}: B{B} N{N} H{H} d'{dp} d_v{dv} + window-{w} attention d_h{dh}, "
                                "then one fused decode step per sequence", "tokens_per_step": tokens_per_step,
                    "buffer_sets": NSETS},
         "prefill_tokens_per_s_linear_attention_only": round(B * N / (prefill_ms * 1e-3), 1),
