@@ -37,10 +37,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 158700206     # based_prefill (prefill_360m)
-MEASURED_SWA_TRAFFIC_BYTES = 142819555         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 579069551      # decode_step_kernel (decode_1p3b)
-MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325378815   # decode_step_kernel on the packed state (decode_1p3b)
+MEASURED_PREFILL_TRAFFIC_BYTES = 158708513     # based_prefill (prefill_360m)
+MEASURED_SWA_TRAFFIC_BYTES = 142820871         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
+MEASURED_DECODE_TRAFFIC_BYTES = 579107448      # decode_step_kernel (decode_1p3b)
+MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325385548   # decode_step_kernel on the packed state (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
@@ -63,6 +63,7 @@ def main() -> int:
                          "the parity-test shapes, timed the same way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-leg", action="store_true")
+    ap.add_argument("--no-graph-leg", action="store_true", help="skip the graph-replay part of the decode leg")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain device copies of 1 GiB (not timed): the known traffic that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -193,7 +194,7 @@ def main() -> int:
 
     # ---- decode leg: 1.3B-shaped, batch 128, fused state update/readout + ring attention ---------
     if not args.no_decode_leg:
-        out["decode"] = decode_leg(torch, based, synth, dev, args.decode_steps)
+        out["decode"] = decode_leg(torch, based, synth, dev, args.decode_steps, not args.no_graph_leg)
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
     if not args.no_cpu_baseline:
@@ -203,7 +204,7 @@ def main() -> int:
     return 0
 
 
-def decode_leg(torch, based, synth, dev, steps: int):
+def decode_leg(torch, based, synth, dev, steps: int, with_graph: bool = True):
     wl = synth.WORKLOADS["decode_1p3b"]
     B, H, dp, dv, dh, w = wl.B, wl.H, wl.d_feat, wl.d_v, wl.d_h, wl.w
     U = B * H
@@ -260,7 +261,7 @@ def decode_leg(torch, based, synth, dev, steps: int):
     run(20, True, use_packed=True)
     ms_fused_p = run(steps, True, use_packed=True)
     ms_lin_p = run(steps, False, lin_only=True, use_packed=True)
-    graph = graph_replay_leg(torch, based, synth, dev, steps)
+    graph = graph_replay_leg(torch, based, synth, dev, steps) if with_graph else None
     D = 1 + dp + dp * dp
     Dp = 1 + dp + dp * (dp + 1) // 2
     lin_bytes = (2 * (D * dv + D) * 4 + (2 * dp + dv) * 2 + dv * 2) * U
