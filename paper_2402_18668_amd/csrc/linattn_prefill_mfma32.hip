@@ -13,9 +13,11 @@
 //
 // Work split.  One workgroup of four waves per (unit, 32-column slice of d_v, sequence segment);
 // wave w owns the four main tiles delta = 4w .. 4w+3.  Two extra tiles: E1 = the 32 linear rows
-// (wave 0), E2 = [1, 0 x 15, the 16 rows of delta = 16] (wave 1).  The three blocks of the
-// intra-chunk product go to waves 2 (two blocks) and 3.  Per chunk each wave produces a partial
-// Y^T over its feature rows for both query tiles; wave 0 finishes query tile 0, wave 1 tile 1.
+// (wave 2), E2 = [1, 0 x 15, the 16 rows of delta = 16] (wave 0); wave 3 has the K-state.  The
+// three blocks of the intra-chunk product go to waves 0 (keys 0, queries 0), 1 (keys 1, queries 1)
+// and 2 (keys 0, queries 1).  Per chunk each wave produces a partial Y^T over its feature rows for
+// both query tiles; wave 0 finishes query tile 0, wave 1 tile 1.  (Roles are spread so that the
+// waves reach the two barriers of a chunk at about the same time.)
 //
 // Denominator.  Wave 3 carries the K-state as moments: M[a][b] = sum_t k_a k_b (one tile, an MFMA
 // of the K rows with themselves), z1[a] = sum_t k_a (vector adds) and the token count.  Per query
@@ -78,6 +80,7 @@ struct Lds {
     float z1s[DP];                // z1, for wave 3's own broadcast reads
     float dint[2][32];            // denominators: the part from before the chunk, [query tile][query]
     float dsum[3][32];            // ... and from inside it: column sums of the blocks (k0,q0), (k0,q1), (k1,q1)
+                                  // (written by waves 0, 2, 1)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 S[TPW];         // main tiles delta = 4w + tt
-    f32x16 X;              // wave 0: E1; wave 1: E2; wave 3: M; unused by wave 2
+    f32x16 X;              // wave 0: E2; wave 2: E1; wave 3: M; unused by wave 1
     float z1 = 0.f, z0 = 0.f;   // wave 3: z1[n] (both halves of the wave), tokens before this call's first
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) zero16(S[tt]);
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 
     if (MODE == 0) {
         // start of segment: entry 0 (the initial state, if any) plus the increments before it
-        const int xs = w < 2 ? 16 + w : 18;
+        const int xs = w == 0 ? 17 : (w == 2 ? 16 : 18);
         for (int p = has_init ? 0 : 1; p <= seg; ++p) {
             const float *e = ws_unit + (size_t)p * kWsEntryFloats;
 #pragma unroll
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) S[tt][4 * j + i] += t[i];
                 }
-            if (w != 2) {
+            if (w != 1) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const f32x4 t = *reinterpret_cast<const f32x4 *>(e + ws_slot_off(xs, j, lane));
@@ -231,8 +234,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) S[tt][r] = fetch(canon_rows_main(4 * w + tt, fl));
-            if (w == 0) X[r] = fetch(canon_rows_e1(fl));
-            else if (w == 1) X[r] = fetch(canon_rows_e2(fl));
+            if (w == 2) X[r] = fetch(canon_rows_e1(fl));
+            else if (w == 0) X[r] = fetch(canon_rows_e2(fl));
             else if (w == 3) {   // M[a][b] = sqrt(2) x the symmetric part of z's pair rows, a = fl, b = n
                 const CanonRows cr = canon_pair(fl, n);
                 X[r] = kRsqrt2 * (zu[cr.r1] + zu[cr.r2]);
@@ -377,10 +380,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                         Y = mfma(pack8_acc(S[tt], sl), pack8(pr), Y);
                     }
                 }
-                if (w < 2) {
+                if (w == 0 || w == 2) {
                     role_guard();
                     const bf16x8 xlo = pack8_acc(X, 0), xhi = pack8_acc(X, 1);
-                    if (w == 0) {
+                    if (w == 2) {
                         role_guard();
                         // E1: the linear rows; the operand is q itself (k-slot (s, jj, i) = element
                         // 16 s + 8 jj + 4 g + i)
@@ -434,10 +437,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                     if (g == 0) lds.dint[qt][n] = z0 + (float)(tok0) + d;
                 }
                 // ---- intra-chunk block: P^T = mask(1 + A^T + A^T^2 / 2), Y^T += V^T P^T ----------
-                // wave 2: key tile 0 against query tiles 0 and 1; wave 3: key tile 1 against query tile 1
-                if (w == 2 || (w == 3 && qt == 1)) {
+                // wave 0: key tile 0 against query tile 0; wave 1: keys 1, queries 1; wave 2: keys 0, queries 1
+                if ((w == 0 && qt == 0) || ((w == 1 || w == 2) && qt == 1)) {
                     role_guard();
-                    const int kt = w - 2;
+                    const int kt = w == 1 ? 1 : 0;
                     const bool diag = kt == qt;
                     f32x16 P;
                     zero16(P);
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 #pragma unroll
                         for (int r = 0; r < 16; ++r) cs += P[r];
                         cs += __shfl_xor(cs, 32, 64);
-                        if (g == 0) lds.dsum[w == 2 ? qt : 2][n] = cs;
+                        if (g == 0) lds.dsum[w == 0 ? 0 : (w == 2 ? 1 : 2)][n] = cs;
                     }
 #pragma unroll
                     for (int sl = 0; sl < 2; ++sl) {
@@ -512,10 +515,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
                     for (int i = 0; i < 4; ++i) { pr[i] = ka0[i] * kb0[i]; pr[4 + i] = ka1[i] * kb1[i]; }
                     S[tt] = mfma(pack8(pr), vk, S[tt]);
                 }
-                if (w < 2) {
+                if (w == 0 || w == 2) {
                     role_guard();
                     s16x4 ea, eb;
-                    tr_read(tr_kbase + tcol * KR_LD + 32 * w, KR_LD, ea, eb);
+                    tr_read(tr_kbase + tcol * KR_LD + (w == 0 ? 32 : 0), KR_LD, ea, eb);
                     X = mfma(join(ea, eb), vk, X);
                 }
                 if (w == 3) {
@@ -600,7 +603,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
         };
 #pragma unroll
         for (int tt = 0; tt < TPW; ++tt) put(4 * w + tt, S[tt]);
-        if (w < 2) put(16 + w, X);
+        if (w == 0) put(17, X);
+        if (w == 2) put(16, X);
         if (w == 3) {
             put(18, X);
             const f32x4 o = {z1, MODE == 2 ? z0 : 0.f, 0.f, 0.f};
@@ -619,8 +623,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) emit(canon_rows_main(4 * w + tt, fl), S[tt][r]);
-            if (w == 0) emit(canon_rows_e1(fl), X[r]);
-            else if (w == 1) emit(canon_rows_e2(fl), X[r]);
+            if (w == 2) emit(canon_rows_e1(fl), X[r]);
+            else if (w == 0) emit(canon_rows_e2(fl), X[r]);
             else if (w == 3 && slice == 0) zu[1 + DP + fl * DP + n] = kRsqrt2 * X[r];
         }
         if (w == 3 && slice == 0 && g == 0) {
