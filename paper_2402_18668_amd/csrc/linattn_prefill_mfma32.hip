@@ -69,7 +69,7 @@ struct Stage {
     float kts[DP][KTS_LD];        // c_k * K^T
     uint16_t krow[C][KR_LD];      // extended K rows: [k_0..k_31 as given, 1 (0 past the end), 0 x 15,
                                   // k_a k_(a+16) / sqrt(2) for a < 16]
-    uint16_t vrow[C][VR_LD];      // V rows of the slice, bf16 as given (ones for the K-state slice)
+    uint16_t vrow[C][VR_LD];      // V rows of the slice, bf16 as given
     float qs[C][QS_LD];           // c_q * Q
     uint16_t qrow[C][QR_LD];      // Q rows, bf16 as given
 };
