@@ -17,7 +17,7 @@
  *   - dtype selects the element type of q, k, v, y (and of the window ring):
  *     BASED_F32 or BASED_BF16.  All accumulation and the recurrent state are fp32.
  *     Outputs are rounded to dtype with round-to-nearest-even.
- *   - Supported sizes: d_feat in {16, 32}; d_v, d_h in {64, 128}; w in {64, 128};
+ *   - Supported sizes: d_feat in {16, 32}; d_v, d_h in {64, 128}; w in {16, 32, 64, 128};
  *     any B, H, N >= 1 with B * H * N < 2^31.  Anything else: BASED_ERR_UNSUPPORTED.
  *
  * Notation follows the paper: d' = d_feat is the projected feature dimension of q and k,

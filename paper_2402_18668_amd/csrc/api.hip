@@ -10,7 +10,10 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool ok_ptr(const void *p) { return p != nullptr && aligned16(p); }
 bool ok_dtype(int dtype) { return dtype == BASED_F32 || dtype == BASED_BF16; }
 bool ok_lin_dims(int dp, int dv) { return (dp == 16 || dp == 32) && (dv == 64 || dv == 128); }
-bool ok_swa_dims(int dh, int w) { return (dh == 64 || dh == 128) && (w == 64 || w == 128); }
+bool ok_swa_dims(int dh, int w)
+{
+    return (dh == 64 || dh == 128) && (w == 16 || w == 32 || w == 64 || w == 128);
+}
 bool ok_counts(int B, int H, int N)
 {
     if (B < 1 || H < 1 || N < 1) return false;

@@ -211,10 +211,10 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
     constexpr int CE = Ch::CE;
     constexpr int LPR = DH / CE;    // lanes per ring row
     constexpr int RPP = NT / LPR;   // ring rows per pass
-    constexpr int PASSES = W / RPP;
-    static_assert(W % RPP == 0 && PASSES >= 1, "window must be a multiple of the rows per pass");
+    constexpr int PASSES = (W + RPP - 1) / RPP;   // a window below one pass leaves row groups idle
+    static_assert(W % RPP == 0 || W < RPP, "window must be a multiple of the rows per pass, or below it");
 
-    __shared__ float sc[W];
+    __shared__ float sc[PASSES * RPP];
     __shared__ float part[RPP][DH];
 
     const int tid = threadIdx.x;
@@ -337,6 +337,21 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
 // ---------------------------------------------------------------------------------------------
 // dispatch
 // ---------------------------------------------------------------------------------------------
+// head dim (64, 128) x window (16, 32, 64, 128)
+#define BASED_PICK_SWA(DH, W, CALL)                               \
+    do {                                                          \
+        if (DH == 64) {                                           \
+            if (W == 16) { CALL(64, 16); }                        \
+            else if (W == 32) { CALL(64, 32); }                   \
+            else if (W == 64) { CALL(64, 64); }                   \
+            else { CALL(64, 128); }                               \
+        } else {                                                  \
+            if (W == 16) { CALL(128, 16); }                       \
+            else if (W == 32) { CALL(128, 32); }                  \
+            else if (W == 64) { CALL(128, 64); }                  \
+            else { CALL(128, 128); }                              \
+        }                                                         \
+    } while (0)
 #define BASED_PICK2(A, a0, a1, B, b0, b1, CALL)                  \
     do {                                                          \
         if (A == a0 && B == b0) { CALL(a0, b0); }                 \
@@ -380,7 +395,7 @@ hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *
         hipLaunchKernelGGL((swa_decode_kernel<DH_, W_, bf16_t>), dim3(U), dim3(kDecodeThreads),   \
                            0, s, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,         \
                            (bf16_t *)y, (bf16_t *)ring, pos, scale)
-    BASED_PICK2(dh, 64, 128, w, 64, 128, CALL_SWA);
+    BASED_PICK_SWA(dh, w, CALL_SWA);
 #undef CALL_SWA
     return hipGetLastError();
 }
@@ -395,7 +410,7 @@ static void fused_pick(const void *q, const void *k, const void *v, void *y_lin,
                        dim3(kDecodeThreads), 0, s, (const T *)q, (const T *)k, (const T *)v,      \
                        (T *)y_lin, state, (const T *)sq, (const T *)sk, (const T *)sv,            \
                        (T *)y_swa, (T *)ring, pos, scale, U)
-    BASED_PICK2(dh, 64, 128, w, 64, 128, CALL_F);
+    BASED_PICK_SWA(dh, w, CALL_F);
 #undef CALL_F
 }
 

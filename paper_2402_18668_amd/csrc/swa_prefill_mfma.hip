@@ -47,7 +47,10 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 constexpr int BQ = 128;   // queries per workgroup
 constexpr int NT = 256;
 
-template <int DH, int W> struct SwaCfg {
+// WIN is the attention window; the key tiles are laid out for W = max(WIN, 32) (a window below one
+// tile of 32 keys walks two tiles and masks the rest).
+template <int DH, int WIN> struct SwaCfg {
+    static constexpr int W = WIN < 32 ? 32 : WIN;
     static constexpr int NK = W + BQ;          // staged key rows
     static constexpr int V_LD = DH + 16;       // bf16 elements per staged V row (row stride = 8 banks mod 32)
     static constexpr int K_LD = DH + 8;        // bf16 elements per staged K row (16-byte pad)
@@ -64,7 +67,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast
 
 }  // namespace
 
-template <int DH, int W>
+template <int DH, int WIN>
 __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__restrict__ q,
                                                               const uint16_t *__restrict__ k,
                                                               const uint16_t *__restrict__ v,
@@ -72,7 +75,8 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                                                               uint16_t *__restrict__ ring, int N,
                                                               int seg_len, int nseg, float scale_log2e)
 {
-    using Cfg = SwaCfg<DH, W>;
+    using Cfg = SwaCfg<DH, WIN>;
+    constexpr int W = Cfg::W;
     constexpr int NK = Cfg::NK, V_LD = Cfg::V_LD, K_LD = Cfg::K_LD, NKT = Cfg::NKT;
     constexpr int SLABS = DH / 16;   // k-slabs of the score contraction
     constexpr int CT = DH / 32;      // column tiles of the output
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     const int q0 = seg * seg_len;                       // first query of this workgroup's segment
     const int q_end = min(N, q0 + seg_len);
     const size_t base = (size_t)u * N * DH;
-    uint16_t *ring_u = ring ? ring + (size_t)u * 2 * W * DH : nullptr;
+    uint16_t *ring_u = ring ? ring + (size_t)u * 2 * WIN * DH : nullptr;
 
     // Staged row of key position p lives in LDS row (p - (q0 - W)) mod NK: a ring of W + BQ rows.
     // A step handles BQ queries; going to the next step overwrites the BQ oldest rows with the BQ
@@ -122,10 +126,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             *reinterpret_cast<u32x4 *>(Ks + (size_t)r * K_LD + c * 8) = fk[it];
             // the w-slot ring receives the last min(N, w) rows (slot = position mod w), written
             // by the segment that owns the row as a query row
-            if (ring_u && key >= q0 && key < N && key >= N - W) {
-                uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
+            if (ring_u && key >= q0 && key < N && key >= N - WIN) {
+                uint16_t *rk = ring_u + (size_t)(key % WIN) * DH + c * 8;
                 *reinterpret_cast<u32x4 *>(rk) = fk[it];
-                *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = fv[it];
+                *reinterpret_cast<u32x4 *>(rk + (size_t)WIN * DH) = fv[it];
             }
         }
     }
@@ -211,8 +215,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             // ---- mask, softmax statistics (lane = query; its keys sit in registers and in lane ^ 32) --
             // Raw scores are masked and their maximum taken; the scale (times log2 e) is applied inside
             // the exponential, exp2(scale * (x - m)), which is one fused multiply-add per element.
-            // Only the first and the last key tile of a query tile cut the window; keys before the
-            // start of the sequence exist only for the first w queries (a uniform branch).
+            // Key 32 t - W + local of the tile row against query n: visible iff -WIN < 32 t - W + local - n <= 0.
+            // Only the tiles whose rows can fall outside get the comparisons (for WIN >= 32 the first
+            // and the last one); keys before the start of the sequence exist only for the first W
+            // queries (a uniform branch).
             float m = -INFINITY;
             auto mask_and_max = [&](auto head_c) {
                 constexpr bool HEAD = decltype(head_c)::value;
@@ -221,11 +227,12 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int local = 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (HEAD || t == 0 || t == NKT - 1) {
+                        const bool cut_low = 32 * t <= W - WIN + 31, cut_high = t == NKT - 1;   // folded when unrolled
+                        if (HEAD || cut_low || cut_high) {
                             bool ok = true;
                             if (HEAD) ok = qbase - W + 32 * t + local >= 0;
-                            if (t == 0) ok = ok && local > n;          // key > query - w
-                            if (t == NKT - 1) ok = ok && local <= n;   // key <= query
+                            if (cut_low) ok = ok && 32 * t - W + local - n > -WIN;   // key > query - w
+                            if (cut_high) ok = ok && local <= n;                      // key <= query
                             P[t][r] = ok ? P[t][r] : -INFINITY;
                         }
                         m = fmaxf(m, P[t][r]);
@@ -345,10 +352,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                 }
                 *reinterpret_cast<u32x4 *>(Vs + (size_t)slot * V_LD + c * 8) = nv[it];
                 *reinterpret_cast<u32x4 *>(Ks + (size_t)slot * K_LD + c * 8) = nk[it];
-                if (ring_u && key < N && key >= N - W && key < q_end) {
-                    uint16_t *rk = ring_u + (size_t)(key % W) * DH + c * 8;
+                if (ring_u && key < N && key >= N - WIN && key < q_end) {
+                    uint16_t *rk = ring_u + (size_t)(key % WIN) * DH + c * 8;
                     *reinterpret_cast<u32x4 *>(rk) = nk[it];
-                    *reinterpret_cast<u32x4 *>(rk + (size_t)W * DH) = nv[it];
+                    *reinterpret_cast<u32x4 *>(rk + (size_t)WIN * DH) = nv[it];
                 }
             }
 #pragma unroll
@@ -361,12 +368,12 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     step(sq0, std::false_type{});
 }
 
-template <int DH, int W>
+template <int DH, int WIN>
 static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
                                   int N, float scale, hipStream_t s)
 {
-    using Cfg = SwaCfg<DH, W>;
-    auto kern = swa_prefill_mfma_kernel<DH, W>;
+    using Cfg = SwaCfg<DH, WIN>;
+    auto kern = swa_prefill_mfma_kernel<DH, WIN>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::lds_bytes);
     if (e != hipSuccess) return e;
@@ -386,12 +393,16 @@ static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, v
 
 bool swa_prefill_mfma_supported(int dh, int w, int dtype)
 {
-    return dtype == BASED_BF16 && (dh == 64 || dh == 128) && (w == 64 || w == 128);
+    return dtype == BASED_BF16 && (dh == 64 || dh == 128) && (w == 16 || w == 32 || w == 64 || w == 128);
 }
 
 hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
                                    int N, int dh, int w, float scale, hipStream_t s)
 {
+    if (dh == 64 && w == 16) return launch_swa_mfma<64, 16>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 64 && w == 32) return launch_swa_mfma<64, 32>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 128 && w == 16) return launch_swa_mfma<128, 16>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 128 && w == 32) return launch_swa_mfma<128, 32>(q, k, v, y, ring, U, N, scale, s);
     if (dh == 64 && w == 64) return launch_swa_mfma<64, 64>(q, k, v, y, ring, U, N, scale, s);
     if (dh == 64 && w == 128) return launch_swa_mfma<64, 128>(q, k, v, y, ring, U, N, scale, s);
     if (dh == 128 && w == 64) return launch_swa_mfma<128, 64>(q, k, v, y, ring, U, N, scale, s);

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kSwaThreads) void swa_prefill_ref_kernel(const T *_
     constexpr int CE = Cfg::CE, STRIDE = Cfg::STRIDE, QB = kSwaQB;
     constexpr int LPR = DH / CE;   // lanes per row
     constexpr int KG = 64 / LPR;   // key groups working in parallel in the value phase
-    constexpr int KPL = W / 64;    // keys per lane in the score phase
+    constexpr int KPL = (W + 63) / 64;   // keys per lane in the score phase (a window below 64 leaves lanes idle)
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
     T *Ks = reinterpret_cast<T *>(lds_raw);
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kSwaThreads) void swa_prefill_ref_kernel(const T *_
         for (int t = 0; t < KPL; ++t) {
             const float p = (sc[t] == -INFINITY) ? 0.f : __expf(sc[t] - m);
             sum += p;
-            pl[wv * W + lane + 64 * t] = p;
+            if (lane + 64 * t < W) pl[wv * W + lane + 64 * t] = p;
         }
         sum = wave_sum(sum);
         __syncthreads();
@@ -187,6 +187,10 @@ hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, v
     if (dh == DH_ && w == W_)                                                                \
         return dtype == BASED_F32 ? launch_swa_ref<DH_, W_, float>(q, k, v, y, U, N, scale, s) \
                                   : launch_swa_ref<DH_, W_, bf16_t>(q, k, v, y, U, N, scale, s)
+    SWA_CASE(64, 16);
+    SWA_CASE(64, 32);
+    SWA_CASE(128, 16);
+    SWA_CASE(128, 32);
     SWA_CASE(64, 64);
     SWA_CASE(64, 128);
     SWA_CASE(128, 64);

@@ -71,7 +71,7 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_decode_step(p, p, p, p, p, 1, 1, 16, 32, 1, st) == based.ERR_UNSUPPORTED
     # window attention
     assert lib.based_swa_prefill(p, p, null, p, null, 1, 1, 8, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
-    assert lib.based_swa_prefill(p, p, p, p, null, 1, 1, 8, 64, 32, 0.125, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_swa_prefill(p, p, p, p, null, 1, 1, 8, 64, 48, 0.125, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_swa_decode(p, p, p, p, p, 0, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_swa_decode(p, p, p, p, null, 1, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_swa_decode(p, p, p, p, p, 1, 1, 1, 80, 64, 0.125, 1, st) == based.ERR_UNSUPPORTED

@@ -197,7 +197,11 @@ def test_prefill_then_decode_equals_longer_prefill(based):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("dh,w,B,H,N", [(64, 64, 2, 2, 300), (128, 64, 1, 2, 150), (64, 128, 1, 2, 333),
                                         (128, 128, 1, 1, 260), (64, 64, 1, 1, 1), (64, 64, 1, 2, 17),
-                                        (128, 64, 1, 1, 64), (64, 64, 1, 1, 65)])
+                                        (128, 64, 1, 1, 64), (64, 64, 1, 1, 65),
+                                        # the small windows (the paper's 1.4B model uses 16)
+                                        (64, 16, 2, 2, 300), (128, 16, 1, 2, 150), (64, 32, 1, 2, 333),
+                                        (128, 32, 1, 1, 260), (64, 16, 1, 1, 1), (128, 16, 1, 2, 15),
+                                        (64, 16, 1, 1, 16), (64, 16, 1, 2, 17), (64, 32, 1, 1, 33)])
 def test_swa_prefill(based, dtype, dh, w, B, H, N):
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
     q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
@@ -216,7 +220,8 @@ def test_swa_prefill(based, dtype, dh, w, B, H, N):
 
 
 @pytest.mark.parametrize("dtype,dh,w", [("f32", 64, 64), ("bf16", 128, 64), ("bf16", 64, 128), ("f32", 128, 128),
-                                        ("bf16", 64, 64)])
+                                        ("bf16", 64, 64), ("bf16", 64, 16), ("bf16", 128, 16), ("f32", 64, 16),
+                                        ("f32", 128, 16), ("bf16", 128, 32), ("f32", 64, 32)])
 def test_swa_decode_from_empty_and_wrapping(based, dtype, dh, w):
     """Decode from an empty ring through the wrap-around: every step equals the prefill row."""
     wl = make_wl("decode_1p3b", d_h=dh, w=w, dtype=dtype)
@@ -234,9 +239,10 @@ def test_swa_decode_from_empty_and_wrapping(based, dtype, dh, w):
         check_close(down(y).reshape(U, dh), want[:, t], TOL[dtype], f"swa decode pos {t + 1}")
 
 
-def test_swa_prefill_then_decode(based):
-    wl = synth.WORKLOADS["decode_1p3b"]
-    dtype, dh, w = wl.dtype, wl.d_h, wl.w
+@pytest.mark.parametrize("w", [64, 16, 32])
+def test_swa_prefill_then_decode(based, w):
+    wl = make_wl("decode_1p3b", w=w)
+    dtype, dh = wl.dtype, wl.d_h
     B, H, N, T = 2, 2, 100, 5
     U = B * H
     q, k, v = synth.swa_inputs(wl, units=U, N=N + T)
@@ -255,7 +261,8 @@ def test_swa_prefill_then_decode(based):
 # fused decode launch
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,dp,dv,dh,w", [("bf16", 16, 128, 128, 64), ("f32", 16, 64, 64, 64),
-                                              ("bf16", 32, 64, 64, 128)])
+                                              ("bf16", 32, 64, 64, 128), ("bf16", 16, 128, 128, 16),
+                                              ("f32", 16, 64, 64, 32)])
 def test_decode_fused_equals_separate_calls(based, dtype, dp, dv, dh, w):
     wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, d_h=dh, w=w, dtype=dtype)
     B, H, N0, T = 2, 2, 70, 6
@@ -363,7 +370,8 @@ def test_full_size_decode_sampled_units(based):
     check_close(down(z).reshape(U, D)[units], zw, TOL[dtype], "full-size decode final z")
 
 
-@pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100)])
+@pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100), (128, 16, 1300),
+                                    (64, 32, 1100)])
 def test_swa_prefill_segmented(based, dh, w, N):
     """Sequences long enough to be cut into segments (ragged last step), every element checked."""
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype="bf16")
