@@ -377,12 +377,23 @@ static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, v
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::lds_bytes);
     if (e != hipSuccess) return e;
-    // Segments per sequence: enough workgroups to fill the chip twice over, but segments of at least
-    // 4 steps so that the W-row halo at a segment start stays small next to the segment.
+    // Segments per sequence.  The launch should be whole rounds of resident workgroups (256 CUs x as
+    // many workgroups as the LDS ring lets a CU hold: a partial last round costs as much as a full
+    // one), with segments long next to the W-row halo and the ring fill every segment starts with.
+    // Score of a candidate: fill of its rounds / (1 + (W + 64) / tokens per segment).
     const int steps = (N + BQ - 1) / BQ;
-    int nseg = (int)((768 + (long)U - 1) / U);
-    if (nseg > steps / 4) nseg = steps / 4;
-    if (nseg < 1) nseg = 1;
+    const int per_cu = (int)((160u * 1024u) / Cfg::lds_bytes) < 1 ? 1 : (int)((160u * 1024u) / Cfg::lds_bytes);
+    const long slots = 256L * per_cu;
+    int nseg = 1;
+    double best = -1.0;
+    for (int c = 1; c <= steps && c <= 64; ++c) {
+        const int seg_steps = (steps + c - 1) / c;
+        const int segs = (steps + seg_steps - 1) / seg_steps;   // segments this candidate really makes
+        const long wgs = (long)segs * U;
+        const double fill = (double)wgs / (double)(((wgs + slots - 1) / slots) * slots);
+        const double score = fill / (1.0 + (double)(Cfg::W + 64) / ((double)seg_steps * BQ));
+        if (score > best * 1.0001) { best = score; nseg = segs; }
+    }
     const int seg_len = ((steps + nseg - 1) / nseg) * BQ;
     nseg = (N + seg_len - 1) / seg_len;
     hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)nseg * U)), dim3(NT), Cfg::lds_bytes, s,
