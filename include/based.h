@@ -173,12 +173,19 @@ int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
  * one, taking the mean of the two rows of a pair; based_state_unpack writes both rows of a pair.
  * based_decode_step_packed and based_decode_fused_packed are based_decode_step and
  * based_decode_fused on a packed state (same y up to rounding order).
+ * based_prefill_packed is based_prefill with the packed layout for the initial and the final state
+ * (same arguments, same workspace size, same y): the prefill hands its state to the packed decode
+ * without a conversion.  Served by the matrix-core kernels only: dtype BASED_BF16, else
+ * BASED_ERR_UNSUPPORTED (use based_prefill and based_state_pack there).
  */
 int based_packed_feature_dim(int d_feat);
 size_t based_packed_state_stride_floats(int d_feat, int d_v);
 size_t based_packed_state_bytes(int B, int H, int d_feat, int d_v);
 int based_state_pack(const void *state, void *packed, int B, int H, int d_feat, int d_v, void *stream);
 int based_state_unpack(const void *packed, void *state, int B, int H, int d_feat, int d_v, void *stream);
+int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
+                         void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                         void *stream);
 int based_decode_step_packed(const void *q, const void *k, const void *v, void *y, void *packed, int B,
                              int H, int d_feat, int d_v, int dtype, void *stream);
 int based_decode_fused_packed(const void *q, const void *k, const void *v, void *y_lin, void *packed,

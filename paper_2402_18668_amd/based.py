@@ -26,6 +26,7 @@ EXPORTS = [
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
+    "based_prefill_packed",
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance",
 ]
 
@@ -87,6 +88,8 @@ def _load() -> ctypes.CDLL:
     lib.based_swa_decode_ragged.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.based_decode_fused_ragged.restype = i
     lib.based_decode_fused_ragged.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, f, i, i, i, vp]
+    lib.based_prefill_packed.restype = i
+    lib.based_prefill_packed.argtypes = lib.based_prefill.argtypes
     lib.based_positions_advance.restype = i
     lib.based_positions_advance.argtypes = [vp, i, vp]
     return lib
@@ -180,8 +183,9 @@ def alloc_prefill_workspace(B, H, N, d_feat, d_v, dtype_code, device="cuda"):
     return torch.empty((n + 3) // 4, dtype=torch.float32, device=device)
 
 
-def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None):
-    """based_prefill.  q, k ``[B,H,N,d']``; v ``[B,H,N,d_v]``; returns y (allocated if not given)."""
+def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=False):
+    """based_prefill, or based_prefill_packed (``packed=True``: ``state`` is a packed-state buffer).
+    q, k ``[B,H,N,d']``; v ``[B,H,N,d_v]``; returns y (allocated if not given)."""
     _dev(q, k, v, y, state, workspace)
     B, H, N, dp = q.shape
     dv = v.shape[-1]
@@ -192,15 +196,17 @@ def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None):
         y = torch.empty_like(v)
     elif y.shape != v.shape or y.dtype != v.dtype:
         raise ValueError("y must match v")
-    if state is not None and (state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv)):
+    sbytes = packed_state_bytes(B, H, dp, dv) if packed else state_bytes(B, H, dp, dv)
+    if state is not None and (state.dtype != torch.float32 or state.numel() * 4 < sbytes):
         raise ValueError("state buffer too small or not fp32")
     need = prefill_workspace_bytes(B, H, N, dp, dv, code)
     if need and workspace is None:
         workspace = alloc_prefill_workspace(B, H, N, dp, dv, code, q.device)
     if need and workspace.numel() * workspace.element_size() < need:
         raise ValueError("workspace too small")
-    _check(lib.based_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
-                             _ptr(workspace), B, H, N, dp, dv, code, _stream()), "based_prefill")
+    fn, what = (lib.based_prefill_packed, "based_prefill_packed") if packed else (lib.based_prefill, "based_prefill")
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
+              _ptr(workspace), B, H, N, dp, dv, code, _stream()), what)
     return y
 
 

@@ -93,20 +93,42 @@ int based_prefill(const void *q, const void *k, const void *v, void *y, void *st
     if (prefill_mfma32_supported(d_feat, d_v, dtype)) {
         // d' = 32 always needs the workspace (it carries the denominators between launches)
         if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return BASED_ERR_INVALID_ARG;
-        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0,
+        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, 0,
                                                workspace, U, N, d_feat, d_v, (hipStream_t)stream));
     }
     if (prefill_mfma_supported(d_feat, d_v, dtype)) {
         const size_t need = prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
         if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
             return BASED_ERR_INVALID_ARG;
-        return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0,
+        return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, 0,
                                              workspace, U, N, d_feat, d_v, (hipStream_t)stream));
     }
     const size_t need = prefill_ref_workspace_bytes(U, N, d_feat, d_v);
     if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
     return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, workspace, U,
                                         N, d_feat, d_v, dtype, (hipStream_t)stream));
+}
+
+int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
+                         void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    // only the matrix-core kernels carry the state packed
+    const bool m32 = prefill_mfma32_supported(d_feat, d_v, dtype);
+    if (!m32 && !prefill_mfma_supported(d_feat, d_v, dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (packed && !aligned16(packed)) return BASED_ERR_INVALID_ARG;
+    if (has_init && !packed) return BASED_ERR_INVALID_ARG;
+    const int U = B * H;
+    const size_t need = m32 ? prefill_mfma32_workspace_bytes(U, N, d_feat, d_v)
+                            : prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
+    if (m32)
+        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(packed), has_init ? 1 : 0, 1,
+                                               workspace, U, N, d_feat, d_v, (hipStream_t)stream));
+    return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(packed), has_init ? 1 : 0, 1,
+                                         workspace, U, N, d_feat, d_v, (hipStream_t)stream));
 }
 
 int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,

@@ -73,13 +73,14 @@ hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void 
 size_t prefill_ref_workspace_bytes(int U, int N, int dp, int dv);
 bool prefill_mfma_supported(int dp, int dv, int dtype);
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv);
+// packed_state != 0: the state buffer is the packed layout (one row per unordered feature pair)
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
-                               int has_init, void *workspace, int U, int N, int dp, int dv,
+                               int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                hipStream_t s);
 bool prefill_mfma32_supported(int dp, int dv, int dtype);
 size_t prefill_mfma32_workspace_bytes(int U, int N, int dp, int dv);
 hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, void *y, float *state,
-                                 int has_init, void *workspace, int U, int N, int dp, int dv,
+                                 int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                  hipStream_t s);
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
                               int U, int dp, int dv, int dtype, int packed, hipStream_t s);

@@ -157,23 +157,29 @@ __device__ __forceinline__ size_t ws_slot_off(int slot, int j, int lane)
 
 // Canonical state rows (Eq. 4 order: row 0 constant, 1 + a linear, 1 + d' + a d' + b the pair
 // (a, b)) of a packed row.  A pair row has two canonical rows (equal for delta = 0).
+// With packed_state the buffer is the packed layout (one row per unordered pair), where a pair has a
+// single row and the constant and linear rows sit at the same indices.
 struct CanonRows { int r1, r2; };   // r1 < 0: the packed row is padding
-__device__ __forceinline__ CanonRows canon_pair(int a, int b)
+__device__ __forceinline__ CanonRows canon_pair(int a, int b, bool packed_state)
 {
+    if (packed_state) {
+        const int r = packed_pair_row(DP, min(a, b), max(a, b));
+        return {r, r};
+    }
     return {1 + DP + a * DP + b, 1 + DP + b * DP + a};
 }
 // local row fl of the main tile of wave w: delta = 2w + fl / 16, a = fl % 16
-__device__ __forceinline__ CanonRows canon_rows_main(int w, int fl)
+__device__ __forceinline__ CanonRows canon_rows_main(int w, int fl, bool packed_state)
 {
     const int a = fl & 15;
-    return canon_pair(a, (a + 2 * w + (fl >> 4)) & 15);
+    return canon_pair(a, (a + 2 * w + (fl >> 4)) & 15, packed_state);
 }
 // local row fl of the extra tile: 0..15 linear, 16 constant, 24..31 the delta = 8 pairs
-__device__ __forceinline__ CanonRows canon_rows_extra(int fl)
+__device__ __forceinline__ CanonRows canon_rows_extra(int fl, bool packed_state)
 {
     if (fl < DP) return {1 + fl, 1 + fl};
     if (fl == DP) return {0, 0};
-    if (fl >= 24) return canon_pair(fl - 24, fl - 16);
+    if (fl >= 24) return canon_pair(fl - 24, fl - 16, packed_state);
     return {-1, -1};
 }
 
@@ -237,6 +243,9 @@ __device__ __forceinline__ void prefill_body(
     float *__restrict__ ws, unsigned *__restrict__ flags, unsigned epoch, int N, int dv,
     const SegTable &segs, int G, int seg, int slice, int u)
 {
+    // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
+    const bool packed_state = (has_init & 2) != 0;
+    has_init &= 1;
     const int tid = threadIdx.x;
     const int w = tid >> 6;   // wave index: owns the main tile delta in {2w, 2w+1}
     const int lane = tid & 63;
@@ -252,8 +261,9 @@ __device__ __forceinline__ void prefill_body(
     const uint16_t *ku = k + (size_t)u * N * DP;
     const uint16_t *vu = v + (size_t)u * N * dv + col0;
     uint16_t *yu = y + (size_t)u * N * dv + col0;
-    float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
-    float *zu = Su ? Su + (size_t)feature_dim(DP) * dv : nullptr;
+    float *Su = state ? state + (size_t)u * (packed_state ? packed_state_stride(DP, dv) : state_stride(DP, dv))
+                      : nullptr;
+    float *zu = Su ? Su + (size_t)(packed_state ? packed_feature_dim(DP) : feature_dim(DP)) * dv : nullptr;
     float *ws_unit = ws ? ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats : nullptr;
     unsigned *flags_unit = flags ? flags + (size_t)(u * slices + slice) * G * G : nullptr;
 
@@ -328,21 +338,21 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
-            const CanonRows cm = canon_rows_main(w, fl);
+            const CanonRows cm = canon_rows_main(w, fl, packed_state);
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2) {
                 const size_t col = (size_t)col0 + 32 * c2 + n;
                 S[c2][r] = 0.5f * (Su[(size_t)cm.r1 * dv + col] + Su[(size_t)cm.r2 * dv + col]);
             }
             if (w < 2) {
-                const CanonRows cx = canon_rows_extra(fl);
+                const CanonRows cx = canon_rows_extra(fl, packed_state);
                 if (cx.r1 >= 0) {
                     const size_t col = (size_t)col0 + 32 * w + n;
                     X[r] = 0.5f * (Su[(size_t)cx.r1 * dv + col] + Su[(size_t)cx.r2 * dv + col]);
                 }
             } else if (w == 2) {
                 float m = 0.f;   // M'[fl][n]
-                if (fl < DP && n < DP) m = zu[1 + DP + fl * DP + n] * 1.41421356237309504880f;
+                if (fl < DP && n < DP) m = zu[canon_pair(fl, n, packed_state).r1] * 1.41421356237309504880f;
                 else if (fl == DP && n < DP) m = zu[1 + n];
                 else if (fl < DP && n == DP) m = zu[1 + fl];
                 else if (fl == DP && n == DP) m = zu[0];
@@ -797,7 +807,7 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
-            const CanonRows cm = canon_rows_main(w, fl);
+            const CanonRows cm = canon_rows_main(w, fl, packed_state);
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2) {
                 const size_t col = (size_t)col0 + 32 * c2 + n;
@@ -805,7 +815,7 @@ __device__ __forceinline__ void prefill_body(
                 if (cm.r2 != cm.r1) Su[(size_t)cm.r2 * dv + col] = S[c2][r];
             }
             if (w < 2) {
-                const CanonRows cx = canon_rows_extra(fl);
+                const CanonRows cx = canon_rows_extra(fl, packed_state);
                 if (cx.r1 >= 0) {
                     const size_t col = (size_t)col0 + 32 * w + n;
                     Su[(size_t)cx.r1 * dv + col] = X[r];
@@ -813,7 +823,9 @@ __device__ __forceinline__ void prefill_body(
                 }
             } else if (w == 2 && slice == 0) {
                 const float m = X[r];
-                if (fl < DP && n < DP) zu[1 + DP + fl * DP + n] = m * kRsqrt2;
+                if (fl < DP && n < DP) {
+                    if (!packed_state || fl <= n) zu[canon_pair(fl, n, packed_state).r1] = m * kRsqrt2;
+                }
                 else if (fl == DP && n < DP) zu[1 + n] = m;
                 else if (fl == DP && n == DP) zu[0] = m;
             }
@@ -927,9 +939,10 @@ size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv)
 }
 
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
-                               int has_init, void *workspace, int U, int N, int dp, int dv,
+                               int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                hipStream_t s)
 {
+    has_init = (has_init ? 1 : 0) | (packed_state ? 2 : 0);   // the kernels' flag word
     (void)dp;
     const int slices = dv / DVS;
     SegTable segs;
@@ -937,9 +950,9 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
     const int G = make_segments(N, pick_segments(U, N, dv), segs);
     const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)k, *v16 = (const uint16_t *)v;
     hipError_t e;
-    if (has_init) {
+    if (has_init & 1) {
         hipLaunchKernelGGL((prefill_mfma_kernel<2>), dim3((unsigned)(U * slices)), dim3(NT), 0, s, q16, k16,
-                           v16, (uint16_t *)y, state, 1, (float *)workspace, N, dv, segs, G);
+                           v16, (uint16_t *)y, state, has_init, (float *)workspace, N, dv, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {

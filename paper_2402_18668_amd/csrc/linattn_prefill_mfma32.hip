@@ -131,20 +131,25 @@ __device__ __forceinline__ size_t ws_slot_off(int slot, int j, int lane)
 }
 
 // Canonical state rows (Eq. 4 order) of a packed row; a pair row has two (equal for delta = 0).
+// With packed_state the buffer is the packed layout (one row per unordered pair: a single row).
 struct CanonRows { int r1, r2; };   // r1 < 0: padding
-__device__ __forceinline__ CanonRows canon_pair(int a, int b)
+__device__ __forceinline__ CanonRows canon_pair(int a, int b, bool packed_state)
 {
+    if (packed_state) {
+        const int r = packed_pair_row(DP, min(a, b), max(a, b));
+        return {r, r};
+    }
     return {1 + DP + a * DP + b, 1 + DP + b * DP + a};
 }
-__device__ __forceinline__ CanonRows canon_rows_main(int delta, int fl)
+__device__ __forceinline__ CanonRows canon_rows_main(int delta, int fl, bool packed_state)
 {
-    return canon_pair(fl, (fl + delta) & (DP - 1));
+    return canon_pair(fl, (fl + delta) & (DP - 1), packed_state);
 }
 __device__ __forceinline__ CanonRows canon_rows_e1(int fl) { return {1 + fl, 1 + fl}; }
-__device__ __forceinline__ CanonRows canon_rows_e2(int fl)
+__device__ __forceinline__ CanonRows canon_rows_e2(int fl, bool packed_state)
 {
     if (fl == 0) return {0, 0};
-    if (fl >= 16) return canon_pair(fl - 16, fl);
+    if (fl >= 16) return canon_pair(fl - 16, fl, packed_state);
     return {-1, -1};
 }
 
@@ -162,6 +167,9 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 {
     __shared__ __align__(16) Lds lds;
 
+    // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
+    const bool packed_state = (has_init & 2) != 0;
+    has_init &= 1;
     const int tid = threadIdx.x;
     const int w = tid >> 6;
     const int lane = tid & 63;
@@ -182,8 +190,9 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
     const uint16_t *ku = k + (size_t)u * N * DP;
     const uint16_t *vu = v + (size_t)u * N * dv + col0;
     uint16_t *yu = y + (size_t)u * N * dv + col0;
-    float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
-    float *zu = Su ? Su + (size_t)feature_dim(DP) * dv : nullptr;
+    float *Su = state ? state + (size_t)u * (packed_state ? packed_state_stride(DP, dv) : state_stride(DP, dv))
+                      : nullptr;
+    float *zu = Su ? Su + (size_t)(packed_state ? packed_feature_dim(DP) : feature_dim(DP)) * dv : nullptr;
     float *ws_unit = ws + ((size_t)(u * slices + slice) * G) * kWsEntryFloats;
 
     // ---- accumulators -------------------------------------------------------------------------
@@ -233,11 +242,11 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
-            for (int tt = 0; tt < TPW; ++tt) S[tt][r] = fetch(canon_rows_main(4 * w + tt, fl));
+            for (int tt = 0; tt < TPW; ++tt) S[tt][r] = fetch(canon_rows_main(4 * w + tt, fl, packed_state));
             if (w == 2) X[r] = fetch(canon_rows_e1(fl));
-            else if (w == 0) X[r] = fetch(canon_rows_e2(fl));
+            else if (w == 0) X[r] = fetch(canon_rows_e2(fl, packed_state));
             else if (w == 3) {   // M[a][b] = sqrt(2) x the symmetric part of z's pair rows, a = fl, b = n
-                const CanonRows cr = canon_pair(fl, n);
+                const CanonRows cr = canon_pair(fl, n, packed_state);
                 X[r] = kRsqrt2 * (zu[cr.r1] + zu[cr.r2]);
             }
         }
@@ -622,10 +631,11 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
         for (int r = 0; r < 16; ++r) {
             const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
 #pragma unroll
-            for (int tt = 0; tt < TPW; ++tt) emit(canon_rows_main(4 * w + tt, fl), S[tt][r]);
+            for (int tt = 0; tt < TPW; ++tt) emit(canon_rows_main(4 * w + tt, fl, packed_state), S[tt][r]);
             if (w == 2) emit(canon_rows_e1(fl), X[r]);
-            else if (w == 0) emit(canon_rows_e2(fl), X[r]);
-            else if (w == 3 && slice == 0) zu[1 + DP + fl * DP + n] = kRsqrt2 * X[r];
+            else if (w == 0) emit(canon_rows_e2(fl, packed_state), X[r]);
+            else if (w == 3 && slice == 0 && (!packed_state || fl <= n))
+                zu[canon_pair(fl, n, packed_state).r1] = kRsqrt2 * X[r];
         }
         if (w == 3 && slice == 0 && g == 0) {
             zu[1 + n] = z1;
@@ -677,9 +687,10 @@ size_t prefill_mfma32_workspace_bytes(int U, int N, int dp, int dv)
 }
 
 hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, void *y, float *state,
-                                 int has_init, void *workspace, int U, int N, int dp, int dv,
+                                 int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                  hipStream_t s)
 {
+    has_init = (has_init ? 1 : 0) | (packed_state ? 2 : 0);   // the kernels' flag word
     using namespace dp32;
     (void)dp;
     const int slices = dv / DVS;
@@ -688,9 +699,9 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, vo
     const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)k, *v16 = (const uint16_t *)v;
     float *ws = static_cast<float *>(workspace);
     hipError_t e;
-    if (has_init) {
+    if (has_init & 1) {
         hipLaunchKernelGGL((prefill_kernel<2>), dim3((unsigned)(U * slices)), dim3(NT), 0, s, q16, k16, v16,
-                           (uint16_t *)y, state, 1, ws, N, dv, segs, G);
+                           (uint16_t *)y, state, has_init, ws, N, dv, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (G > 1) {

@@ -83,6 +83,9 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_decode_step_packed(p, p, p, p, null, 1, 1, 16, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_decode_step_packed(p, p, p, p, p, 1, 1, 16, 32, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_decode_fused_packed(p, p, p, p, p, 16, 64, p, p, p, p, p, 0, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill_packed(p, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 0, st) == based.ERR_UNSUPPORTED   # fp32
+    assert lib.based_prefill_packed(p, p, p, p, null, 1, p, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG     # no state
+    assert lib.based_prefill_packed(p, p, p, p, p, 0, null, 1, 1, 8, 32, 64, 1, st) == based.ERR_INVALID_ARG     # no workspace
     assert lib.based_state_pack(p, null, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_unpack(p, p, 1, 1, 12, 64, st) == based.ERR_UNSUPPORTED
     # position bookkeeping

@@ -494,6 +494,48 @@ def test_decode_steps_packed_state(based, dtype, dp, dv):
     check_close(down(zg).reshape(zd.shape), zd, TOL["f32"], "packed decode final z")
 
 
+@pytest.mark.parametrize("dp,dv,N,N1", [(16, 64, 300, 130), (16, 128, 1400, 1100), (32, 64, 300, 130),
+                                        (32, 128, 1700, 600)])
+def test_prefill_packed_state(based, dp, dv, N, N1):
+    """based_prefill_packed: the same y as the oracle over a split sequence (second part starting from
+    the packed state of the first), the packed state equals pack(state of based_prefill) bit for bit,
+    and packed decode continues from it."""
+    dtype = "bf16"
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, T = 1, 3, 3
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N + T)
+    want = oracle.linattn_quadratic(q, k, v)
+
+    def part(a, lo, hi, d):
+        return up(a[:, lo:hi], dtype, (B, H, hi - lo, d))
+
+    packed = based.alloc_packed_state(B, H, dp, dv)
+    y1 = based.prefill(part(q, 0, N1, dp), part(k, 0, N1, dp), part(v, 0, N1, dv), state=packed, packed=True)
+    # the unpacked call on the same tokens, then packed: identical buffers
+    state = based.alloc_state(B, H, dp, dv)
+    based.prefill(part(q, 0, N1, dp), part(k, 0, N1, dp), part(v, 0, N1, dv), state=state)
+    ref = based.alloc_packed_state(B, H, dp, dv)
+    based.state_pack(state, ref, B, H, dp, dv)
+    torch.cuda.synchronize()
+    assert torch.equal(packed, ref)
+    y2 = based.prefill(part(q, N1, N, dp), part(k, N1, N, dp), part(v, N1, N, dv), state=packed, has_init=True,
+                       packed=True)
+    torch.cuda.synchronize()
+    check_close(rows(down(y1).reshape(U, N1, dv)), rows(want[:, :N1]), TOL[dtype], "packed prefill part 1")
+    check_close(rows(down(y2).reshape(U, N - N1, dv)), rows(want[:, N1:N]), TOL[dtype], "packed prefill part 2")
+    for t in range(N, N + T):
+        y = based.decode_step(up(q[:, t], dtype, (B, H, dp)), up(k[:, t], dtype, (B, H, dp)),
+                              up(v[:, t], dtype, (B, H, dv)), packed, packed=True)
+        check_close(down(y).reshape(U, dv), want[:, t], TOL[dtype], f"decode after packed prefill, token {t}")
+    back = based.alloc_state(B, H, dp, dv)
+    based.state_unpack(packed, back, B, H, dp, dv)
+    Sg, zg = based.state_export(back, B, H, dp, dv)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(Sg).reshape(Sw.shape), Sw, TOL[dtype], "state after packed prefill + decode")
+    check_close(down(zg).reshape(zw.shape), zw, TOL[dtype], "K-state after packed prefill + decode")
+
+
 def test_decode_fused_packed_equals_separate(based):
     wl = make_wl("decode_1p3b", dtype="bf16")
     B, H, N0, T = 2, 2, 70, 4
