@@ -460,6 +460,63 @@ def test_prefill_graph_replay(based):
         assert torch.equal(y2, y_eager)
 
 
+@pytest.mark.parametrize("dp", [16, 32])
+def test_whole_step_graph_replay(based, dp):
+    """Linear-attention prefill (with final state), window prefill (with ring fill) and the fused decode
+    step of the next token captured as one graph: every replay reproduces the eager results bit for bit.
+    (d' = 32: three prefill launches handing data through the workspace.)"""
+    wl = make_wl("prefill_360m", d_feat=dp)
+    B, H, N = 1, 2, 1300
+    dv, dh, w = wl.d_v, wl.d_h, wl.w
+    scale = 1.0 / math.sqrt(dh)
+    q, k, v = lin_case(wl, B, H, N)
+    sq, sk, sv = synth.swa_inputs(wl, units=B * H, N=N)
+    dec = synth.decode_inputs(wl, 1, units=B * H)
+    tq, tk, tv = (up(a, "bf16", (B, H, N, a.shape[-1])) for a in (q, k, v))
+    tsq, tsk, tsv = (up(a, "bf16", (B, H, N, dh)) for a in (sq, sk, sv))
+    tok = [up(dec[n][0], "bf16", (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+    ws = based.alloc_prefill_workspace(B, H, N, dp, dv, based.BF16)
+
+    def step(bufs):
+        y, sy, state, ring, yl, ys = bufs
+        state.zero_()
+        based.prefill(tq, tk, tv, y=y, state=state, workspace=ws)
+        based.swa_prefill(tsq, tsk, tsv, w, scale, y=sy, ring=ring)
+        based.decode_fused(*tok[:3], state, *tok[3:], ring, N + 1, w, scale, y_lin=yl, y_swa=ys)
+
+    def bufs():
+        return (torch.empty((B, H, N, dv), dtype=torch.bfloat16, device="cuda"),
+                torch.empty((B, H, N, dh), dtype=torch.bfloat16, device="cuda"),
+                based.alloc_state(B, H, dp, dv), based.alloc_swa_ring(B, H, w, dh, torch.bfloat16),
+                torch.empty((B, H, dv), dtype=torch.bfloat16, device="cuda"),
+                torch.empty((B, H, dh), dtype=torch.bfloat16, device="cuda"))
+
+    eager = bufs()
+    step(eager)
+    torch.cuda.synchronize()
+    check_close(rows(down(eager[0]).reshape(B * H, N, dv)), rows(oracle.linattn_quadratic(q, k, v)), TOL["bf16"],
+                "eager prefill of the captured step")
+    g = bufs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(g)
+    for rep in range(3):
+        for t in g:
+            t.fill_(1) if t.dtype == torch.float32 else t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("y", "swa y", "state", "ring", "decode y_lin", "decode y_swa"), g, eager):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager result"
+        step(bufs())   # eager work on the same workspace between replays
+        torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------------------------------------
 # packed state (one row per unordered feature pair)
 # ------------------------------------------------------------------------------------------------
