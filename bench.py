@@ -196,6 +196,33 @@ def main() -> int:
         "swa_prefill": {"tokens_per_s": round(B * N / (swa_ms * 1e-3), 1), "roofline": swa_roofline},
     }
 
+    # ---- the same step as captured graphs (one per buffer set), replayed: launch gaps and event markers gone
+    if not args.no_graph_leg:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(NSETS):
+                step(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = []
+        for i in range(NSETS):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                step(i)
+            graphs.append(gr)
+        for i in range(args.warmup):
+            graphs[i % NSETS].replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % NSETS].replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        out["step_graph_replay"] = {"ms_per_step": round(g_ms, 4),
+                                    "tokens_per_s": round(tokens_per_step / (g_ms * 1e-3), 1)}
+        del graphs
+
     # ---- decode leg: 1.3B-shaped, batch 128, fused state update/readout + ring attention ---------
     if not args.no_decode_leg:
         out["decode"] = decode_leg(torch, based, synth, dev, args.decode_steps, not args.no_graph_leg)
