@@ -55,8 +55,8 @@ def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--decode-steps", type=int, default=1024, help="steps of the batch-128 decode leg")
     ap.add_argument("--workload", default="prefill_360m", choices=["prefill_360m", "prefill_1p3b", "prefill_long"],
                     help="prefill workload of the step; the metric is quoted on the default, the others are "
