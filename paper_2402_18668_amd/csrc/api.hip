@@ -229,7 +229,7 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
                      int H, int d_h, int w, float scale, int dtype, void *stream)
 {
     if (pos < 1) return BASED_ERR_INVALID_ARG;
-    return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H}, B, H, d_h, w, scale, dtype, stream);
+    return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H, 0}, B, H, d_h, w, scale, dtype, stream);
 }
 
 int based_positions_advance(int *pos, int B, void *stream)
@@ -243,7 +243,7 @@ int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y
                             void *stream)
 {
     if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u)) return BASED_ERR_INVALID_ARG;
-    return swa_decode_any(q, k, v, y, ring, PosArg{0, pos, H}, B, H, d_h, w, scale, dtype, stream);
+    return swa_decode_any(q, k, v, y, ring, PosArg{0, pos, H, 0}, B, H, d_h, w, scale, dtype, stream);
 }
 
 static int decode_fused_any(const void *q, const void *k, const void *v, void *y_lin, void *state,
@@ -270,7 +270,7 @@ int based_decode_fused(const void *q, const void *k, const void *v, void *y_lin,
 {
     if (pos < 1) return BASED_ERR_INVALID_ARG;
     return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
-                            PosArg{pos, nullptr, H}, d_h, w, scale, B, H, dtype, 0, stream);
+                            PosArg{pos, nullptr, H, 0}, d_h, w, scale, B, H, dtype, 0, stream);
 }
 
 int based_decode_fused_packed(const void *q, const void *k, const void *v, void *y_lin, void *packed,
@@ -280,7 +280,7 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
 {
     if (pos < 1) return BASED_ERR_INVALID_ARG;
     return decode_fused_any(q, k, v, y_lin, packed, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
-                            PosArg{pos, nullptr, H}, d_h, w, scale, B, H, dtype, 1, stream);
+                            PosArg{pos, nullptr, H, 0}, d_h, w, scale, B, H, dtype, 1, stream);
 }
 
 int based_decode_fused_ragged(const void *q, const void *k, const void *v, void *y_lin, void *state,
@@ -290,7 +290,7 @@ int based_decode_fused_ragged(const void *q, const void *k, const void *v, void 
 {
     if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u)) return BASED_ERR_INVALID_ARG;
     return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
-                            PosArg{0, pos, H}, d_h, w, scale, B, H, dtype, packed ? 1 : 0, stream);
+                            PosArg{0, pos, H, 0}, d_h, w, scale, B, H, dtype, packed ? 1 : 0, stream);
 }
 
 }  // extern "C"

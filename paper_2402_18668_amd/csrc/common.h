@@ -97,6 +97,7 @@ struct PosArg {
     int pos;
     const int *per_seq;
     int H;
+    int ring_stream;   // set by the fused launcher: read the ring with non-temporal loads (see there)
 };
 hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
                              PosArg pos, int U, int dh, int w, float scale, int dtype, hipStream_t s);
