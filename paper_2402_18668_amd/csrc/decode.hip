@@ -8,6 +8,8 @@
 // features, the softmax scores and the cross-wave partial sums.
 #include "common.h"
 
+#include <atomic>
+
 namespace based {
 
 constexpr int kDecodeThreads = 256;
@@ -322,9 +324,11 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
 // ---------------------------------------------------------------------------------------------
 template <int DP, int DV, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q, const T *k,
-                                                                     const T *v, T *y, float *state)
+                                                                     const T *v, T *y, float *state,
+                                                                     int reverse)
 {
-    decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state, blockIdx.x);
+    decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state,
+                                        reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x);
 }
 
 template <int DH, int W, typename T>
@@ -339,13 +343,18 @@ __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, 
 
 // Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
 // the window attention step.  (Interleaving the two kinds block by block measured 15 % slower.)
+// reverse: the units are walked from the last to the first.  Consecutive decode steps alternate the
+// direction, so that a step starts with the state the step before it touched last, which is what
+// the last-level cache still holds when the whole state does not fit (batch 192, d_v 128, 433 MB of
+// state: 188 -> 149 us per fused step; neutral when it fits).
 template <int DP, int DV, int DH, int W, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
     const T *q, const T *k, const T *v, T *y_lin, float *state, const T *sq, const T *sk,
-    const T *sv, T *y_swa, T *ring, PosArg pa, float scale, int U)
+    const T *sv, T *y_swa, T *ring, PosArg pa, float scale, int U, int reverse)
 {
     const bool lin = (int)blockIdx.x < U;
-    const int u = lin ? blockIdx.x : blockIdx.x - U;
+    const int ub = lin ? blockIdx.x : blockIdx.x - U;
+    const int u = reverse ? U - 1 - ub : ub;
     const int pos = resolve_pos(pa, u);
     if (pos < 1) {
         if (lin) zero_row(y_lin + (size_t)u * DV, DV);
@@ -384,16 +393,31 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
         else { CALL(a1, b1); }                                    \
     } while (0)
 
+// Direction of the sweep over the units.  For a state well beyond the 256 MB last-level cache it
+// alternates from one launch of the process to the next; a state that fits, or nearly fits (batch 128,
+// d_v 128: 288 MB), is served better by the cache as it is (85.3 against 90.6 us per state update).
+static int next_direction(size_t state_bytes)
+{
+    static std::atomic<unsigned> calls{0};
+    if (state_bytes <= ((size_t)340 << 20)) return 0;
+    return (int)(calls.fetch_add(1, std::memory_order_relaxed) & 1u);
+}
+template <int DP, int DV> static size_t state_bytes_of(int U, int packed)
+{
+    return (size_t)U * (packed ? packed_state_stride(DP, DV) : state_stride(DP, DV)) * sizeof(float);
+}
+
 template <int DP, int DV, typename T>
 static void step_pick(const void *q, const void *k, const void *v, void *y, float *state, int U,
                       int packed, hipStream_t s)
 {
+    const int reverse = next_direction(state_bytes_of<DP, DV>(U, packed));
     if (packed)
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, true>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse);
     else
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, false>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse);
 }
 
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
@@ -429,11 +453,12 @@ static void fused_pick(const void *q, const void *k, const void *v, void *y_lin,
                        const void *sq, const void *sk, const void *sv, void *y_swa, void *ring,
                        PosArg pos, int dh, int w, float scale, int U, hipStream_t s)
 {
+    const int reverse = next_direction(state_bytes_of<DP, DV>(U, PACKED ? 1 : 0));
 #define CALL_F(DH_, W_)                                                                           \
     hipLaunchKernelGGL((decode_fused_kernel<DP, DV, DH_, W_, T, PACKED>), dim3(2 * U),            \
                        dim3(kDecodeThreads), 0, s, (const T *)q, (const T *)k, (const T *)v,      \
                        (T *)y_lin, state, (const T *)sq, (const T *)sk, (const T *)sv,            \
-                       (T *)y_swa, (T *)ring, pos, scale, U)
+                       (T *)y_swa, (T *)ring, pos, scale, U, reverse)
     BASED_PICK_SWA(dh, w, CALL_F);
 #undef CALL_F
 }
