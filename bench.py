@@ -37,10 +37,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 158780433     # based_prefill (prefill_360m)
+MEASURED_PREFILL_TRAFFIC_BYTES = 158803833     # based_prefill (prefill_360m)
 MEASURED_SWA_TRAFFIC_BYTES = 142835642         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 579118293      # decode_step_kernel (decode_1p3b)
-MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325385548   # decode_step_kernel on the packed state (decode_1p3b)
+MEASURED_DECODE_TRAFFIC_BYTES = 579123709      # decode_step_kernel (decode_1p3b)
+MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325370100   # decode_step_kernel on the packed state (decode_1p3b)
 
 
 def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool = True) -> int:
