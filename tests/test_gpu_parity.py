@@ -333,6 +333,27 @@ def test_full_size_prefill_sampled_rows(based, name):
     assert (y[units] <= hi + slack).all() and (y[units] >= lo - slack).all()
 
 
+def test_full_size_window16_sampled_rows(based):
+    """The 1.3B-layer-shaped window attention at the window the paper's 1.4B model uses (16; training
+    table in the appendix), full size: sampled rows of sampled units, and the decode ring it leaves."""
+    wl = make_wl("prefill_1p3b", w=16)
+    B, H, N, U, dh, w = wl.B, wl.H, wl.N, wl.units, wl.d_h, wl.w
+    sq, sk, sv = synth.swa_inputs(wl)
+    scale = 1.0 / math.sqrt(dh)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[wl.dtype])
+    ys = based.swa_prefill(up(sq, wl.dtype, (B, H, N, dh)), up(sk, wl.dtype, (B, H, N, dh)),
+                           up(sv, wl.dtype, (B, H, N, dh)), w, scale, ring=ring)
+    torch.cuda.synchronize()
+    units = np.array([0, 1, U // 2, U - 1])
+    sample = np.array([0, 1, 14, 15, 16, 17, 127, 128, 129, 1023, 1024, N - 2, N - 1])
+    want = oracle.swa_rows(sq[units], sk[units], sv[units], w, scale, sample)
+    check_close(rows(down(ys).reshape(U, N, dh)[units][:, sample]), rows(want), TOL[wl.dtype], "window-16 sampled rows")
+    r = down(ring).reshape(U, 2, w, dh)
+    for j in range(N - w, N):
+        assert np.array_equal(r[units, 0, j % w], sk[units, j].astype(np.float64))
+        assert np.array_equal(r[units, 1, j % w], sv[units, j].astype(np.float64))
+
+
 def test_full_size_decode_sampled_units(based):
     """The batch-128 decode workload in the launch shape the benchmark times (2048 units): a short
     prefill builds state and ring, then fused decode steps; sampled units against the oracle."""
