@@ -207,6 +207,18 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
  * device).  Errors: BASED_ERR_INVALID_ARG for a null pointer or B < 1.
  */
 int based_positions_advance(int *pos, int B, void *stream);
+
+/*
+ * based_linear -- a bias-free linear projection, y = x W^T: the q / k / v projections that feed the
+ * mixers and the output projection after them (the block of Sec. 3; the architecture listing in the
+ * appendix gives all four as linear layers without bias).  A plain dense product on the matrix
+ * cores, bf16 in and out, fp32 accumulation; not part of the mixers' hot path.
+ *   x [M][K] in,  W [N][K] in (one row per output feature),  y [M][N] out; all BASED_BF16, device.
+ *   Supported: K a multiple of 64, N a multiple of 128, any M >= 1; dtype BASED_BF16.
+ *   Errors: BASED_ERR_UNSUPPORTED for other sizes or dtype, BASED_ERR_INVALID_ARG for null or
+ *   misaligned pointers or non-positive sizes.
+ */
+int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int dtype, void *stream);
 int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
                             const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
                             void *stream);

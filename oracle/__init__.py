@@ -177,3 +177,14 @@ def swa_rows(q, k, v, w: int, scale: float, rows) -> np.ndarray:
                             y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), U, N, dh, int(w),
                             float(scale))
     return y
+
+
+def linear(x, W) -> np.ndarray:
+    """Bias-free linear projection ``y = x W^T`` (the q / k / v / output projections around the mixers,
+    Sec. 3; the architecture listing gives them as bias-free linear layers): ``x [M, K]``, ``W [N, K]`` ->
+    ``[M, N]``, fp64.  The definition written out with the library matrix product."""
+    x = np.asarray(x, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    if x.ndim != 2 or W.ndim != 2 or x.shape[1] != W.shape[1]:
+        raise ValueError("x [M, K], W [N, K]")
+    return x @ W.T

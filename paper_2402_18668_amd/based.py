@@ -27,7 +27,7 @@ EXPORTS = [
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
     "based_prefill_packed",
-    "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance",
+    "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
 ]
 
 
@@ -90,6 +90,8 @@ def _load() -> ctypes.CDLL:
     lib.based_decode_fused_ragged.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, f, i, i, i, vp]
     lib.based_prefill_packed.restype = i
     lib.based_prefill_packed.argtypes = lib.based_prefill.argtypes
+    lib.based_linear.restype = i
+    lib.based_linear.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
     lib.based_positions_advance.argtypes = [vp, i, vp]
     return lib
@@ -289,6 +291,22 @@ def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
 def _check_pos(pos, B):
     if pos.dtype != torch.int32 or pos.numel() != B or not pos.is_cuda or not pos.is_contiguous():
         raise ValueError("per-sequence positions must be a contiguous int32 device tensor of B elements")
+
+
+def linear(x, W, y=None):
+    """based_linear: ``y = x W^T``; x ``[..., K]``, W ``[N, K]`` (bf16); returns y ``[..., N]``."""
+    _dev(x, W, y)
+    K = x.shape[-1]
+    N = W.shape[0]
+    M = x.numel() // K
+    if W.shape != (N, K) or W.dtype != x.dtype or not x.is_contiguous() or not W.is_contiguous():
+        raise ValueError("x [..., K] and W [N, K] must be contiguous and of one dtype")
+    if y is None:
+        y = torch.empty((*x.shape[:-1], N), dtype=x.dtype, device=x.device)
+    elif y.numel() != M * N or y.dtype != x.dtype or not y.is_contiguous():
+        raise ValueError("y must be [..., N], contiguous, of x's dtype")
+    _check(lib.based_linear(_ptr(x), _ptr(W), _ptr(y), M, K, N, _dtype_code(x), _stream()), "based_linear")
+    return y
 
 
 def positions_advance(pos):

@@ -232,6 +232,15 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
     return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H, 0}, B, H, d_h, w, scale, dtype, stream);
 }
 
+int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int dtype, void *stream)
+{
+    if (M < 1 || K < 1 || N < 1) return BASED_ERR_INVALID_ARG;
+    if ((unsigned long long)M * (unsigned long long)(K > N ? K : N) >= (1ull << 40)) return BASED_ERR_INVALID_ARG;
+    if (!linear_supported(M, K, N, dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(x) || !ok_ptr(W) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_linear(x, W, y, M, K, N, (hipStream_t)stream));
+}
+
 int based_positions_advance(int *pos, int B, void *stream)
 {
     if (!pos || B < 1) return BASED_ERR_INVALID_ARG;

@@ -111,5 +111,7 @@ hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, in
 hipError_t launch_state_repack(float *state, float *packed, int U, int dp, int dv, int to_packed,
                                hipStream_t s);
 hipError_t launch_positions_advance(int *pos, int B, hipStream_t s);
+bool linear_supported(int M, int K, int N, int dtype);
+hipError_t launch_linear(const void *x, const void *W, void *y, int M, int K, int N, hipStream_t s);
 
 }  // namespace based

@@ -1,0 +1,172 @@
+// Bias-free linear projection y = x W^T on the gfx950 matrix cores (bf16 in, fp32 accumulate, bf16
+// out): the q / k / v and output projections that surround the sequence mixers in a Based block
+// (architecture of Sec. 3: projections of the d_model-wide input to H d' features for q and k and
+// H d_v for v, and of the H d_v mixer output back to d_model; all without bias).
+//
+// x [M][K] and W [N][K] are both contiguous along K, so both MFMA operands are 16 contiguous bytes
+// of a row per lane.  One workgroup of four waves computes a 128 x 128 tile of y; each wave a
+// 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32 (computed transposed: rows = output features,
+// columns = tokens, so that a lane holds runs of 4 consecutive features of one token).  The K
+// dimension is walked in steps of 64 through two LDS buffers: the rows of the next step are fetched
+// into registers while the current one is multiplied, and written to the other buffer after it, one
+// barrier a step.  The finished tile is turned through LDS and leaves as 128-byte row segments.
+//
+// Workgroups that share rows of x run back to back on the same XCD (its L2 then serves x once per
+// row of tiles): block b belongs to XCD b % 8, which walks its own rows of tiles one after another.
+#include "common.h"
+
+namespace based {
+
+namespace lin {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BM = 128;        // tokens per workgroup tile
+constexpr int BN = 128;        // output features per workgroup tile
+constexpr int BK = 64;         // K step
+constexpr int NT = 256;
+constexpr int LD = BK + 8;     // bf16 elements per staged row (144-byte stride: 16-byte reads of 8 rows hit 32 banks)
+constexpr int OUT_LD = 64 + 8; // bf16 elements per row of a wave's output staging tile
+constexpr int kXcds = 8;
+
+struct Lds {
+    uint16_t a[2][BM][LD];     // rows of x
+    uint16_t b[2][BN][LD];     // rows of W
+};
+static_assert(sizeof(Lds) <= 80 * 1024, "two workgroups per CU");
+static_assert(4 * 64 * OUT_LD * 2 <= (int)sizeof(Lds), "the output staging reuses the operand buffers");
+
+__device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+}
+
+// K % 64 == 0, N % 128 == 0 (checked by the launcher); any M >= 1.
+__global__ __launch_bounds__(NT, 2) void linear_kernel(const uint16_t *__restrict__ x,
+                                                       const uint16_t *__restrict__ W,
+                                                       uint16_t *__restrict__ y, int M, int K, int N,
+                                                       int tiles_m, int tiles_n)
+{
+    __shared__ __align__(16) Lds lds;
+
+    // block -> tile: XCD (b % 8) owns the rows of tiles xcd, xcd + 8, ... and walks each along N
+    const int b = blockIdx.x;
+    const int xcd = b % kXcds, local = b / kXcds;
+    const int tm = (local / tiles_n) * kXcds + xcd, tn = local % tiles_n;
+    if (tm >= tiles_m) return;   // uniform: the grid is padded to a multiple of 8 rows of tiles
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63, g = lane >> 5, n = lane & 31;
+    const int wm = w >> 1, wn = w & 1;   // this wave's quarter: tokens 64 wm .., features 64 wn ..
+    const int row0 = tm * BM, col0 = tn * BN;
+
+    // staging: thread t moves 16-byte chunk (t % 8) of rows t / 8 + 32 it, it = 0..3, of both tiles
+    const int s_chunk = tid & 7, s_row = tid >> 3;
+    const uint16_t *xa[4], *wb[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int r = s_row + 32 * it;
+        xa[it] = x + (size_t)min(row0 + r, M - 1) * K + 8 * s_chunk;   // rows past M re-read the last one
+        wb[it] = W + (size_t)(col0 + r) * K + 8 * s_chunk;
+    }
+    u32x4 ra[4], rb[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            ra[it] = *reinterpret_cast<const u32x4 *>(xa[it] + k0);
+            rb[it] = *reinterpret_cast<const u32x4 *>(wb[it] + k0);
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            *reinterpret_cast<u32x4 *>(&lds.a[buf][s_row + 32 * it][8 * s_chunk]) = ra[it];
+            *reinterpret_cast<u32x4 *>(&lds.b[buf][s_row + 32 * it][8 * s_chunk]) = rb[it];
+        }
+    };
+
+    // acc[j][i]: features 64 wn + 32 j .. (rows of the MFMA tile) x tokens 64 wm + 32 i .. (columns)
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    const int steps = K / BK;
+    for (int kt = 0; kt < steps; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < steps;
+        if (more) fetch((kt + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            u32x4 fw[2], fx[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fw[j] = *reinterpret_cast<const u32x4 *>(&lds.b[buf][64 * wn + 32 * j + n][16 * ks + 8 * g]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                fx[i] = *reinterpret_cast<const u32x4 *>(&lds.a[buf][64 * wm + 32 * i + n][16 * ks + 8 * g]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) acc[j][i] = mfma(fw[j], fx[i], acc[j][i]);
+        }
+        if (more) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane (g, n) of tile (j, i) holds token 64 wm + 32 i + n, features 64 wn + 32 j + 8 (r / 4) +
+    // 4 g + r % 4.  Through this wave's staging rows [64 tokens][64 features], then 128-byte row segments.
+    uint16_t *out = reinterpret_cast<uint16_t *>(&lds) + (size_t)w * 64 * OUT_LD;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = acc[j][i][4 * q4 + e];
+                const bf16x4 hv = __builtin_convertvector(o, bf16x4);
+                *reinterpret_cast<u32x2 *>(out + (size_t)(32 * i + n) * OUT_LD + 32 * j + 8 * q4 + 4 * g) =
+                    __builtin_bit_cast(u32x2, hv);
+            }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own tile is complete in LDS
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int r = 8 * it + (lane >> 3), c = lane & 7;
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(out + (size_t)r * OUT_LD + 8 * c);
+        const int row = row0 + 64 * wm + r;
+        if (row < M) *reinterpret_cast<u32x4 *>(y + (size_t)row * N + col0 + 64 * wn + 8 * c) = val;
+    }
+}
+
+}  // namespace lin
+
+bool linear_supported(int M, int K, int N, int dtype)
+{
+    return dtype == BASED_BF16 && M >= 1 && K >= lin::BK && K % lin::BK == 0 && N >= lin::BN && N % lin::BN == 0;
+}
+
+hipError_t launch_linear(const void *x, const void *W, void *y, int M, int K, int N, hipStream_t s)
+{
+    using namespace lin;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int rows_padded = (tiles_m + kXcds - 1) / kXcds * kXcds;
+    hipLaunchKernelGGL(linear_kernel, dim3((unsigned)((size_t)rows_padded * tiles_n)), dim3(NT), 0, s,
+                       (const uint16_t *)x, (const uint16_t *)W, (uint16_t *)y, M, K, N, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace based

@@ -138,3 +138,14 @@ def decode_inputs(wl: Workload, steps: int, units: int | None = None):
         "swa_k": tensor(wl, T_DECODE + 4, (steps, U, wl.d_h), wl.swa_qk_scale),
         "swa_v": tensor(wl, T_DECODE + 5, (steps, U, wl.d_h), wl.v_scale),
     }
+
+
+T_LINEAR = 40   # tensor indices of the projection inputs
+
+
+def linear_inputs(index: int, M: int, K: int, N: int, dtype: str = "bf16"):
+    """Inputs of a bias-free projection y = x W^T: activations x ``[M, K]`` ~ N(0, 1) and weights W ``[N, K]`` ~
+    N(0, 1) / sqrt(K) (unit-variance outputs), rounded to ``dtype``; ``index`` keys the draw."""
+    x = round_to(normal(seed_for(index, T_LINEAR), (M, K), 1.0), dtype)
+    W = round_to(normal(seed_for(index, T_LINEAR + 1), (N, K), 1.0 / np.sqrt(K)), dtype)
+    return x, W

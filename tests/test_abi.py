@@ -88,6 +88,12 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_prefill_packed(p, p, p, p, p, 0, null, 1, 1, 8, 32, 64, 1, st) == based.ERR_INVALID_ARG     # no workspace
     assert lib.based_state_pack(p, null, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_unpack(p, p, 1, 1, 12, 64, st) == based.ERR_UNSUPPORTED
+    # projection
+    assert lib.based_linear(null, p, p, 8, 64, 128, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_linear(p, p, p, 0, 64, 128, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_linear(p, p, p, 8, 48, 128, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_linear(p, p, p, 8, 64, 100, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_linear(p, p, p, 8, 64, 128, 0, st) == based.ERR_UNSUPPORTED
     # position bookkeeping
     assert lib.based_positions_advance(null, 4, st) == based.ERR_INVALID_ARG
     assert lib.based_positions_advance(p, 0, st) == based.ERR_INVALID_ARG

@@ -807,3 +807,26 @@ def test_full_size_long_config_sampled_rows(based):
     want = oracle.swa_rows(sq[units], sk[units], sv[units], wl.w, scale, sample)
     check_close(rows(down(ys).reshape(U, N, wl.d_h)[units][:, sample]), rows(want), TOL[wl.dtype],
                 "prefill_long swa sampled rows")
+
+
+# ------------------------------------------------------------------------------------------------
+# projections around the mixers
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M,K,N", [(300, 128, 128), (128, 64, 256), (1, 192, 128), (129, 1024, 384), (1000, 256, 1536)])
+def test_linear_projection(based, M, K, N):
+    """y = x W^T against the fp64 oracle: several tiles, ragged M (rows past the end of a tile), one row."""
+    x, W = synth.linear_inputs(7, M, K, N)
+    y = based.linear(up(x, "bf16"), up(W, "bf16"))
+    torch.cuda.synchronize()
+    check_close(down(y), oracle.linear(x, W), TOL["bf16"], f"linear {M}x{K}x{N}")
+
+
+def test_linear_projection_full_size_sampled(based):
+    """The fused q / k / v projection of the 360M-shaped layer (16384 tokens, d_model 1024 -> 16 heads x
+    (16 + 16 + 64)) at full size: sampled rows against the oracle, every output feature."""
+    M, K, N = 8 * 2048, 1024, 16 * (16 + 16 + 64)
+    x, W = synth.linear_inputs(8, M, K, N)
+    y = based.linear(up(x, "bf16"), up(W, "bf16"))
+    torch.cuda.synchronize()
+    sample = np.array([0, 1, 127, 128, 129, 4095, 8192, 12345, M - 2, M - 1])
+    check_close(down(y)[sample], oracle.linear(x[sample], W), TOL["bf16"], "qkv projection, sampled rows")

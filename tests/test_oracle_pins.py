@@ -332,5 +332,32 @@ def test_swa_special_cases():
         assert np.allclose(row, y[:, pos - 1], rtol=1e-12, atol=1e-13)
 
 
+def test_linear_projection_pins():
+    """y = x W^T against what fixes it: brute-force loops, the identity and a one-hot weight (picks a
+    column of x), a closed form with constant rows, and linearity in each argument (a transposed operand
+    or a swapped index fails the brute-force and the one-hot case)."""
+    g = rng(23)
+    M, K, N = 5, 7, 3
+    x = g.standard_normal((M, K)); W = g.standard_normal((N, K))
+    want = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            for kk in range(K):
+                want[m, n] += x[m, kk] * W[n, kk]
+    assert np.allclose(oracle.linear(x, W), want, rtol=1e-13, atol=1e-14)
+    assert np.array_equal(oracle.linear(x, np.eye(K)), x)
+    onehot = np.zeros((2, K)); onehot[0, 4] = 1.0; onehot[1, 1] = -2.0
+    assert np.array_equal(oracle.linear(x, onehot), np.stack([x[:, 4], -2.0 * x[:, 1]], axis=1))
+    # x row m constant c_m, W row n constant d_n: y[m, n] = K c_m d_n
+    c = g.standard_normal(M); d = g.standard_normal(N)
+    y = oracle.linear(np.repeat(c[:, None], K, 1), np.repeat(d[:, None], K, 1))
+    assert np.allclose(y, K * np.outer(c, d), rtol=1e-13, atol=0)
+    x2 = g.standard_normal((M, K)); W2 = g.standard_normal((N, K))
+    assert np.allclose(oracle.linear(2 * x + x2, W), 2 * oracle.linear(x, W) + oracle.linear(x2, W), rtol=1e-12, atol=1e-13)
+    assert np.allclose(oracle.linear(x, W - 3 * W2), oracle.linear(x, W) - 3 * oracle.linear(x, W2), rtol=1e-12, atol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.linear(x, g.standard_normal((N, K + 1)))
+
+
 def test_oracle_threads_reported():
     assert oracle.threads() >= 1
