@@ -4,12 +4,13 @@
 // H d_v for v, and of the H d_v mixer output back to d_model; all without bias).
 //
 // x [M][K] and W [N][K] are both contiguous along K, so both MFMA operands are 16 contiguous bytes
-// of a row per lane.  One workgroup of four waves computes a 128 x 128 tile of y; each wave a
-// 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32 (computed transposed: rows = output features,
-// columns = tokens, so that a lane holds runs of 4 consecutive features of one token).  The K
-// dimension is walked in steps of 64 through two LDS buffers: the rows of the next step are fetched
-// into registers while the current one is multiplied, and written to the other buffer after it, one
-// barrier a step.  The finished tile is turned through LDS and leaves as 128-byte row segments.
+// of a row per lane.  One workgroup of four waves computes a 256 x 128 tile of y (tokens x
+// features); each wave a 128 x 64 quarter as 4 x 2 MFMA tiles of 32 x 32 (computed transposed: rows
+// = output features, columns = tokens, so that a lane holds runs of 4 consecutive features of one
+// token): 6 operand reads of 16 bytes per lane feed 8 MFMAs, which keeps the LDS pipe below the
+// matrix pipe.  The K dimension is walked in steps of 64: the rows of the next step are fetched into
+// registers while the current one is multiplied and written to LDS between two barriers.  The
+// finished tile is turned through LDS and leaves as 128-byte row segments.
 //
 // Workgroups that share rows of x run back to back on the same XCD (its L2 then serves x once per
 // row of tiles): block b belongs to XCD b % 8, which walks its own rows of tiles one after another.
@@ -26,7 +27,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 128;        // tokens per workgroup tile
+constexpr int BM = 256;        // tokens per workgroup tile
 constexpr int BN = 128;        // output features per workgroup tile
 constexpr int BK = 64;         // K step
 constexpr int NT = 256;
@@ -34,9 +35,10 @@ constexpr int LD = BK + 8;     // bf16 elements per staged row (144-byte stride:
 constexpr int OUT_LD = 64 + 8; // bf16 elements per row of a wave's output staging tile
 constexpr int kXcds = 8;
 
+constexpr int TI = BM / 2 / 32;   // MFMA tiles along the tokens per wave
 struct Lds {
-    uint16_t a[2][BM][LD];     // rows of x
-    uint16_t b[2][BN][LD];     // rows of W
+    uint16_t a[BM][LD];        // rows of x
+    uint16_t b[BN][LD];        // rows of W
 };
 static_assert(sizeof(Lds) <= 80 * 1024, "two workgroups per CU");
 static_assert(4 * 64 * OUT_LD * 2 <= (int)sizeof(Lds), "the output staging reuses the operand buffers");
@@ -63,92 +65,97 @@ __global__ __launch_bounds__(NT, 2) void linear_kernel(const uint16_t *__restric
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, g = lane >> 5, n = lane & 31;
-    const int wm = w >> 1, wn = w & 1;   // this wave's quarter: tokens 64 wm .., features 64 wn ..
+    const int wm = w >> 1, wn = w & 1;   // this wave's quarter: tokens 128 wm .., features 64 wn ..
     const int row0 = tm * BM, col0 = tn * BN;
 
-    // staging: thread t moves 16-byte chunk (t % 8) of rows t / 8 + 32 it, it = 0..3, of both tiles
+    // staging: thread t moves 16-byte chunk (t % 8) of rows t / 8 + 32 it of the two tiles
+    constexpr int AIT = BM / 32, BIT = BN / 32;
     const int s_chunk = tid & 7, s_row = tid >> 3;
-    const uint16_t *xa[4], *wb[4];
+    const uint16_t *xa[AIT], *wb[BIT];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int r = s_row + 32 * it;
-        xa[it] = x + (size_t)min(row0 + r, M - 1) * K + 8 * s_chunk;   // rows past M re-read the last one
-        wb[it] = W + (size_t)(col0 + r) * K + 8 * s_chunk;
-    }
-    u32x4 ra[4], rb[4];
+    for (int it = 0; it < AIT; ++it)   // rows past M re-read the last one
+        xa[it] = x + (size_t)min(row0 + s_row + 32 * it, M - 1) * K + 8 * s_chunk;
+#pragma unroll
+    for (int it = 0; it < BIT; ++it) wb[it] = W + (size_t)(col0 + s_row + 32 * it) * K + 8 * s_chunk;
+    u32x4 ra[AIT], rb[BIT];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            ra[it] = *reinterpret_cast<const u32x4 *>(xa[it] + k0);
-            rb[it] = *reinterpret_cast<const u32x4 *>(wb[it] + k0);
-        }
-    };
-    auto stage = [&](int buf) {
+        for (int it = 0; it < AIT; ++it) ra[it] = *reinterpret_cast<const u32x4 *>(xa[it] + k0);
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            *reinterpret_cast<u32x4 *>(&lds.a[buf][s_row + 32 * it][8 * s_chunk]) = ra[it];
-            *reinterpret_cast<u32x4 *>(&lds.b[buf][s_row + 32 * it][8 * s_chunk]) = rb[it];
-        }
+        for (int it = 0; it < BIT; ++it) rb[it] = *reinterpret_cast<const u32x4 *>(wb[it] + k0);
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int it = 0; it < AIT; ++it) *reinterpret_cast<u32x4 *>(&lds.a[s_row + 32 * it][8 * s_chunk]) = ra[it];
+#pragma unroll
+        for (int it = 0; it < BIT; ++it) *reinterpret_cast<u32x4 *>(&lds.b[s_row + 32 * it][8 * s_chunk]) = rb[it];
     };
 
-    // acc[j][i]: features 64 wn + 32 j .. (rows of the MFMA tile) x tokens 64 wm + 32 i .. (columns)
-    f32x16 acc[2][2];
+    // acc[j][i]: features 64 wn + 32 j .. (rows of the MFMA tile) x tokens 128 wm + 32 i .. (columns)
+    f32x16 acc[2][TI];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
     fetch(0);
-    stage(0);
+    stage();
     __syncthreads();
     const int steps = K / BK;
     for (int kt = 0; kt < steps; ++kt) {
-        const int buf = kt & 1;
         const bool more = kt + 1 < steps;
         if (more) fetch((kt + 1) * BK);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            u32x4 fw[2], fx[2];
+            u32x4 fw[2], fx[TI];
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                fw[j] = *reinterpret_cast<const u32x4 *>(&lds.b[buf][64 * wn + 32 * j + n][16 * ks + 8 * g]);
+                fw[j] = *reinterpret_cast<const u32x4 *>(&lds.b[64 * wn + 32 * j + n][16 * ks + 8 * g]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fx[i] = *reinterpret_cast<const u32x4 *>(&lds.a[buf][64 * wm + 32 * i + n][16 * ks + 8 * g]);
+            for (int i = 0; i < TI; ++i)
+                fx[i] = *reinterpret_cast<const u32x4 *>(&lds.a[(BM / 2) * wm + 32 * i + n][16 * ks + 8 * g]);
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int i = 0; i < 2; ++i) acc[j][i] = mfma(fw[j], fx[i], acc[j][i]);
+                for (int i = 0; i < TI; ++i) acc[j][i] = mfma(fw[j], fx[i], acc[j][i]);
         }
-        if (more) stage(buf ^ 1);
-        __syncthreads();
+        __syncthreads();   // every wave is done reading this step's rows
+        if (more) {
+            stage();
+            __syncthreads();
+        }
     }
 
-    // epilogue: lane (g, n) of tile (j, i) holds token 64 wm + 32 i + n, features 64 wn + 32 j + 8 (r / 4) +
-    // 4 g + r % 4.  Through this wave's staging rows [64 tokens][64 features], then 128-byte row segments.
+    // epilogue: lane (g, n) of tile (j, i) holds token 128 wm + 32 i + n, features 64 wn + 32 j + 8 (r / 4) +
+    // 4 g + r % 4.  64 tokens at a time through this wave's staging rows [64 tokens][64 features], then
+    // 128-byte row segments.
     uint16_t *out = reinterpret_cast<uint16_t *>(&lds) + (size_t)w * 64 * OUT_LD;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int half = 0; half < TI / 2; ++half) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                f32x4 o;
+            for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = acc[j][i][4 * q4 + e];
-                const bf16x4 hv = __builtin_convertvector(o, bf16x4);
-                *reinterpret_cast<u32x2 *>(out + (size_t)(32 * i + n) * OUT_LD + 32 * j + 8 * q4 + 4 * g) =
-                    __builtin_bit_cast(u32x2, hv);
-            }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own tile is complete in LDS
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 o;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int r = 8 * it + (lane >> 3), c = lane & 7;
-        const u32x4 val = *reinterpret_cast<const u32x4 *>(out + (size_t)r * OUT_LD + 8 * c);
-        const int row = row0 + 64 * wm + r;
-        if (row < M) *reinterpret_cast<u32x4 *>(y + (size_t)row * N + col0 + 64 * wn + 8 * c) = val;
+                    for (int e = 0; e < 4; ++e) o[e] = acc[j][2 * half + i2][4 * q4 + e];
+                    const bf16x4 hv = __builtin_convertvector(o, bf16x4);
+                    *reinterpret_cast<u32x2 *>(out + (size_t)(32 * i2 + n) * OUT_LD + 32 * j + 8 * q4 + 4 * g) =
+                        __builtin_bit_cast(u32x2, hv);
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own 64 x 64 piece is complete in LDS
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = 8 * it + (lane >> 3), c = lane & 7;
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(out + (size_t)r * OUT_LD + 8 * c);
+            const int row = row0 + (BM / 2) * wm + 64 * half + r;
+            if (row < M) *reinterpret_cast<u32x4 *>(y + (size_t)row * N + col0 + 64 * wn + 8 * c) = val;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read back before the next piece overwrites it
     }
 }
 
