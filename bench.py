@@ -37,9 +37,9 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counters scaled by what they read for a plain 1 GiB copy: fetch x 2.000, write x 1.000).
 # They hold for the workloads this file times and for the kernels as committed with those summaries.
-MEASURED_PREFILL_TRAFFIC_BYTES = 158803833     # based_prefill (prefill_360m)
+MEASURED_PREFILL_TRAFFIC_BYTES = 158776377     # based_prefill (prefill_360m)
 MEASURED_SWA_TRAFFIC_BYTES = 142835642         # swa_prefill_mfma_kernel<64, 64> (prefill_360m)
-MEASURED_DECODE_TRAFFIC_BYTES = 579123709      # decode_step_kernel (decode_1p3b)
+MEASURED_DECODE_TRAFFIC_BYTES = 579130768      # decode_step_kernel (decode_1p3b)
 MEASURED_PACKED_DECODE_TRAFFIC_BYTES = 325370100   # decode_step_kernel on the packed state (decode_1p3b)
 
 
@@ -64,6 +64,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-leg", action="store_true")
     ap.add_argument("--no-graph-leg", action="store_true", help="skip the graph-replay part of the decode leg")
+    ap.add_argument("--no-projection-leg", action="store_true", help="skip the timing of the projection GEMMs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain device copies of 1 GiB (not timed): the known traffic that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -223,6 +224,11 @@ def main() -> int:
                                     "tokens_per_s": round(tokens_per_step / (g_ms * 1e-3), 1)}
         del graphs
 
+    # ---- the projections around the mixers (not part of the step or of `value`): the fused q / k / v
+    # projection of this layer shape and the output projection, as plain GEMMs on the matrix cores
+    if not args.no_projection_leg:
+        out["projection"] = projection_leg(torch, based, dev, B * N, 1024 if dv == 64 else 2048, H * (2 * dp + dv), H * dv)
+
     # ---- decode leg: 1.3B-shaped, batch 128, fused state update/readout + ring attention ---------
     if not args.no_decode_leg:
         out["decode"] = decode_leg(torch, based, synth, dev, args.decode_steps, not args.no_graph_leg)
@@ -325,6 +331,36 @@ def decode_leg(torch, based, synth, dev, steps: int, with_graph: bool = True):
                          "traffic": MEASURED_PACKED_DECODE_TRAFFIC_BYTES},
         },
     }
+
+
+def projection_leg(torch, based, dev, M: int, d_model: int, n_qkv: int, n_o: int):
+    """based_linear on the layer's fused q/k/v projection (d_model -> H (2 d' + d_v)) and its output projection
+    (H d_v -> d_model): time per call and fraction of the bf16 MFMA peak (2 M K N flop)."""
+    bf = torch.bfloat16
+    res = {}
+    for name, K, N in (("qkv", d_model, n_qkv), ("out", n_o, d_model)):
+        if K % 64 or N % 128:
+            continue
+        g = torch.Generator(device="cpu").manual_seed(11)
+        xs = [(torch.randn((M, K), generator=g)).to(bf).to(dev) for _ in range(3)]
+        W = (torch.randn((N, K), generator=g) / math.sqrt(K)).to(bf).to(dev)
+        y = torch.empty((M, N), dtype=bf, device=dev)
+        for i in range(3):
+            based.linear(xs[i % 3], W, y=y)
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        R = 30
+        for i in range(R):
+            based.linear(xs[i % 3], W, y=y)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / R
+        tf = 2.0 * M * K * N / (ms * 1e-3) / 1e12
+        res[name] = {"M": M, "K": K, "N": N, "ms": round(ms, 4),
+                     "roofline": {"kernel": "based_linear (lin::linear_kernel)", "bound": "mfma", "achieved": round(tf, 1),
+                                  "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4)}}
+    return res
 
 
 def graph_replay_leg(torch, based, synth, dev, steps: int):
