@@ -391,6 +391,40 @@ def test_full_size_decode_sampled_units(based):
     check_close(down(z).reshape(U, D)[units], zw, TOL[dtype], "full-size decode final z")
 
 
+def test_decode_state_beyond_the_cache(based):
+    """A state well beyond the last-level cache (704 units x 545 KB = 384 MB at d' = 32, d_v = 128): the
+    launches then walk the units in alternating directions and the fused launch streams the ring past the
+    cache.  Four steps from an empty state (both directions at least once in each entry point), sampled
+    units against the oracle, for the state update alone and for the fused step."""
+    wl = make_wl("decode_1p3b", d_feat=32, d_v=128)
+    B, H = 44, 16
+    U = B * H
+    dp, dv, dh, w, dtype = wl.d_feat, wl.d_v, wl.d_h, wl.w, wl.dtype
+    T = 4
+    dec = synth.decode_inputs(wl, T, units=U)
+    scale = 1.0 / math.sqrt(dh)
+    units = np.array([0, 1, 2, 351, 352, U - 2, U - 1])
+    tr = lambda a: np.ascontiguousarray(a.transpose(1, 0, 2)[units])
+    steps = np.arange(T)
+    want_lin = oracle.linattn_rows(tr(dec["q"]), tr(dec["k"]), tr(dec["v"]), steps)
+    want_swa = oracle.swa_rows(tr(dec["swa_q"]), tr(dec["swa_k"]), tr(dec["swa_v"]), w, scale, steps)
+    state_a = based.alloc_state(B, H, dp, dv)
+    state_b = based.alloc_state(B, H, dp, dv)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    toks = [[up(dec[n][t], dtype, (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")] for t in range(T)]
+    # consecutive launches of one entry point, so that each of them runs in both directions
+    for t in range(T):
+        y = based.decode_step(toks[t][0], toks[t][1], toks[t][2], state_a)
+        torch.cuda.synchronize()
+        check_close(down(y).reshape(U, dv)[units], want_lin[:, t], TOL[dtype], f"large-state update step {t}")
+    for t in range(T):
+        f1, f2 = based.decode_fused(*toks[t][:3], state_b, *toks[t][3:], ring, t + 1, w, scale)
+        torch.cuda.synchronize()
+        check_close(down(f1).reshape(U, dv)[units], want_lin[:, t], TOL[dtype], f"large-state fused lin step {t}")
+        check_close(down(f2).reshape(U, dh)[units], want_swa[:, t], TOL[dtype], f"large-state fused swa step {t}")
+    assert torch.equal(state_a, state_b)
+
+
 @pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100), (128, 16, 1300),
                                     (64, 32, 1100)])
 def test_swa_prefill_segmented(based, dh, w, N):
