@@ -5,8 +5,11 @@
  *
  * General contract (all entry points)
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
- *     allocates, frees or keeps device memory.  Its only process-wide state is a counter of
- *     segmented prefill calls, used to tag the ready flags it keeps in the caller's workspace.
+ *     allocates, frees or keeps device memory.  Its only process-wide state is two launch
+ *     counters: one of segmented prefill calls, used to tag the ready flags it keeps in the
+ *     caller's workspace, and one of decode launches on states far larger than the last-level
+ *     cache, which alternates the order in which such a launch walks the units (results do
+ *     not depend on either).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on it and never synchronise; buffers must stay alive until the work
  *     has run.
