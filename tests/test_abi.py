@@ -102,3 +102,21 @@ def test_bad_arguments_are_rejected_before_launch(based):
     # state copies
     assert lib.based_state_export(null, p, p, 1, 1, 16, 64, st) == based.ERR_INVALID_ARG
     assert lib.based_state_import(p, p, p, 1, 1, 16, 100, st) == based.ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: --gpus 2 exits with a message and a non-zero status before
+    touching any device; the credited-work helper matches the hand count for both state layouts."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(root, "bench.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    # 4 D d_v + 4 D + (C + 1)(d' + d_v + 1) with D = 273 (unpacked) and 153 (one row per unordered pair)
+    assert mod.lin_prefill_flops_per_token_head(16, 64, packed=False) == 4 * 273 * 64 + 4 * 273 + 65 * 81
+    assert mod.lin_prefill_flops_per_token_head(16, 64, packed=True) == 4 * 153 * 64 + 4 * 153 + 65 * 81 == 45045
