@@ -143,6 +143,18 @@ def test_prefill_initial_state_symmetric_part(based, dtype, dp, dv):
     check_close(down(zf).reshape(zw.shape), zw, TOL[dtype], "final z")
 
 
+@pytest.mark.parametrize("dp", [16, 32])
+@pytest.mark.parametrize("scale", [2.0, 4.0])
+def test_prefill_large_magnitudes(based, dp, scale):
+    """Inputs 4 and 8 times larger than the workloads' (q.k of the order of +-100, kernel values up to 1e4):
+    the bf16 matrix-core kernels stay finite and inside the same tolerance."""
+    wl = make_wl("prefill_360m", d_feat=dp, qk_scale=scale, v_scale=scale)
+    B, H, N = 1, 2, 700
+    q, k, v = lin_case(wl, B, H, N)
+    y = run_prefill(based, wl, B, H, N, q, k, v)
+    check_close(rows(y), rows(oracle.linattn_quadratic(q, k, v)), TOL["bf16"], f"prefill at input scale {scale}, d'={dp}")
+
+
 def test_prefill_deterministic(based):
     wl = synth.WORKLOADS["prefill_360m"]
     B, H, N = 2, 4, 512
