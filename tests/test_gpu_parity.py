@@ -876,3 +876,66 @@ def test_linear_projection_full_size_sampled(based):
     torch.cuda.synchronize()
     sample = np.array([0, 1, 127, 128, 129, 4095, 8192, 12345, M - 2, M - 1])
     check_close(down(y)[sample], oracle.linear(x[sample], W), TOL["bf16"], "qkv projection, sampled rows")
+
+
+# ------------------------------------------------------------------------------------------------
+# seeded random shapes (segment boundaries, ragged chunks, splits at arbitrary tokens)
+# ------------------------------------------------------------------------------------------------
+def _random_prefill_cases():
+    g = np.random.Generator(np.random.Philox(key=2402))
+    cases = []
+    for _ in range(14):
+        dp = int(g.choice([16, 32])); dv = int(g.choice([64, 128]))
+        B = int(g.integers(1, 3)); H = int(g.integers(1, 4))
+        N = int(g.integers(2, 4200)); N1 = int(g.integers(1, N))
+        cases.append((dp, dv, B, H, N, N1))
+    return cases
+
+
+@pytest.mark.parametrize("dp,dv,B,H,N,N1", _random_prefill_cases())
+def test_prefill_random_shapes(based, dp, dv, B, H, N, N1):
+    """bf16 prefill of N tokens as one call and as two calls split at token N1 (state handed over), both
+    against the oracle; final states agree with the oracle's."""
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv)
+    q, k, v = lin_case(wl, B, H, N)
+    want = oracle.linattn_quadratic(q, k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    y = run_prefill(based, wl, B, H, N, q, k, v, state=state)
+    check_close(rows(y), rows(want), TOL["bf16"], f"random shape one call d'={dp} dv={dv} U={B * H} N={N}")
+    state2 = based.alloc_state(B, H, dp, dv)
+    y1 = run_prefill(based, wl, B, H, N1, q[:, :N1], k[:, :N1], v[:, :N1], state=state2)
+    y2 = run_prefill(based, wl, B, H, N - N1, q[:, N1:], k[:, N1:], v[:, N1:], state=state2, has_init=True)
+    check_close(rows(y1), rows(want[:, :N1]), TOL["bf16"], f"random shape part 1 (N1={N1})")
+    check_close(rows(y2), rows(want[:, N1:]), TOL["bf16"], f"random shape part 2 (N1={N1})")
+    Sw, zw = oracle.linattn_state(k, v)
+    for st, what in ((state, "one call"), (state2, "two calls")):
+        S, z = based.state_export(st, B, H, dp, dv)
+        check_close(down(S).reshape(Sw.shape), Sw, TOL["bf16"], f"random shape final S, {what}")
+        check_close(down(z).reshape(zw.shape), zw, TOL["bf16"], f"random shape final z, {what}")
+
+
+def _random_swa_cases():
+    g = np.random.Generator(np.random.Philox(key=18668))
+    cases = []
+    for _ in range(12):
+        cases.append((str(g.choice(["bf16", "bf16", "f32"])), int(g.choice([64, 128])), int(g.choice([16, 32, 64, 128])),
+                      int(g.integers(1, 3)), int(g.integers(1, 4)), int(g.integers(1, 3000))))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,dh,w,B,H,N", _random_swa_cases())
+def test_swa_random_shapes(based, dtype, dh, w, B, H, N):
+    """Window attention prefill at random sizes, then one decode step from the ring it leaves."""
+    wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
+    U = B * H
+    q, k, v = synth.swa_inputs(wl, units=U, N=N + 1)
+    scale = 1.0 / math.sqrt(dh)
+    want = oracle.swa(q, k, v, w, scale)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    y = based.swa_prefill(up(q[:, :N], dtype, (B, H, N, dh)), up(k[:, :N], dtype, (B, H, N, dh)),
+                          up(v[:, :N], dtype, (B, H, N, dh)), w, scale, ring=ring)
+    torch.cuda.synchronize()
+    check_close(down(y).reshape(U * N, dh), rows(want[:, :N]), TOL[dtype], f"random swa {dtype} dh={dh} w={w} N={N}")
+    yd = based.swa_decode(up(q[:, N], dtype, (B, H, dh)), up(k[:, N], dtype, (B, H, dh)), up(v[:, N], dtype, (B, H, dh)),
+                          ring, N + 1, w, scale)
+    check_close(down(yd).reshape(U, dh), want[:, N], TOL[dtype], f"random swa decode after N={N}")
