@@ -703,32 +703,54 @@ def test_decode_fused_packed_equals_separate(based):
 def test_decode_fused_ragged_positions(based, packed):
     """Sequences that start at different steps: every sequence, on its own token stream, matches the
     oracle; a sequence whose position is < 1 is left untouched and gets zero rows."""
-    wl = make_wl("decode_1p3b", dtype="bf16")
-    B, H, T = 4, 2, 70                      # 70 > w: the ring wraps for the early starters
-    dp, dv, dh, w = wl.d_feat, wl.d_v, wl.d_h, wl.w
+    # 70 > w: the ring wraps for the early starters
+    _ragged_decode_case(based, "bf16", 16, 128, 128, 64, packed, B=4, H=2, T=70, start=np.array([0, 3, 40, 69]))
+
+
+def _ragged_decode_case(based, dtype, dp, dv, dh, w, packed, B, H, T, start):
+    wl = make_wl("decode_1p3b", dtype=dtype, d_feat=dp, d_v=dv, d_h=dh, w=w)
     U = B * H
-    start = np.array([0, 3, 40, 69])        # first step at which sequence b is active
     dec = synth.decode_inputs(wl, T, units=U)
     scale = 1.0 / math.sqrt(dh)
     state = (based.alloc_packed_state if packed else based.alloc_state)(B, H, dp, dv)
-    ring = based.alloc_swa_ring(B, H, w, dh, torch.bfloat16)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
     ylin = np.zeros((T, U, dv)); yswa = np.zeros((T, U, dh))
     for t in range(T):
         pos = torch.tensor(np.maximum(t - start + 1, 0), dtype=torch.int32, device="cuda")
-        args = [up(dec[n][t], "bf16", (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
+        args = [up(dec[n][t], dtype, (B, H, -1)) for n in ("q", "k", "v", "swa_q", "swa_k", "swa_v")]
         f1, f2 = based.decode_fused(args[0], args[1], args[2], state, args[3], args[4], args[5], ring,
                                     pos, w, scale, packed=packed)
         torch.cuda.synchronize()
         ylin[t] = down(f1).reshape(U, dv); yswa[t] = down(f2).reshape(U, dh)
     for b in range(B):
         units = np.arange(b * H, (b + 1) * H)
-        s0 = start[b]
+        s0 = int(start[b])
         assert not ylin[:s0, units].any() and not yswa[:s0, units].any()
+        if s0 >= T:
+            continue
         seq = lambda name: dec[name][s0:, units].transpose(1, 0, 2)
         want_lin = oracle.linattn_quadratic(seq("q"), seq("k"), seq("v"))
         want_swa = oracle.swa(seq("swa_q"), seq("swa_k"), seq("swa_v"), w, scale)
-        check_close(rows(ylin[s0:, units].transpose(1, 0, 2)), rows(want_lin), TOL["bf16"], f"ragged lin seq {b}")
-        check_close(rows(yswa[s0:, units].transpose(1, 0, 2)), rows(want_swa), TOL["bf16"], f"ragged swa seq {b}")
+        check_close(rows(ylin[s0:, units].transpose(1, 0, 2)), rows(want_lin), TOL[dtype], f"ragged lin seq {b}")
+        check_close(rows(yswa[s0:, units].transpose(1, 0, 2)), rows(want_swa), TOL[dtype], f"ragged swa seq {b}")
+
+
+def _random_decode_cases():
+    g = np.random.Generator(np.random.Philox(key=31))
+    cases = []
+    for _ in range(8):
+        B = int(g.integers(1, 5)); T = int(g.integers(3, 40))
+        cases.append((str(g.choice(["bf16", "f32"])), int(g.choice([16, 32])), int(g.choice([64, 128])),
+                      int(g.choice([64, 128])), int(g.choice([16, 32, 64, 128])), bool(g.integers(0, 2)), B,
+                      int(g.integers(1, 4)), T, tuple(int(x) for x in g.integers(0, T + 1, size=B))))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,dp,dv,dh,w,packed,B,H,T,start", _random_decode_cases())
+def test_decode_fused_random_cases(based, dtype, dp, dv, dh, w, packed, B, H, T, start):
+    """Fused decode from empty state and ring at random sizes, dtypes, windows and state layouts, with
+    sequences joining at random steps (a start of T: the sequence never takes part)."""
+    _ragged_decode_case(based, dtype, dp, dv, dh, w, packed, B, H, T, np.array(start))
 
 
 def test_decode_step_graph_replay_with_device_positions(based):
