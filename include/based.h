@@ -6,14 +6,17 @@
  * General contract (all entry points)
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
  *     allocates, frees or keeps device memory.  Its only process-wide state is two launch
- *     counters: one of segmented prefill calls, used to tag the ready flags it keeps in the
+ *     counters (one of segmented prefill calls, used to tag the ready flags it keeps in the
  *     caller's workspace, and one of decode launches on states far larger than the last-level
- *     cache, which alternates the order in which such a launch walks the units (results do
- *     not depend on either).
+ *     cache, which alternates the order in which such a launch walks the units; results do
+ *     not depend on either) and the poll limit of based_debug_set_poll_limit.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on it and never synchronise; buffers must stay alive until the work
  *     has run.
- *   - Return value: BASED_OK or an error code; on any error nothing has been launched.
+ *   - Return value: BASED_OK or an error code.  BASED_ERR_INVALID_ARG and BASED_ERR_UNSUPPORTED are
+ *     decided on the host before anything is launched.  BASED_ERR_LAUNCH means the HIP runtime
+ *     refused a launch; a call that consists of several launches (based_prefill can be up to
+ *     three) may then have enqueued the earlier ones, and its outputs are unspecified.
  *     Nothing aborts or throws.
  *   - Tensors are contiguous, last index fastest, base pointers 16-byte aligned.
  *     A "unit" is one (batch, head) pair; units are independent, u = b * H + h.
@@ -43,7 +46,8 @@ enum {
     BASED_OK = 0,
     BASED_ERR_INVALID_ARG = 1, /* null / misaligned pointer, non-positive size, bad pos */
     BASED_ERR_UNSUPPORTED = 2, /* size or dtype outside the supported set               */
-    BASED_ERR_LAUNCH = 3       /* the HIP runtime refused the launch                    */
+    BASED_ERR_LAUNCH = 3       /* the HIP runtime refused the launch, or (based_prefill_status)
+                                  a launch gave up a bounded wait and its outputs are invalid */
 };
 
 enum { BASED_F32 = 0, BASED_BF16 = 1 };
@@ -99,19 +103,43 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
  *          the two rows and writes both rows equal.  For a state produced by this library, or
  *          imported from the canonical arrays of such a state, that changes nothing.
  *   workspace  scratch of at least based_prefill_workspace_bytes(...) bytes, 256-byte aligned;
- *          may be NULL when that size is 0 (it never is for bf16 at d' = 32).  Contents on
- *          return are unspecified and need no initialisation.  For few units and long sequences
- *          the sequence is cut into segments that run side by side; state increments of the
- *          segments travel through the workspace.  At d' = 16 (bf16) that is one launch, in
- *          which workgroups wait for each other's increments with a bounded number of polls
- *          (about a second), after which they proceed: a launch always terminates.
+ *          may be NULL when that size is 0 (it never is for bf16).  It must be zero-filled ONCE
+ *          after it is allocated; after that the library maintains it, and calls may reuse it
+ *          without clearing.  For few units and long sequences the sequence is cut into segments
+ *          that run side by side; state increments of the segments travel through the workspace.
+ *          At d' = 16 (bf16) that is one launch, in which a workgroup waits for the increments of
+ *          the segments before its own with a bounded number of polls (about a quarter of a
+ *          second per increment).  A launch therefore always terminates; a workgroup that gives
+ *          up sets a sticky status word in the workspace and carries on with incomplete data:
+ *          y and the final state of that call are then INVALID although based_prefill itself
+ *          returned BASED_OK (it returns when the work is enqueued).  based_prefill_status
+ *          reports it.  The wait cannot time out as long as the device starts the workgroups of
+ *          a launch in grid order (the workgroups waited for come first in the grid and wait for
+ *          nothing), which is how the hardware dispatcher works but is not a documented promise.
  *
  * Calls sharing a workspace or a state buffer must be ordered on one stream.
+ *
+ * based_prefill_status -- did a based_prefill / based_prefill_packed call that used this workspace
+ * give up a bounded wait?  Same size arguments as the call it asks about.  It waits for `stream`
+ * (hipStreamSynchronize) and reads the status word back, so it is a host-synchronous call and
+ * must not be made while the stream is being captured.  BASED_OK: no launch since the last query
+ * gave up.  BASED_ERR_LAUNCH: at least one did (outputs of those calls are invalid); the query
+ * also clears the status word and the ready flags, after which the workspace can be used again.
+ * Without a query, eager calls after a failed one are still correct (every call tags its flags
+ * with a new epoch); a replayed graph repeats its epoch and needs the query's clean-up first.
+ * Configurations whose prefill has no such waits (fp32, d' = 32) always give BASED_OK.
+ *
+ * based_debug_set_poll_limit -- testing hook: the bound on the polls of one ready flag for later
+ * calls in this process (negative: back to the default).  With 0 a waiting workgroup gives up at
+ * once, which lets a test drive the error path while every workgroup still exits normally.
  */
 size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype);
 int based_prefill(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
                   void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
                   void *stream);
+int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                         void *stream);
+void based_debug_set_poll_limit(int polls);
 
 /*
  * based_decode_step -- one token of the recurrent view (Eq. 3), state update fused with

@@ -22,7 +22,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH = 0, 1, 2, 3
 EXPORTS = [
     "based_strerror", "based_version", "based_feature_dim", "based_state_bytes",
     "based_state_stride_floats", "based_state_export", "based_state_import",
-    "based_prefill_workspace_bytes", "based_prefill", "based_decode_step", "based_swa_ring_bytes",
+    "based_prefill_workspace_bytes", "based_prefill", "based_prefill_status", "based_debug_set_poll_limit",
+    "based_decode_step", "based_swa_ring_bytes",
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
@@ -60,6 +61,10 @@ def _load() -> ctypes.CDLL:
     lib.based_prefill_workspace_bytes.argtypes = [i, i, i, i, i, i]
     lib.based_prefill.restype = i
     lib.based_prefill.argtypes = [vp, vp, vp, vp, vp, i, vp, i, i, i, i, i, i, vp]
+    lib.based_prefill_status.restype = i
+    lib.based_prefill_status.argtypes = [vp, i, i, i, i, i, i, vp]
+    lib.based_debug_set_poll_limit.restype = None
+    lib.based_debug_set_poll_limit.argtypes = [i]
     lib.based_decode_step.restype = i
     lib.based_decode_step.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     lib.based_swa_ring_bytes.restype = sz
@@ -179,10 +184,23 @@ def prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype_code) -> int:
 
 
 def alloc_prefill_workspace(B, H, N, d_feat, d_v, dtype_code, device="cuda"):
+    """Workspace of the size the library asks for, zero-filled once as its contract requires."""
     n = prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype_code)
     if n == 0:
         return None
-    return torch.empty((n + 3) // 4, dtype=torch.float32, device=device)
+    return torch.zeros((n + 3) // 4, dtype=torch.float32, device=device)
+
+
+def prefill_status(workspace, B, H, N, d_feat, d_v, dtype_code) -> int:
+    """based_prefill_status: OK, or ERR_LAUNCH if a call on this workspace gave up a bounded wait
+    (host-synchronous; clears the condition)."""
+    _dev(workspace)
+    return int(lib.based_prefill_status(_ptr(workspace), B, H, N, d_feat, d_v, dtype_code, _stream()))
+
+
+def debug_set_poll_limit(polls: int) -> None:
+    """based_debug_set_poll_limit (testing hook)."""
+    lib.based_debug_set_poll_limit(int(polls))
 
 
 def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=False):

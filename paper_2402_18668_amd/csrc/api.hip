@@ -32,7 +32,7 @@ const char *based_strerror(int status)
     case BASED_OK: return "ok";
     case BASED_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, non-positive size, bad pos)";
     case BASED_ERR_UNSUPPORTED: return "unsupported size or dtype";
-    case BASED_ERR_LAUNCH: return "HIP launch failed";
+    case BASED_ERR_LAUNCH: return "HIP launch failed, or a launch gave up waiting for one of its own workgroups";
     default: return "unknown status";
     }
 }
@@ -108,6 +108,29 @@ int based_prefill(const void *q, const void *k, const void *v, void *y, void *st
     return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, workspace, U,
                                         N, d_feat, d_v, dtype, (hipStream_t)stream));
 }
+
+int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    // only the single-launch segmented prefill (bf16, d' = 16) has workgroups that wait for each other
+    if (!prefill_mfma_supported(d_feat, d_v, dtype)) return BASED_OK;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return BASED_ERR_INVALID_ARG;
+    size_t flags_off = 0, status_off = 0;
+    prefill_mfma_status_region(B * H, N, d_feat, d_v, &flags_off, &status_off);
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BASED_ERR_LAUNCH;
+    unsigned word = 0;
+    char *base = static_cast<char *>(workspace);
+    if (hipMemcpy(&word, base + status_off, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
+        return BASED_ERR_LAUNCH;
+    if (word == 0) return BASED_OK;
+    // a workgroup gave up: report it once, and clear the flags (a late writer may have left one raised)
+    // and the status word so that the workspace can be used again
+    if (hipMemset(base + flags_off, 0, status_off + 256 - flags_off) != hipSuccess) return BASED_ERR_LAUNCH;
+    return BASED_ERR_LAUNCH;
+}
+
+void based_debug_set_poll_limit(int polls) { prefill_mfma_set_poll_limit(polls); }
 
 int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
                          void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)

@@ -77,6 +77,11 @@ size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv);
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
                                int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                hipStream_t s);
+// byte offsets, inside a workspace of prefill_mfma_workspace_bytes, of the ready flags and of the
+// sticky status word that a workgroup sets when it gives up waiting for a flag
+void prefill_mfma_status_region(int U, int N, int dp, int dv, size_t *flags_offset, size_t *status_offset);
+// bound on the polls of one flag for later launches (negative: the default); a testing hook
+void prefill_mfma_set_poll_limit(int polls);
 bool prefill_mfma32_supported(int dp, int dv, int dtype);
 size_t prefill_mfma32_workspace_bytes(int U, int N, int dp, int dv);
 hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, void *y, float *state,

@@ -215,9 +215,13 @@ __device__ __forceinline__ void load_entry_coherent(const float *p0, const float
         : "memory");
 }
 
-// Upper bound on the polls of a segment-ready flag (each poll sleeps ~0.25 us): a workgroup never
-// waits forever, whatever happens to the workgroup it waits for.
+// Default upper bound on the polls of a segment-ready flag (each poll sleeps ~0.25 us): a workgroup
+// never waits forever, whatever happens to the workgroup it waits for.  A workgroup that gives up
+// stores the call's epoch into the workspace's status word (a plain vector store) and carries on, so
+// that every workgroup of the launch exits normally; its outputs are then wrong, and
+// based_prefill_status reports the launch as failed.
 constexpr int kMaxFlagPolls = 1 << 20;
+std::atomic<int> g_flag_poll_limit{kMaxFlagPolls};
 
 constexpr int kMaxSegments = 16;
 // first token of each segment (multiples of the chunk length), and the end of the last one
@@ -240,8 +244,8 @@ template <int MODE, bool FUSED>
 __device__ __forceinline__ void prefill_body(
     Lds &lds, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
     const uint16_t *__restrict__ v, uint16_t *__restrict__ y, float *__restrict__ state, int has_init,
-    float *__restrict__ ws, unsigned *__restrict__ flags, unsigned epoch, int N, int dv,
-    const SegTable &segs, int G, int seg, int slice, int u)
+    float *__restrict__ ws, unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls,
+    unsigned epoch, int N, int dv, const SegTable &segs, int G, int seg, int slice, int u)
 {
     // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
     const bool packed_state = (has_init & 2) != 0;
@@ -297,14 +301,18 @@ __device__ __forceinline__ void prefill_body(
         if (FUSED) {
             // wait for the increments of this call (entry 0 comes from an earlier launch)
             if (tid == 0) {
+                bool gave_up = false;
                 for (int p = 1; p <= seg; ++p) {
                     unsigned *f = flags_unit + p * G + seg;
                     int polls = 0;
-                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch &&
-                           ++polls < kMaxFlagPolls)
+                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch) {
+                        if (polls++ >= max_polls) { gave_up = true; break; }
                         __builtin_amdgcn_s_sleep(8);
+                    }
                     __hip_atomic_store(f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                 }
+                // sticky: stays set until based_prefill_status has reported it
+                if (gave_up) __hip_atomic_store(status, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
             __syncthreads();
             for (int p = p0; p <= seg; ++p) {
@@ -844,8 +852,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
     const int gseg = MODE == 1 ? G - 1 : (MODE == 2 ? 1 : G);   // segments this launch covers
     int bid = blockIdx.x;
     const int seg = bid % gseg; bid /= gseg;
-    prefill_body<MODE, false>(lds, q, k, v, y, state, has_init, ws, nullptr, 0u, N, dv, segs, G, seg,
-                              bid % slices, bid / slices);
+    prefill_body<MODE, false>(lds, q, k, v, y, state, has_init, ws, nullptr, nullptr, 0, 0u, N, dv, segs, G,
+                              seg, bid % slices, bid / slices);
 }
 
 // Increments and main pass in one launch.  Grid: first the (G - 1) increments of every unit slice,
@@ -854,7 +862,8 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_kernel(
 __global__ __launch_bounds__(NT, 2) void prefill_mfma_fused_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws,
-    unsigned *__restrict__ flags, unsigned epoch, int N, int dv, SegTable segs, int G, int groups)
+    unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls, unsigned epoch, int N, int dv,
+    SegTable segs, int G, int groups)
 {
     __shared__ __align__(16) Lds lds;
     const int slices = dv / DVS;
@@ -862,13 +871,13 @@ __global__ __launch_bounds__(NT, 2) void prefill_mfma_fused_kernel(
     int bid = blockIdx.x;
     if (bid < n_inc) {
         const int seg = bid % (G - 1); bid /= (G - 1);
-        prefill_body<1, true>(lds, q, k, v, y, state, has_init, ws, flags, epoch, N, dv, segs, G, seg,
-                              bid % slices, bid / slices);
+        prefill_body<1, true>(lds, q, k, v, y, state, has_init, ws, flags, status, max_polls, epoch, N, dv,
+                              segs, G, seg, bid % slices, bid / slices);
     } else {
         bid -= n_inc;
         const int seg = bid / groups; bid %= groups;
-        prefill_body<0, true>(lds, q, k, v, y, state, has_init, ws, flags, epoch, N, dv, segs, G, seg,
-                              bid % slices, bid / slices);
+        prefill_body<0, true>(lds, q, k, v, y, state, has_init, ws, flags, status, max_polls, epoch, N, dv,
+                              segs, G, seg, bid % slices, bid / slices);
     }
 }
 
@@ -924,19 +933,33 @@ bool prefill_mfma_supported(int dp, int dv, int dtype)
     return dtype == BASED_BF16 && dp == DP && (dv == 64 || dv == 128);
 }
 
-// Workspace: G entries per unit slice, then G x G ready-flag words per unit slice (256-byte aligned).
+// Workspace: G entries per unit slice, then G x G ready-flag words per unit slice (256-byte aligned),
+// then 256 bytes whose first word is the sticky status of the bounded waits.
 static size_t ws_entry_bytes(int U, int N, int dv)
 {
     return (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
+}
+static size_t ws_flag_bytes(int U, int N, int dv)
+{
+    const size_t Gmax = (size_t)pick_segments(U, N, dv);
+    const size_t flags = (size_t)U * (dv / DVS) * Gmax * Gmax * sizeof(unsigned);
+    return (flags + 255) / 256 * 256;
 }
 
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv)
 {
     (void)dp;
-    const size_t Gmax = (size_t)pick_segments(U, N, dv);
-    const size_t flags = (size_t)U * (dv / DVS) * Gmax * Gmax * sizeof(unsigned);
-    return ws_entry_bytes(U, N, dv) + (flags + 255) / 256 * 256;
+    return ws_entry_bytes(U, N, dv) + ws_flag_bytes(U, N, dv) + 256;
 }
+
+void prefill_mfma_status_region(int U, int N, int dp, int dv, size_t *flags_offset, size_t *status_offset)
+{
+    (void)dp;
+    *flags_offset = ws_entry_bytes(U, N, dv);
+    *status_offset = *flags_offset + ws_flag_bytes(U, N, dv);
+}
+
+void prefill_mfma_set_poll_limit(int polls) { g_flag_poll_limit.store(polls < 0 ? kMaxFlagPolls : polls); }
 
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
                                int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
@@ -961,10 +984,11 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
         static std::atomic<unsigned> calls{0};
         const unsigned epoch = 0x5EED0000u + calls.fetch_add(1u) + 1u;
         unsigned *flags = reinterpret_cast<unsigned *>((char *)workspace + ws_entry_bytes(U, N, dv));
+        unsigned *status = reinterpret_cast<unsigned *>((char *)flags + ws_flag_bytes(U, N, dv));
         const int groups = U * slices;
         hipLaunchKernelGGL(prefill_mfma_fused_kernel, dim3((unsigned)(groups * (2 * G - 1))), dim3(NT), 0, s,
-                           q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, flags, epoch, N,
-                           dv, segs, G, groups);
+                           q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, flags, status,
+                           g_flag_poll_limit.load(), epoch, N, dv, segs, G, groups);
         return hipGetLastError();
     }
     hipLaunchKernelGGL((prefill_mfma_kernel<0>), dim3((unsigned)(U * slices * G)), dim3(NT), 0, s, q16, k16,

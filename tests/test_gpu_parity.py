@@ -231,6 +231,25 @@ def test_swa_prefill(based, dtype, dh, w, B, H, N):
         assert np.array_equal(r[:, 1, j % w], v[:, j].astype(np.float64))
 
 
+def test_swa_tiny_fp32_on_the_linear_attention_values(based):
+    """The tiny fp32 case as the workload list states it: one unit, 256 tokens, window 64, 64-dim q and k
+    of their own and the SAME v as the linear-attention leg; every element, and the ring it leaves."""
+    wl = synth.WORKLOADS["tiny"]
+    B, H, N, dh, w = wl.B, wl.H, wl.N, wl.d_h, wl.w
+    q, k, v = synth.swa_inputs(wl)
+    assert np.array_equal(v, synth.linattn_inputs(wl)[2]) and q.shape == (1, 256, 64)
+    scale = 1.0 / math.sqrt(dh)
+    ring = based.alloc_swa_ring(B, H, w, dh, torch.float32)
+    y = based.swa_prefill(up(q, "f32", (B, H, N, dh)), up(k, "f32", (B, H, N, dh)), up(v, "f32", (B, H, N, dh)),
+                          w, scale, ring=ring)
+    torch.cuda.synchronize()
+    check_close(down(y).reshape(N, dh), rows(oracle.swa(q, k, v, w, scale)), TOL["f32"], "tiny window attention")
+    r = down(ring).reshape(1, 2, w, dh)
+    for j in range(N - w, N):
+        assert np.array_equal(r[:, 0, j % w], k[:, j].astype(np.float64))
+        assert np.array_equal(r[:, 1, j % w], v[:, j].astype(np.float64))
+
+
 @pytest.mark.parametrize("dtype,dh,w", [("f32", 64, 64), ("bf16", 128, 64), ("bf16", 64, 128), ("f32", 128, 128),
                                         ("bf16", 64, 64), ("bf16", 64, 16), ("bf16", 128, 16), ("f32", 64, 16),
                                         ("f32", 128, 16), ("bf16", 128, 32), ("f32", 64, 32)])
@@ -327,7 +346,10 @@ def test_full_size_prefill_sampled_rows(based, name):
     q, k, v = synth.linattn_inputs(wl)
     y = run_prefill(based, wl, B, H, N, q, k, v)
     units = np.array([0, 1, U // 2, U - 1])
-    sample = np.array([0, 1, 63, 64, 65, 511, 512, 1024, N - 2, N - 1])
+    # chunk boundaries, and every place where the launcher may cut the sequence into segments (multiples of
+    # the chunk length between a quarter and three quarters of the sequence, rows on both sides)
+    sample = np.array([0, 1, 63, 64, 65, 127, 128, 447, 448, 511, 512, 513, 575, 576, 577, 639, 640, 1023, 1024, 1025,
+                       1087, 1088, 1089, 1151, 1152, 1535, 1536, 1537, 1599, 1600, 1601, 1663, 1664, N - 2, N - 1])
     want = oracle.linattn_rows(q[units], k[units], v[units], sample)
     check_close(rows(y[units][:, sample]), rows(want), TOL[wl.dtype], f"{name} sampled rows")
     sq, sk, sv = synth.swa_inputs(wl)
@@ -401,6 +423,89 @@ def test_full_size_decode_sampled_units(based):
     D = Sw.shape[1]
     check_close(down(S).reshape(U, D, dv)[units], Sw, TOL[dtype], "full-size decode final S")
     check_close(down(z).reshape(U, D)[units], zw, TOL[dtype], "full-size decode final z")
+
+
+def test_decode_workload_as_stated(based):
+    """The batch-128 decode workload exactly as the workload list states it: state and ring from a seeded
+    512-token prefill of all 2048 units, then 1024 sequential fused steps on 1024 distinct seeded tokens.
+    Rows of Eq. 2 / Eq. 1 over the 1536-token history are independent, so sampled units at sampled steps
+    are compared with the oracle directly; the final state of those units as well.  Three chains run side
+    by side: (a) the state as based_prefill leaves it (bf16 matrix-core arithmetic: bf16 tolerance on the
+    state); (b) the same, but the sampled units start from the oracle's 512-token state rounded to fp32,
+    which isolates the 1024-step fp32 read-modify-write chain (fp32 tolerance on the final state);
+    (c) chain (b) on the packed state."""
+    from concurrent.futures import ThreadPoolExecutor
+    wl = synth.WORKLOADS["decode_1p3b"]
+    B, H, U = wl.B, wl.H, wl.units
+    dp, dv, dh, w, dtype = wl.d_feat, wl.d_v, wl.d_h, wl.w, wl.dtype
+    N0, T = wl.N, wl.decode_steps
+    assert (B, H, N0, T, dp, dv, dh, w) == (128, 16, 512, 1024, 16, 128, 128, 64)
+    D = 1 + dp + dp * dp
+    scale = 1.0 / math.sqrt(dh)
+    q, k, v = synth.linattn_inputs(wl)
+    sq, sk, sv = synth.swa_inputs(wl)
+    # synth.decode_inputs(wl, T), its six tensors drawn side by side (same seeds, same values)
+    names = ("q", "k", "v", "swa_q", "swa_k", "swa_v")
+    dims = (dp, dp, dv, dh, dh, dh)
+    scales = (wl.qk_scale, wl.qk_scale, wl.v_scale, wl.swa_qk_scale, wl.swa_qk_scale, wl.v_scale)
+    with ThreadPoolExecutor(6) as pool:
+        futs = [pool.submit(synth.tensor, wl, synth.T_DECODE + i, (T, U, dims[i]), scales[i]) for i in range(6)]
+        dec = {n: f.result() for n, f in zip(names, futs)}
+    dev = {n: up(dec[n], dtype, (T, B, H, -1)) for n in names}
+
+    state_a = based.alloc_state(B, H, dp, dv)
+    run_prefill(based, wl, B, H, N0, q, k, v, state=state_a)
+    ring_a = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    based.swa_prefill(up(sq, dtype, (B, H, N0, dh)), up(sk, dtype, (B, H, N0, dh)), up(sv, dtype, (B, H, N0, dh)),
+                      w, scale, ring=ring_a)
+    units = np.array([0, 1, 15, 16, 777, U // 2, U - 2, U - 1])
+    # chain (b): sampled units start from the oracle's state of the 512 prefill tokens
+    S0, z0 = oracle.linattn_state(k[units], v[units])
+    S, z = based.state_export(state_a, B, H, dp, dv)
+    S = S.reshape(U, D, dv).clone(); z = z.reshape(U, D).clone()
+    S[torch.from_numpy(units).cuda()] = up(S0, "f32")
+    z[torch.from_numpy(units).cuda()] = up(z0, "f32")
+    state_b = based.alloc_state(B, H, dp, dv)
+    based.state_import(state_b, S.reshape(B, H, D, dv), z.reshape(B, H, D), dp)
+    packed_c = based.alloc_packed_state(B, H, dp, dv)
+    based.state_pack(state_b, packed_c, B, H, dp, dv)
+    ring_b, ring_c = ring_a.clone(), ring_a.clone()
+    torch.cuda.synchronize()
+
+    steps = np.array([1, 2, 64, 65, 512, 1023, 1024])   # 1-based step numbers
+    keep = {int(t) - 1 for t in steps}
+    got = {c: {} for c in "abc"}
+    for t in range(T):
+        a = [dev[n][t] for n in names]
+        for c, st, rg, pk in (("a", state_a, ring_a, False), ("b", state_b, ring_b, False), ("c", packed_c, ring_c, True)):
+            f1, f2 = based.decode_fused(a[0], a[1], a[2], st, a[3], a[4], a[5], rg, N0 + t + 1, w, scale, packed=pk)
+            if t in keep:
+                got[c][t] = (down(f1).reshape(U, dv)[units], down(f2).reshape(U, dh)[units])
+    torch.cuda.synchronize()
+
+    cat = lambda x, y: np.concatenate([x[units], y.transpose(1, 0, 2)[units]], axis=1)
+    hist_rows = N0 + steps - 1
+    allk, allv = cat(k, dec["k"]), cat(v, dec["v"])
+    want_lin = oracle.linattn_rows(cat(q, dec["q"]), allk, allv, hist_rows)
+    want_swa = oracle.swa_rows(cat(sq, dec["swa_q"]), cat(sk, dec["swa_k"]), cat(sv, dec["swa_v"]), w, scale, hist_rows)
+    for c in "abc":
+        for i, step in enumerate(steps):
+            yl, ys = got[c][int(step) - 1]
+            check_close(yl, want_lin[:, i], TOL[dtype], f"decode workload, chain {c}, step {step}: linear attention")
+            check_close(ys, want_swa[:, i], TOL[dtype], f"decode workload, chain {c}, step {step}: window attention")
+    Sw, zw = oracle.linattn_state(allk, allv)
+    back = based.alloc_state(B, H, dp, dv)
+    based.state_unpack(packed_c, back, B, H, dp, dv)
+    for c, st, tol in (("a", state_a, TOL[dtype]), ("b", state_b, TOL["f32"]), ("c", back, TOL["f32"])):
+        Sg, zg = based.state_export(st, B, H, dp, dv)
+        check_close(down(Sg).reshape(U, D, dv)[units], Sw, tol, f"decode workload, chain {c}: S after 1024 steps")
+        check_close(down(zg).reshape(U, D)[units], zw, tol, f"decode workload, chain {c}: z after 1024 steps")
+    # the rings of the three chains saw the same tokens
+    assert torch.equal(ring_a, ring_b) and torch.equal(ring_a, ring_c)
+    r = down(ring_a).reshape(U, 2, w, dh)[units]
+    for j in range(N0 + T - w, N0 + T):
+        assert np.array_equal(r[:, 0, j % w], dec["swa_k"][j - N0, units].astype(np.float64))
+        assert np.array_equal(r[:, 1, j % w], dec["swa_v"][j - N0, units].astype(np.float64))
 
 
 def test_decode_state_beyond_the_cache(based):
@@ -525,6 +630,35 @@ def test_prefill_graph_replay(based):
         y2 = based.prefill(tq, tk, tv, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(y2, y_eager)
+
+
+def test_prefill_bounded_wait_reports_failure(based):
+    """The single-launch segmented prefill: a workgroup that gives up waiting for a segment's increment sets
+    the sticky status word and based_prefill_status reports the call as failed.  The condition is forced
+    from the host (poll limit 0: a waiting workgroup gives up at its first look), so every workgroup still
+    exits normally.  After the query the same workspace serves a correct call again, replays included."""
+    wl = synth.WORKLOADS["prefill_360m"]
+    B, H, N = 1, 2, 2048   # four segments
+    q, k, v = lin_case(wl, B, H, N)
+    tq, tk, tv = (up(a, "bf16", (B, H, N, a.shape[-1])) for a in (q, k, v))
+    ws = based.alloc_prefill_workspace(B, H, N, wl.d_feat, wl.d_v, based.BF16)
+    sizes = (B, H, N, wl.d_feat, wl.d_v, based.BF16)
+    want = oracle.linattn_quadratic(q, k, v)
+    y_ok = based.prefill(tq, tk, tv, workspace=ws)
+    assert based.prefill_status(ws, *sizes) == based.OK
+    check_close(rows(down(y_ok).reshape(B * H, N, wl.d_v)), rows(want), TOL["bf16"], "before the forced failure")
+    based.debug_set_poll_limit(0)
+    try:
+        based.prefill(tq, tk, tv, workspace=ws)
+        assert based.prefill_status(ws, *sizes) == based.ERR_LAUNCH
+        assert based.prefill_status(ws, *sizes) == based.OK   # reported once, then cleared
+    finally:
+        based.debug_set_poll_limit(-1)
+    y2 = based.prefill(tq, tk, tv, workspace=ws)
+    assert based.prefill_status(ws, *sizes) == based.OK
+    assert torch.equal(y2, y_ok)
+    # configurations without waiting workgroups always report OK
+    assert based.prefill_status(ws, 1, 2, 100, 32, 64, based.BF16) == based.OK
 
 
 @pytest.mark.parametrize("dp", [16, 32])
