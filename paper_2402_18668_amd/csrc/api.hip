@@ -73,40 +73,62 @@ int based_state_import(void *state, const float *S, const float *z, int B, int H
                                        (hipStream_t)stream));
 }
 
+// A prefill workspace is a 256-byte header followed by the scratch of the kernel family that serves
+// the call.  The header's first word is the sticky status of the bounded waits; it sits at offset 0
+// whatever the sizes, so a workspace can be reused for calls of any shape.
+constexpr size_t kWsHeader = 256;
+
+static size_t prefill_scratch_bytes(int U, int N, int d_feat, int d_v, int dtype)
+{
+    if (prefill_mfma32_supported(d_feat, d_v, dtype)) return prefill_mfma32_workspace_bytes(U, N, d_feat, d_v);
+    if (prefill_mfma_supported(d_feat, d_v, dtype)) return prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
+    return prefill_ref_workspace_bytes(U, N, d_feat, d_v);
+}
+
 size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype)
 {
     if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype) || !ok_counts(B, H, N)) return 0;
-    if (prefill_mfma32_supported(d_feat, d_v, dtype)) return prefill_mfma32_workspace_bytes(B * H, N, d_feat, d_v);
-    if (!prefill_mfma_supported(d_feat, d_v, dtype)) return prefill_ref_workspace_bytes(B * H, N, d_feat, d_v);
-    return prefill_mfma_workspace_bytes(B * H, N, d_feat, d_v);
+    const size_t scratch_bytes = prefill_scratch_bytes(B * H, N, d_feat, d_v, dtype);
+    return scratch_bytes ? kWsHeader + scratch_bytes : 0;
+}
+
+static int prefill_any(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                       int packed, void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                       void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    const bool m32 = prefill_mfma32_supported(d_feat, d_v, dtype);
+    const bool m16 = prefill_mfma_supported(d_feat, d_v, dtype);
+    // only the matrix-core kernels carry the state packed
+    if (packed && !m32 && !m16) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
+    if (has_init && !state) return BASED_ERR_INVALID_ARG;
+    const int U = B * H;
+    const size_t need = prefill_scratch_bytes(U, N, d_feat, d_v, dtype);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
+    void *inner = workspace ? static_cast<char *>(workspace) + kWsHeader : nullptr;
+    float *st = static_cast<float *>(state);
+    hipStream_t s = (hipStream_t)stream;
+    if (m32)
+        return status_of(launch_prefill_mfma32(q, k, v, y, st, has_init ? 1 : 0, packed, inner, U, N, d_feat, d_v, s));
+    if (m16)
+        return status_of(launch_prefill_mfma(q, k, v, y, st, has_init ? 1 : 0, packed, inner,
+                                             static_cast<unsigned *>(workspace), U, N, d_feat, d_v, s));
+    return status_of(launch_prefill_ref(q, k, v, y, st, has_init ? 1 : 0, inner, U, N, d_feat, d_v, dtype, s));
 }
 
 int based_prefill(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
                   void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
 {
-    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
-    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
-    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
-    if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
-    if (has_init && !state) return BASED_ERR_INVALID_ARG;
-    const int U = B * H;
-    if (prefill_mfma32_supported(d_feat, d_v, dtype)) {
-        // d' = 32 always needs the workspace (it carries the denominators between launches)
-        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return BASED_ERR_INVALID_ARG;
-        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, 0,
-                                               workspace, U, N, d_feat, d_v, (hipStream_t)stream));
-    }
-    if (prefill_mfma_supported(d_feat, d_v, dtype)) {
-        const size_t need = prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
-        if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)))
-            return BASED_ERR_INVALID_ARG;
-        return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, 0,
-                                             workspace, U, N, d_feat, d_v, (hipStream_t)stream));
-    }
-    const size_t need = prefill_ref_workspace_bytes(U, N, d_feat, d_v);
-    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
-    return status_of(launch_prefill_ref(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, workspace, U,
-                                        N, d_feat, d_v, dtype, (hipStream_t)stream));
+    return prefill_any(q, k, v, y, state, has_init, 0, workspace, B, H, N, d_feat, d_v, dtype, stream);
+}
+
+int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
+                         void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    return prefill_any(q, k, v, y, packed, has_init, 1, workspace, B, H, N, d_feat, d_v, dtype, stream);
 }
 
 int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
@@ -115,44 +137,23 @@ int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d
     if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
     // only the single-launch segmented prefill (bf16, d' = 16) has workgroups that wait for each other
     if (!prefill_mfma_supported(d_feat, d_v, dtype)) return BASED_OK;
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return BASED_ERR_INVALID_ARG;
-    size_t flags_off = 0, status_off = 0;
-    prefill_mfma_status_region(B * H, N, d_feat, d_v, &flags_off, &status_off);
+    if (!workspace) return BASED_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BASED_ERR_INVALID_ARG;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BASED_ERR_LAUNCH;
     unsigned word = 0;
     char *base = static_cast<char *>(workspace);
-    if (hipMemcpy(&word, base + status_off, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess)
-        return BASED_ERR_LAUNCH;
+    if (hipMemcpy(&word, base, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) return BASED_ERR_LAUNCH;
     if (word == 0) return BASED_OK;
-    // a workgroup gave up: report it once, and clear the flags (a late writer may have left one raised)
-    // and the status word so that the workspace can be used again
-    if (hipMemset(base + flags_off, 0, status_off + 256 - flags_off) != hipSuccess) return BASED_ERR_LAUNCH;
+    // a workgroup gave up: report it once; clear the status word, and the ready flags of this shape (a
+    // late writer may have left one raised), so that the workspace can be used again
+    size_t flags_off = 0, flags_bytes = 0;
+    prefill_mfma_flags_region(B * H, N, d_feat, d_v, &flags_off, &flags_bytes);
+    if (hipMemset(base, 0, kWsHeader) != hipSuccess) return BASED_ERR_LAUNCH;
+    if (flags_bytes && hipMemset(base + kWsHeader + flags_off, 0, flags_bytes) != hipSuccess) return BASED_ERR_LAUNCH;
     return BASED_ERR_LAUNCH;
 }
 
 void based_debug_set_poll_limit(int polls) { prefill_mfma_set_poll_limit(polls); }
-
-int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
-                         void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
-{
-    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
-    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
-    // only the matrix-core kernels carry the state packed
-    const bool m32 = prefill_mfma32_supported(d_feat, d_v, dtype);
-    if (!m32 && !prefill_mfma_supported(d_feat, d_v, dtype)) return BASED_ERR_UNSUPPORTED;
-    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
-    if (packed && !aligned16(packed)) return BASED_ERR_INVALID_ARG;
-    if (has_init && !packed) return BASED_ERR_INVALID_ARG;
-    const int U = B * H;
-    const size_t need = m32 ? prefill_mfma32_workspace_bytes(U, N, d_feat, d_v)
-                            : prefill_mfma_workspace_bytes(U, N, d_feat, d_v);
-    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
-    if (m32)
-        return status_of(launch_prefill_mfma32(q, k, v, y, static_cast<float *>(packed), has_init ? 1 : 0, 1,
-                                               workspace, U, N, d_feat, d_v, (hipStream_t)stream));
-    return status_of(launch_prefill_mfma(q, k, v, y, static_cast<float *>(packed), has_init ? 1 : 0, 1,
-                                         workspace, U, N, d_feat, d_v, (hipStream_t)stream));
-}
 
 int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,
                       int H, int d_feat, int d_v, int dtype, void *stream)

@@ -73,13 +73,13 @@ hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void 
 size_t prefill_ref_workspace_bytes(int U, int N, int dp, int dv);
 bool prefill_mfma_supported(int dp, int dv, int dtype);
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv);
-// packed_state != 0: the state buffer is the packed layout (one row per unordered feature pair)
+// packed_state != 0: the state buffer is the packed layout (one row per unordered feature pair);
+// status: the sticky word a workgroup sets when it gives up waiting for a segment's ready flag
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
-                               int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
-                               hipStream_t s);
-// byte offsets, inside a workspace of prefill_mfma_workspace_bytes, of the ready flags and of the
-// sticky status word that a workgroup sets when it gives up waiting for a flag
-void prefill_mfma_status_region(int U, int N, int dp, int dv, size_t *flags_offset, size_t *status_offset);
+                               int has_init, int packed_state, void *workspace, unsigned *status, int U, int N,
+                               int dp, int dv, hipStream_t s);
+// where the ready flags sit inside a workspace of prefill_mfma_workspace_bytes
+void prefill_mfma_flags_region(int U, int N, int dp, int dv, size_t *offset, size_t *bytes);
 // bound on the polls of one flag for later launches (negative: the default); a testing hook
 void prefill_mfma_set_poll_limit(int polls);
 bool prefill_mfma32_supported(int dp, int dv, int dtype);

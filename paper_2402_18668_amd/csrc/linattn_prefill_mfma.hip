@@ -933,8 +933,7 @@ bool prefill_mfma_supported(int dp, int dv, int dtype)
     return dtype == BASED_BF16 && dp == DP && (dv == 64 || dv == 128);
 }
 
-// Workspace: G entries per unit slice, then G x G ready-flag words per unit slice (256-byte aligned),
-// then 256 bytes whose first word is the sticky status of the bounded waits.
+// Workspace: G entries per unit slice, then G x G ready-flag words per unit slice (256-byte aligned).
 static size_t ws_entry_bytes(int U, int N, int dv)
 {
     return (size_t)U * (dv / DVS) * pick_segments(U, N, dv) * kWsEntryFloats * sizeof(float);
@@ -949,21 +948,21 @@ static size_t ws_flag_bytes(int U, int N, int dv)
 size_t prefill_mfma_workspace_bytes(int U, int N, int dp, int dv)
 {
     (void)dp;
-    return ws_entry_bytes(U, N, dv) + ws_flag_bytes(U, N, dv) + 256;
+    return ws_entry_bytes(U, N, dv) + ws_flag_bytes(U, N, dv);
 }
 
-void prefill_mfma_status_region(int U, int N, int dp, int dv, size_t *flags_offset, size_t *status_offset)
+void prefill_mfma_flags_region(int U, int N, int dp, int dv, size_t *offset, size_t *bytes)
 {
     (void)dp;
-    *flags_offset = ws_entry_bytes(U, N, dv);
-    *status_offset = *flags_offset + ws_flag_bytes(U, N, dv);
+    *offset = ws_entry_bytes(U, N, dv);
+    *bytes = ws_flag_bytes(U, N, dv);
 }
 
 void prefill_mfma_set_poll_limit(int polls) { g_flag_poll_limit.store(polls < 0 ? kMaxFlagPolls : polls); }
 
 hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void *y, float *state,
-                               int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
-                               hipStream_t s)
+                               int has_init, int packed_state, void *workspace, unsigned *status, int U, int N,
+                               int dp, int dv, hipStream_t s)
 {
     has_init = (has_init ? 1 : 0) | (packed_state ? 2 : 0);   // the kernels' flag word
     (void)dp;
@@ -984,7 +983,6 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
         static std::atomic<unsigned> calls{0};
         const unsigned epoch = 0x5EED0000u + calls.fetch_add(1u) + 1u;
         unsigned *flags = reinterpret_cast<unsigned *>((char *)workspace + ws_entry_bytes(U, N, dv));
-        unsigned *status = reinterpret_cast<unsigned *>((char *)flags + ws_flag_bytes(U, N, dv));
         const int groups = U * slices;
         hipLaunchKernelGGL(prefill_mfma_fused_kernel, dim3((unsigned)(groups * (2 * G - 1))), dim3(NT), 0, s,
                            q16, k16, v16, (uint16_t *)y, state, has_init, (float *)workspace, flags, status,
