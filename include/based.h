@@ -46,6 +46,7 @@ enum {
     BASED_OK = 0,
     BASED_ERR_INVALID_ARG = 1, /* null / misaligned pointer, non-positive size, bad pos */
     BASED_ERR_UNSUPPORTED = 2, /* size or dtype outside the supported set               */
+    BASED_ERR_TOO_LARGE = 4,   /* based_prefill_static: needs more than the static scratch   */
     BASED_ERR_LAUNCH = 3       /* the HIP runtime refused the launch, or (based_prefill_status)
                                   a launch gave up a bounded wait and its outputs are invalid */
 };
@@ -140,6 +141,27 @@ int based_prefill(const void *q, const void *k, const void *v, void *y, void *st
 int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
                          void *stream);
 void based_debug_set_poll_limit(int polls);
+
+/*
+ * based_prefill_static -- based_prefill for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as based_prefill without the workspace: the scratch is a device array of
+ * BASED_STATIC_SCRATCH_BYTES that lives inside the library (one copy per GPU, held from the
+ * moment the library's code is loaded on that GPU until the process ends).  The call allocates
+ * and frees nothing, on the host or on the device.
+ *   Errors: as based_prefill; BASED_ERR_TOO_LARGE when based_prefill_workspace_bytes(...) of the
+ *   sizes exceeds BASED_STATIC_SCRATCH_BYTES (nothing is launched); BASED_ERR_LAUNCH also when
+ *   the address of the scratch cannot be obtained.
+ *   All calls on one GPU share that GPU's scratch, whatever their stream: calls that may overlap
+ *   in time race on it and give wrong results; order them on one stream (or with events).  The
+ *   scratch keeps the last call's contents; nothing in it needs clearing between calls.
+ *   based_prefill_status with workspace = NULL asks about the calls made through this entry point
+ *   on the current device.
+ */
+#define BASED_STATIC_SCRATCH_BYTES (64u << 20)
+int based_prefill_static(const void *q, const void *k, const void *v, void *y, void *state,
+                         int has_init, int B, int H, int N, int d_feat, int d_v, int dtype,
+                         void *stream);
 
 /*
  * based_decode_step -- one token of the recurrent view (Eq. 3), state update fused with

@@ -17,12 +17,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("BASED_HIP_LIB") or os.path.join(_HERE, "lib", "libbased_hip.so")
 
 F32, BF16 = 0, 1
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH = 0, 1, 2, 3
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_TOO_LARGE = 0, 1, 2, 3, 4
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "based_strerror", "based_version", "based_feature_dim", "based_state_bytes",
     "based_state_stride_floats", "based_state_export", "based_state_import",
     "based_prefill_workspace_bytes", "based_prefill", "based_prefill_status", "based_debug_set_poll_limit",
+    "based_prefill_static",
     "based_decode_step", "based_swa_ring_bytes",
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
@@ -61,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.based_prefill_workspace_bytes.argtypes = [i, i, i, i, i, i]
     lib.based_prefill.restype = i
     lib.based_prefill.argtypes = [vp, vp, vp, vp, vp, i, vp, i, i, i, i, i, i, vp]
+    lib.based_prefill_static.restype = i
+    lib.based_prefill_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.based_prefill_status.restype = i
     lib.based_prefill_status.argtypes = [vp, i, i, i, i, i, i, vp]
     lib.based_debug_set_poll_limit.restype = None
@@ -189,6 +193,22 @@ def alloc_prefill_workspace(B, H, N, d_feat, d_v, dtype_code, device="cuda"):
     if n == 0:
         return None
     return torch.zeros((n + 3) // 4, dtype=torch.float32, device=device)
+
+
+def prefill_static(q, k, v, y, state=None, has_init=False):
+    """based_prefill_static: based_prefill on the library's own static scratch.  Allocates nothing, so
+    ``y`` must be given.  Returns the status code (the caller decides what an error means)."""
+    _dev(q, k, v, y, state)
+    B, H, N, dp = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:3]) != (B, H, N) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if y.shape != v.shape or y.dtype != v.dtype:
+        raise ValueError("y must match v")
+    if state is not None and (state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv)):
+        raise ValueError("state buffer too small or not fp32")
+    return int(lib.based_prefill_static(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
+                                        B, H, N, dp, dv, _dtype_code(q), _stream()))
 
 
 def prefill_status(workspace, B, H, N, d_feat, d_v, dtype_code) -> int:

@@ -2,6 +2,8 @@
 // contract of every entry point.
 #include "common.h"
 
+#include <mutex>
+
 using namespace based;
 
 namespace {
@@ -22,6 +24,36 @@ bool ok_counts(int B, int H, int N)
 }
 int status_of(hipError_t e) { return e == hipSuccess ? BASED_OK : BASED_ERR_LAUNCH; }
 
+// ---- scratch of based_prefill_static ------------------------------------------------------------
+// A file-scope device array: every GPU this library runs on holds its own copy, at its own address,
+// from the moment the code object is loaded there until the process ends (zero-filled at load).
+// In host code the array's name is only a handle; the device address comes from
+// hipGetSymbolAddress, asked once per device with that device current, and only that pointer is
+// ever handed to kernels or memory calls.
+constexpr size_t kStaticScratchBytes = BASED_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device, or nullptr (err says why)
+void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -32,6 +64,7 @@ const char *based_strerror(int status)
     case BASED_OK: return "ok";
     case BASED_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, non-positive size, bad pos)";
     case BASED_ERR_UNSUPPORTED: return "unsupported size or dtype";
+    case BASED_ERR_TOO_LARGE: return "the call needs more scratch memory than the library's static scratch holds";
     case BASED_ERR_LAUNCH: return "HIP launch failed, or a launch gave up waiting for one of its own workgroups";
     default: return "unknown status";
     }
@@ -131,13 +164,42 @@ int based_prefill_packed(const void *q, const void *k, const void *v, void *y, v
     return prefill_any(q, k, v, y, packed, has_init, 1, workspace, B, H, N, d_feat, d_v, dtype, stream);
 }
 
+int based_prefill_static(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                         int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
+    if (has_init && !state) return BASED_ERR_INVALID_ARG;
+    const size_t need = based_prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype);
+    if (need > kStaticScratchBytes) return BASED_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    if (need) {
+        hipError_t e;
+        ws = static_scratch(&e);
+        if (!ws) return BASED_ERR_LAUNCH;
+    }
+    // Nothing in the scratch has to start at zero for a new call: workspace entries are written
+    // before they are read, ready flags carry a per-call epoch and are cleared by their readers, and
+    // the status word (zero when the array is created) is meant to persist until
+    // based_prefill_status has seen it.
+    return prefill_any(q, k, v, y, state, has_init, 0, ws, B, H, N, d_feat, d_v, dtype, stream);
+}
+
 int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
 {
     if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
     if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
     // only the single-launch segmented prefill (bf16, d' = 16) has workgroups that wait for each other
     if (!prefill_mfma_supported(d_feat, d_v, dtype)) return BASED_OK;
-    if (!workspace) return BASED_ERR_INVALID_ARG;
+    if (!workspace) {
+        // the calls asked about went through based_prefill_static
+        if (based_prefill_workspace_bytes(B, H, N, d_feat, d_v, dtype) > kStaticScratchBytes) return BASED_ERR_TOO_LARGE;
+        hipError_t e;
+        workspace = static_scratch(&e);
+        if (!workspace) return BASED_ERR_LAUNCH;
+    }
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return BASED_ERR_INVALID_ARG;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return BASED_ERR_LAUNCH;
     unsigned word = 0;

@@ -72,7 +72,11 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_prefill_status(p, 1, 1, 8, 24, 64, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_prefill_status(null, 1, 1, 8, 16, 64, 0, st) == based.OK
     assert lib.based_prefill_status(null, 1, 1, 8, 32, 64, 1, st) == based.OK
-    assert lib.based_prefill_status(null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    # the entry point on the library's static scratch: same host checks, and its size limit
+    assert lib.based_prefill_static(null, p, p, p, null, 0, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill_static(p, p, p, p, null, 0, 1, 1, 8, 16, 96, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill_static(p, p, p, p, null, 0, 64, 16, 8192, 32, 128, 1, st) == based.ERR_TOO_LARGE
+    assert lib.based_prefill_status(null, 64, 16, 8192, 16, 128, 1, st) == based.ERR_TOO_LARGE
     lib.based_debug_set_poll_limit(5)
     lib.based_debug_set_poll_limit(-1)
     # decode
