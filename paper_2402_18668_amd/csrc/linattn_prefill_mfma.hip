@@ -96,23 +96,20 @@ __host__ __device__ constexpr size_t entry_floats(int nc) { return (size_t)nc * 
 
 template <int NC>
 struct Lds {
-    // The first four arrays (16,432 bytes) are dead once a chunk's operands are built; the readout
-    // waves then turn their finished output tiles through the same bytes (yt).
-    union Front {
-        struct {
-            float kts[KT_ROWS][KTS_LD];     // c_k * K^T, then the rows [valid / c_k], [valid * c_k], [0]
-            float qs[C][QS_LD];             // c_q * Q
-            uint16_t qrow[C][RB_LD];        // Q rows, bf16 as given
-            uint16_t krow[C][RB_LD];        // K rows, bf16 as given
-        } st;
-        uint16_t yt[NC][32][YT_LD];         // per readout wave: a finished output tile on its way out
-    } f;
-    uint16_t vrow[C][32 * NC + 16];     // V rows, bf16 as given (operands are read transposed; the
-                                        // stride leaves those reads free of bank conflicts)
-    u32x4 phik[NTILE][4][64];           // phi(K)^T operands: [state tile][16-token slab][lane]
-    u32x4 pop[3][2][64];                // masked intra-chunk blocks as operands: [block][slab][lane]
-    float den[3][C];                    // per query: inter-chunk part; row sums of the blocks of key tile 0, 1
-    u32x4 sb[NC][NSLAB][64];            // bf16 copy of the state as readout operands: [column tile][slab][lane]
+    // the producers' own staging of the q and k rows of the chunk they are preparing
+    float kts[KT_ROWS][KTS_LD];         // c_k * K^T, then the rows [valid / c_k], [valid * c_k], [0]
+    float qs[C][QS_LD];                 // c_q * Q
+    uint16_t qrow[C][RB_LD];            // Q rows, bf16 as given
+    uint16_t krow[C][RB_LD];            // K rows, bf16 as given
+    // everything the consumers read exists twice, indexed by the parity of the chunk: the producers fill
+    // one generation while the consumers work on the other
+    uint16_t vrow[2][C][32 * NC + 16];  // V rows, bf16 as given (operands are read transposed; the stride
+                                        // leaves those reads free of bank conflicts)
+    u32x4 phiq[2][2][NSLAB][64];        // phi(Q)^T operands: [parity][query tile][slab][lane]
+    u32x4 phik[2][NTILE][4][64];        // phi(K)^T operands: [parity][state tile][16-token slab][lane]
+    u32x4 pop[2][3][2][64];             // masked intra-chunk blocks as operands: [parity][block][slab][lane]
+    float den[2][3][C];                 // per query: inter-chunk part; row sums of the blocks of key tile 0, 1
+    uint16_t yt[NC][32][YT_LD];         // per consumer wave: a finished output tile on its way out
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -194,9 +191,12 @@ __device__ __forceinline__ CanonRows canon_rows(int T, int fl, bool packed_state
 // written by a workgroup on one XCD is only guaranteed to be seen by another XCD's workgroups at a
 // kernel boundary, unless the accesses are marked system-coherent (sc0 sc1: written through to, and
 // read from, the memory side of the L2s).
+// (A store of more than 64 bits reads its data registers a few cycles after it issues, and whatever
+// overwrites them in the next two cycles corrupts the stored data.  The compiler keeps that distance for
+// stores it emits itself but cannot see inside an asm statement, so the wait states are part of it.)
 __device__ __forceinline__ void store16_coherent(float *p, const f32x4 &v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 2" : : "v"(p), "v"(v) : "memory");
 }
 // The six slots of one wave in one entry: all 24 loads are in flight at once and the wait sits in the
 // same statement, so that every output register is valid as far as the compiler can tell.  p1, p3, p5
@@ -269,8 +269,7 @@ __device__ __forceinline__ void prefill_body(
     float *__restrict__ ws, unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls,
     unsigned epoch, int N, const SegTable &segs, int G, int seg, int u)
 {
-    constexpr int NW = 2 * NC;        // waves: a readout wave and an update wave per 32 columns
-    constexpr int NT = 64 * NW;
+    constexpr int NP = 64 * NC;       // producer threads
     constexpr int DV = 32 * NC;       // d_v
     constexpr int VR_LD = DV + 16;
     // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
@@ -278,13 +277,14 @@ __device__ __forceinline__ void prefill_body(
     has_init &= 1;
     const int tid = threadIdx.x;
     const int w = tid >> 6;
-    const bool is_u = w >= NC;            // update wave (owns the state tiles) or readout wave
-    const int c = is_u ? w - NC : w;      // column tile: columns 32c .. 32c+31
+    const bool is_p = w >= NC;            // producer wave; else consumer wave (owns the state tiles)
+    const int c = is_p ? w - NC : w;      // consumer: column tile (columns 32c .. 32c+31); producer: its role
     const int lane = tid & 63;
     const int g = lane >> 5, n = lane & 31;
 
     const int tok_begin = segs.begin[seg];
     const int tok_end = min(N, segs.begin[seg + 1]);
+    const int n_chunks = (tok_end - tok_begin + C - 1) / C;
 
     const uint16_t *qu = q + (size_t)u * N * DP;
     const uint16_t *ku = k + (size_t)u * N * DP;
@@ -295,49 +295,39 @@ __device__ __forceinline__ void prefill_body(
     float *zu = Su ? Su + (size_t)(packed_state ? packed_feature_dim(DP) : feature_dim(DP)) * DV : nullptr;
     float *ws_unit = ws ? ws + (size_t)u * G * entry_floats(NC) : nullptr;
     unsigned *flags_unit = flags ? flags + (size_t)u * G * G : nullptr;
-    // this lane's 16 bytes of register group 0 of slot 0 of this column tile, inside an entry
-    const size_t lane_off = (size_t)c * WS_WAVE_SLOTS * kSlotFloats + (size_t)lane * 4;
+    // this lane's 16 bytes of register group 0 of slot 0 of column tile c (producer 0 keeps the moment
+    // tile, which travels in the sixth slot of column tile 0), inside an entry
+    const size_t lane_off = (size_t)(is_p ? 0 : c) * WS_WAVE_SLOTS * kSlotFloats + (size_t)lane * 4;
+    const bool holds_x = is_p && c == 0;
 
-    // ---- accumulators (update waves) -------------------------------------------------------------
-    f32x16 S[NTILE];       // the five state tiles of this wave's 32 columns
-    f32x16 X;              // update wave of column tile 0: the moment tile M' = [k, 1]^T [k, 1]
-#pragma unroll
-    for (int T = 0; T < NTILE; ++T) zero16(S[T]);
-    zero16(X);
-
-    // bf16 copy of the state tiles as the A operands of the next readout: register-local conversion
-    // (accumulator registers 8 sl .. 8 sl + 7 of tile T are the k-slots of slab 2T + sl), one 16-byte
-    // LDS store per lane and operand
-    auto publish_state = [&]() {
-#pragma unroll
-        for (int T = 0; T < NTILE; ++T)
-#pragma unroll
-            for (int sl = 0; sl < 2; ++sl) lds.sb[c][2 * T + sl][lane] = as_u32x4(pack8_acc(S[T], sl));
-    };
-
-    if (MODE == 0) {
-        // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
-        const int p0 = has_init ? 0 : 1;
-        if (G > 1 && seg > 0) {
-            // wait for the increments of this call (entry 0 comes from an earlier launch)
-            if (tid == 0) {
-                bool gave_up = false;
-                for (int p = 1; p <= seg; ++p) {
-                    unsigned *f = flags_unit + p * G + seg;
-                    int polls = 0;
-                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch) {
-                        if (polls++ >= max_polls) { gave_up = true; break; }
-                        __builtin_amdgcn_s_sleep(8);
-                    }
-                    __hip_atomic_store(f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (MODE == 0 && G > 1 && seg > 0) {
+        // wait for the increments of this call (entry 0 comes from an earlier launch)
+        if (tid == 0) {
+            bool gave_up = false;
+            for (int p = 1; p <= seg; ++p) {
+                unsigned *f = flags_unit + p * G + seg;
+                int polls = 0;
+                while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != epoch) {
+                    if (polls++ >= max_polls) { gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(8);
                 }
-                // sticky: stays set until based_prefill_status has reported it
-                if (gave_up) __hip_atomic_store(status, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
-            __syncthreads();
+            // sticky: stays set until based_prefill_status has reported it
+            if (gave_up) __hip_atomic_store(status, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        if (is_u) {
-            for (int p = p0; p <= seg; ++p) {
+        __syncthreads();
+    }
+
+    if (!is_p) {
+        // =================================== consumer waves =========================================
+        f32x16 S[NTILE];       // the five state tiles of this wave's 32 columns
+#pragma unroll
+        for (int T = 0; T < NTILE; ++T) zero16(S[T]);
+
+        if (MODE == 0) {
+            // start of segment: initial state (entry 0, if any) plus the increments of earlier segments
+            for (int p = has_init ? 0 : 1; p <= seg; ++p) {
                 const float *e = ws_unit + (size_t)p * entry_floats(NC) + lane_off;
                 f32x4 t[24];
                 load_wave_slots_coherent(e + 1 * kSlotFloats, e + 3 * kSlotFloats, e + 5 * kSlotFloats, t);
@@ -345,494 +335,166 @@ __device__ __forceinline__ void prefill_body(
                 for (int T = 0; T < NTILE; ++T)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) S[T][r] += t[T * 4 + (r >> 2)][r & 3];
-                if (c == 0) {
+            }
+        }
+        if (MODE == 2) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) X[r] += t[20 + (r >> 2)][r & 3];
+            for (int r = 0; r < 16; ++r) {
+                const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
+                const size_t col = (size_t)32 * c + n;
+#pragma unroll
+                for (int T = 0; T < NTILE; ++T) {
+                    const CanonRows cr = canon_rows(T, fl, packed_state);
+                    if (cr.r1 >= 0) S[T][r] = 0.5f * (Su[(size_t)cr.r1 * DV + col] + Su[(size_t)cr.r2 * DV + col]);
                 }
             }
-            publish_state();
         }
-    }
-    if (MODE == 2 && is_u) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
-            const size_t col = (size_t)32 * c + n;
-#pragma unroll
-            for (int T = 0; T < NTILE; ++T) {
-                const CanonRows cr = canon_rows(T, fl, packed_state);
-                if (cr.r1 >= 0) S[T][r] = 0.5f * (Su[(size_t)cr.r1 * DV + col] + Su[(size_t)cr.r2 * DV + col]);
-            }
-            if (c == 0) {
-                float m = 0.f;   // M'[fl][n]
-                if (fl < DP && n < DP) m = zu[canon_pair(fl, n, packed_state).r1] * 1.41421356237309504880f;
-                else if (fl == DP && n < DP) m = zu[1 + n];
-                else if (fl < DP && n == DP) m = zu[1 + fl];
-                else if (fl == DP && n == DP) m = zu[0];
-                X[r] = m;
-            }
-        }
-    }
 
-    // once: the row sums of a block that does not exist (key tile 1 against query tile 0)
-    if (MODE != 2 && tid < C) lds.den[2][tid] = 0.f;
+        if (MODE != 2) {
+            // V operand of an MFMA (lane (g, n): column 32 c + n at the 8 tokens of its k-slots, two runs of
+            // 4 consecutive tokens starting at tok4 and tok4 + 8) from the row-major V rows: the transposing
+            // LDS read.  In each group of 16 lanes, lane k supplies the address of 4 consecutive columns
+            // (4 (k % 4) ..) of row k / 4 of the group's 16-column block and receives column k of that
+            // block at the 4 rows.  The same registers serve as A operand (V^T, output product) and as B
+            // operand (update).
+            const int tr_kk = lane & 15, tr_grp = (lane >> 4) & 1;
+            const uint16_t *tr_base = &lds.vrow[0][(tr_kk >> 2) + 4 * g][32 * c + 16 * tr_grp + 4 * (tr_kk & 3)];
+            auto load_v = [&](int b, int ts) {   // tokens 16 ts + 4 g + {0..3, 8..11}
+                const uint16_t *p = tr_base + (b * C + 16 * ts) * VR_LD;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 8 * VR_LD));
+                s16x8 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { o[i] = lo[i]; o[4 + i] = hi[i]; }
+                return __builtin_bit_cast(bf16x8, o);
+            };
 
-    // ---- staging: global -> registers -> LDS ----------------------------------------------------
-    // A chunk of V is one contiguous block of 64 rows x DV columns: 16-byte piece p = tid + NT j
-    // (j = 0, 1) is row p / (DV / 8), columns 8 (p % (DV / 8)) ...  A chunk of K (and of Q) is 128
-    // pieces: piece p holds elements 8 (p % 2) .. of token p / 2; threads 0..127 stage K, threads
-    // 128..255 stage Q.
-    constexpr int VPR = DV / 8;   // pieces per V row
-    const bool is_k = tid < 128, is_q = tid >= 128 && tid < 256;
-    const int xp = tid & 127;
-    const int x_tok = xp >> 1, x_h = xp & 1;
-    u32x4 raw_x = {0u, 0u, 0u, 0u};
-    u32x4 raw_v[2];
-    // Loads are unconditional (rows past the end of the segment re-read its last row and are zeroed
-    // when staged): a conditional load would have the compiler pre-zero its destination registers,
-    // and before that write it waits for every memory operation still in flight, stores included.
-    auto load_raw = [&](int tok0) {
-        const int tok = min(tok0 + x_tok, tok_end - 1);
-        const uint16_t *xsrc = (is_k || MODE != 0) ? ku : qu;   // threads past 255 re-read K and drop it
-        raw_x = *reinterpret_cast<const u32x4 *>(xsrc + (size_t)tok * DP + 8 * x_h);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int p = tid + NT * j;
-            const int row = min(tok0 + p / VPR, tok_end - 1);
-            raw_v[j] = *reinterpret_cast<const u32x4 *>(vu + (size_t)row * DV + 8 * (p % VPR));
-        }
-    };
-    auto stage = [&](int tok0) {
-        const bool valid = tok0 + x_tok < tok_end;
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
-        if (is_k) {
-            const u32x4 raw = valid ? raw_x : zero4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lds.f.st.kts[8 * x_h + 2 * i][x_tok] = bf16lo(raw[i]) * kCK;
-                lds.f.st.kts[8 * x_h + 2 * i + 1][x_tok] = bf16hi(raw[i]) * kCK;
-            }
-            *reinterpret_cast<u32x4 *>(&lds.f.st.krow[x_tok][8 * x_h]) = raw;
-            if (x_h == 0) {
-                lds.f.st.kts[DP][x_tok] = valid ? 1.f / kCK : 0.f;
-                lds.f.st.kts[DP + 1][x_tok] = valid ? kCK : 0.f;
-            } else {
-                lds.f.st.kts[DP + 2][x_tok] = 0.f;
-            }
-        } else if (MODE == 0 && is_q) {
-            const u32x4 raw = raw_x;
-            f32x4 lo, hi;
-            lo[0] = bf16lo(raw[0]) * kCQ; lo[1] = bf16hi(raw[0]) * kCQ;
-            lo[2] = bf16lo(raw[1]) * kCQ; lo[3] = bf16hi(raw[1]) * kCQ;
-            hi[0] = bf16lo(raw[2]) * kCQ; hi[1] = bf16hi(raw[2]) * kCQ;
-            hi[2] = bf16lo(raw[3]) * kCQ; hi[3] = bf16hi(raw[3]) * kCQ;
-            *reinterpret_cast<f32x4 *>(&lds.f.st.qs[x_tok][8 * x_h]) = lo;
-            *reinterpret_cast<f32x4 *>(&lds.f.st.qs[x_tok][8 * x_h + 4]) = hi;
-            *reinterpret_cast<u32x4 *>(&lds.f.st.qrow[x_tok][8 * x_h]) = raw;
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int p = tid + NT * j;
-            const int row = p / VPR;
-            *reinterpret_cast<u32x4 *>(&lds.vrow[row][8 * (p % VPR)]) = tok0 + row < tok_end ? raw_v[j] : zero4;
-        }
-    };
-
-    // V operand of an MFMA (lane (g, n): column 32 c + n at the 8 tokens of its k-slots, two runs of 4
-    // consecutive tokens starting at tok4 and tok4 + 8) from the row-major V rows: the transposing LDS
-    // read.  In each group of 16 lanes, lane k supplies the address of 4 consecutive columns
-    // (4 (k % 4) ..) of row k / 4 of the group's 16-column block and receives column k of that block at
-    // the 4 rows.  The same layout serves as A operand (V^T, output product) and B operand (update).
-    const int tr_kk = lane & 15, tr_grp = (lane >> 4) & 1;
-    const uint16_t *tr_base = &lds.vrow[(tr_kk >> 2) + 4 * g][32 * c + 16 * tr_grp + 4 * (tr_kk & 3)];
-    auto load_v = [&](int ts) {   // tokens 16 ts + 4 g + {0..3, 8..11}
-        const uint16_t *p = tr_base + 16 * ts * VR_LD;
-        const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-        const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 8 * VR_LD));
-        s16x8 o;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { o[i] = a[i]; o[4 + i] = b[i]; }
-        return __builtin_bit_cast(bf16x8, o);
-    };
-
-    // ---- the pieces of a chunk ------------------------------------------------------------------
-    // phi(Q)^T operands of query tile qt, all ten slabs, built by every readout wave for itself, in
-    // registers: lane (g, n) is query 32 qt + n; k-slot (jj, i) of slab s is feature row
-    // 16 s + 8 jj + 4 g + i.  xr[j] = c_q q[(4g + j) % 16] is the lane's query row rotated by 4g, so that
-    // the "a side" of k-slot (jj, i) is xr[8 jj + i] and the "b side" of delta is
-    // xr[(8 jj + i + delta) % 16]: every product is between two registers known at compile time.
-    auto build_phiq = [&](const int qt, bf16x8 (&out)[NSLAB]) {
-        float xr[16];
-        const float *row = lds.f.st.qs[32 * qt + n];
-        f32x4 t[4];
-#pragma unroll
-        for (int m = 0; m < 4; ++m) t[m] = *reinterpret_cast<const f32x4 *>(row + ((4 * g + 4 * m) & 15));
-        // slab 8: the linear rows; the operand is q itself, as given
-        const uint16_t *p = &lds.f.st.qrow[32 * qt + n][4 * g];
-        const u32x2 ra = *reinterpret_cast<const u32x2 *>(p);
-        const u32x2 rb = *reinterpret_cast<const u32x2 *>(p + 8);
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) xr[4 * m + i] = t[m][i];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {   // pair slabs: delta = s
-            float pr[8];
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int a = 8 * jj + i;
-                    const float av = s == 0 ? xr[a] * 0.5f : xr[a];   // delta = 0: x_a^2 / sqrt(2)
-                    pr[4 * jj + i] = av * xr[(a + s) & 15];
-                }
-            out[s] = pack8(pr);
-        }
-        {
-            u32x4 o; o[0] = ra[0]; o[1] = ra[1]; o[2] = rb[0]; o[3] = rb[1];
-            out[8] = as_bf16x8(o);
-        }
-        {   // slab 9: the constant row (k-slot 0 of g = 0 = row 16 of the tile), padding, and the delta = 8
-            // rows (k-slots 4 + i = row 24 + 4g + i: sqrt(2) q_a q_(a+8), a = 4g + i)
-            float pr[8];
-            pr[0] = g == 0 ? 1.f : 0.f; pr[1] = 0.f; pr[2] = 0.f; pr[3] = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pr[4 + i] = xr[i] * xr[8 + i];
-            out[9] = pack8(pr);
-        }
-    };
-    // phi(K)^T operands of token slab ts, all five state tiles, shared by the update waves through LDS:
-    // lane (g, n) is feature row n of a tile, its k-slots are the tokens 16 ts + 4 g + {0..3, 8..11}.
-    // Every row is a product of two rows of the staged K^T: pair rows k_a k_b / sqrt(2); linear rows
-    // (c_k k_a)(valid / c_k); the constant row (valid c_k)(valid / c_k); padding rows 0 * 0.
-    // (c_k k_a / c_k differs from k_a by fp32 rounding only, far below half a bf16 step, so the
-    // conversion returns k_a exactly.)  The "a" row of the four pair tiles is the same (a = n % 16), so
-    // a slab costs 14 LDS loads, all issued before the products.
-    const float *kt_a03 = &lds.f.st.kts[n & 15][4 * g];
-    const float *kt_a4 = &lds.f.st.kts[n < DP ? n : (n == DP ? DP + 1 : (n < 24 ? DP + 2 : n - 24))][4 * g];
-    const float *kt_b[NTILE];
-#pragma unroll
-    for (int T = 0; T < 4; ++T) kt_b[T] = &lds.f.st.kts[((n & 15) + 2 * T + (n >> 4)) & 15][4 * g];
-    kt_b[4] = &lds.f.st.kts[n < DP ? DP : (n == DP ? DP : (n < 24 ? DP + 2 : n - 16))][4 * g];
-    auto build_phik = [&](const int ts) {
-        f32x4 a03[2], a4[2], kb[NTILE][2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            a03[h] = *reinterpret_cast<const f32x4 *>(kt_a03 + 16 * ts + 8 * h);
-            a4[h] = *reinterpret_cast<const f32x4 *>(kt_a4 + 16 * ts + 8 * h);
-#pragma unroll
-            for (int T = 0; T < NTILE; ++T) kb[T][h] = *reinterpret_cast<const f32x4 *>(kt_b[T] + 16 * ts + 8 * h);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int T = 0; T < NTILE; ++T) {
-            float pr[8];
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pr[4 * h + i] = (T < 4 ? a03[h][i] : a4[h][i]) * kb[T][h][i];
-            lds.phik[T][ts][lane] = as_u32x4(pack8(pr));
-        }
-    };
-    // Intra-chunk block b: 0 = key tile 0 against query tile 0, 1 = key tile 0 against query tile 1,
-    // 2 = key tile 1 against query tile 1 (0 and 2 are cut by the diagonal).
-    // P^T = mask(1 + A^T + A^T^2 / 2), A^T = K Q^T: lane (g, n) is query 32 qt + n, register r is key
-    // 32 kt + 8 (r / 4) + 4 g + r % 4.  Keys past the end of the segment come after every valid query
-    // and fall to the causal mask.  Split in two so that a wave can do other work under the product.
-    auto block_start = [&](const int b) {
-        const int kt = b == 2 ? 1 : 0, qt = b == 0 ? 0 : 1;
-        f32x16 P;
-        zero16(P);
-        const u32x4 kop = *reinterpret_cast<const u32x4 *>(&lds.f.st.krow[32 * kt + n][8 * g]);
-        const u32x4 qop = *reinterpret_cast<const u32x4 *>(&lds.f.st.qrow[32 * qt + n][8 * g]);
-        return mfma(as_bf16x8(kop), as_bf16x8(qop), P);
-    };
-    auto block_finish = [&](const int b, f32x16 P) {
-        const int kt = b == 2 ? 1 : 0, qt = b == 0 ? 0 : 1;
-        const bool diag = b != 1;
-        float dsum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float x = P[r];
-            float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
-            const int key = 8 * (r >> 2) + 4 * g + (r & 3);
-            pv = (!diag || key <= n) ? pv : 0.f;
-            P[r] = pv;
-            dsum += pv;
-        }
-        lds.pop[b][0][lane] = as_u32x4(pack8_acc(P, 0));
-        lds.pop[b][1][lane] = as_u32x4(pack8_acc(P, 1));
-        dsum += __shfl_xor(dsum, 32, 64);
-        if (g == 0) lds.den[1 + kt][32 * qt + n] = dsum;
-    };
-    // Inter-chunk denominators of both query tiles from the moments: count + q.z1 + q^T M q / 2.
-    auto build_den = [&]() {
-        f32x4 a0[2], a1[2];
-        u32x2 ra[2], rb[2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            const float *row = lds.f.st.qs[32 * qt + n];
-            a0[qt] = *reinterpret_cast<const f32x4 *>(row + 4 * g);
-            a1[qt] = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
-            const uint16_t *p = &lds.f.st.qrow[32 * qt + n][4 * g];
-            ra[qt] = *reinterpret_cast<const u32x2 *>(p);
-            rb[qt] = *reinterpret_cast<const u32x2 *>(p + 8);
-        }
-        float mres[8];
-        const bf16x8 mhi = pack8_acc(X, 0);
-        {
-            const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                mres[2 * i] = X[2 * i] - bf16lo(hb[i]);
-                mres[2 * i + 1] = X[2 * i + 1] - bf16hi(hb[i]);
-            }
-        }
-        const bf16x8 mlo = pack8(mres);
-        const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[8]), 16));
-        f32x16 T[2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            u32x4 o; o[0] = ra[qt][0]; o[1] = ra[qt][1]; o[2] = rb[qt][0]; o[3] = rb[qt][1];
-            zero16(T[qt]);
-            T[qt] = mfma(mhi, as_bf16x8(o), T[qt]);
-            T[qt] = mfma(mlo, as_bf16x8(o), T[qt]);
-        }
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            float d2 = 0.f;
-            // row of T[e] = 8 (e / 4) + 4 g + e % 4
-#pragma unroll
-            for (int e = 0; e < 4; ++e) d2 = fmaf(T[qt][e], a0[qt][e], d2);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) d2 = fmaf(T[qt][4 + e], a1[qt][e], d2);
-            const float d = fmaf(d2, kHalfInvCQ, T[qt][8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
-            const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
-            if (g == 0) lds.den[0][32 * qt + n] = tot;
-        }
-    };
-
-    // Pipeline: the rows of chunk c+1 are fetched from global memory into registers at the top of
-    // chunk c and written to LDS at its bottom, so their latency hides under the whole chunk.
-    // Every chunk has three barriers: [rows staged] phase 1: operands [operands visible] phase 2: matrix
-    // products [all reads done] stage the next rows.  The two kinds of wave run the same barrier
-    // sequence in loops of their own, so that the registers of one role are not live in the other.
-    if (MODE != 2) {
-        load_raw(tok_begin);
-        stage(tok_begin);
-    }
-    if (MODE != 2 && !is_u) {
-        // ================================ readout waves =============================================
-        for (int tok0 = tok_begin; tok0 < tok_end; tok0 += C) {
-            wg_sync();   // this chunk's rows, and the state operands after the previous chunk, are visible
-            const bool more = tok0 + C < tok_end;
-            if (more) load_raw(tok0 + C);   // a whole chunk ahead: consumed by stage() at the bottom
-            // phase 1: the bf16 state of this column tile (the update waves overwrite it in phase 2),
-            // phi(Q) of both query tiles in registers
-            bf16x8 sbr[NSLAB], phq[2][NSLAB];
-            if (MODE == 0) {
-#pragma unroll
-                for (int sl = 0; sl < NSLAB; ++sl) sbr[sl] = as_bf16x8(lds.sb[c][sl][lane]);
-                build_phiq(0, phq[0]);
-                build_phiq(1, phq[1]);
-            }
-            wg_sync();   // the shared operands are visible; the staging of q and k is dead
-            if (MODE == 0) {
-                // phase 2.  All LDS loads are issued first, into registers of their own, so that the
-                // matrix instructions below wait for LDS once.
+            wg_sync();   // (the producers stage the first chunk)
+            wg_sync();   // the operands of the first chunk are visible
+            for (int t = 0; t < n_chunks; ++t) {
+                const int b = t & 1;
+                const int tok0 = tok_begin + C * t;
                 bf16x8 vop[4];
 #pragma unroll
-                for (int ts = 0; ts < 4; ++ts) vop[ts] = load_v(ts);
-                float dn[2][3];
-#pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-                    for (int d = 0; d < 3; ++d) dn[qt][d] = lds.den[d][32 * qt + n];
-                // readout: Y^T of query tile qt: lane (g, n) = query 32 qt + n, register r = column
-                // 32 c + 8 (r / 4) + 4 g + r % 4
+                for (int ts = 0; ts < 4; ++ts) vop[ts] = load_v(b, ts);
                 f32x16 Y[2];
-                zero16(Y[0]); zero16(Y[1]);
+                float dn[2][3];
+                if (MODE == 0) {
+                    // ---- readout: Y^T of query tile qt: lane (g, n) = query 32 qt + n, register r = column
+                    // 32 c + 8 (r / 4) + 4 g + r % 4.  The bf16 copy of a state tile (a register-local
+                    // conversion: accumulator registers 8 sl .. 8 sl + 7 are the k-slots of slab 2T + sl) is the
+                    // A operand.  The LDS loads go out in groups, into registers of their own, ahead of the
+                    // matrix instructions that consume them.
+                    u32x4 oa[2][5], ob[2][5];
 #pragma unroll
-                for (int sl = 0; sl < NSLAB; ++sl)
+                    for (int sl = 0; sl < 5; ++sl)
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) Y[qt] = mfma(sbr[sl], phq[qt][sl], Y[qt]);
-                // intra-chunk: Y^T += V^T P^T over the key tiles at or before the query tile (the blocks are
-                // fetched into the registers the state operands have just left)
-                u32x4 op[3][2];
+                        for (int qt = 0; qt < 2; ++qt) oa[qt][sl] = lds.phiq[b][qt][sl][lane];
 #pragma unroll
-                for (int bb = 0; bb < 3; ++bb)
+                    for (int sl = 0; sl < 5; ++sl)
 #pragma unroll
-                    for (int sl = 0; sl < 2; ++sl) op[bb][sl] = lds.pop[bb][sl][lane];
+                        for (int qt = 0; qt < 2; ++qt) ob[qt][sl] = lds.phiq[b][qt][5 + sl][lane];
 #pragma unroll
-                for (int sl = 0; sl < 2; ++sl) {
-                    Y[0] = mfma(vop[sl], as_bf16x8(op[0][sl]), Y[0]);
-                    Y[1] = mfma(vop[sl], as_bf16x8(op[1][sl]), Y[1]);
+                    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                        for (int d = 0; d < 3; ++d) dn[qt][d] = lds.den[b][d][32 * qt + n];
+                    __builtin_amdgcn_sched_barrier(0);
+                    zero16(Y[0]); zero16(Y[1]);
+#pragma unroll
+                    for (int sl = 0; sl < 5; ++sl) {
+                        const bf16x8 sb = pack8_acc(S[sl >> 1], sl & 1);
+#pragma unroll
+                        for (int qt = 0; qt < 2; ++qt) Y[qt] = mfma(sb, as_bf16x8(oa[qt][sl]), Y[qt]);
+                    }
+                    // the intra-chunk blocks, into the registers the first group has left
+                    u32x4 op[3][2];
+#pragma unroll
+                    for (int bb = 0; bb < 3; ++bb)
+#pragma unroll
+                        for (int sl = 0; sl < 2; ++sl) op[bb][sl] = lds.pop[b][bb][sl][lane];
+#pragma unroll
+                    for (int sl = 5; sl < NSLAB; ++sl) {
+                        const bf16x8 sb = pack8_acc(S[sl >> 1], sl & 1);
+#pragma unroll
+                        for (int qt = 0; qt < 2; ++qt) Y[qt] = mfma(sb, as_bf16x8(ob[qt][sl - 5]), Y[qt]);
+                    }
+                    // intra-chunk: Y^T += V^T P^T over the key tiles at or before the query tile
+#pragma unroll
+                    for (int sl = 0; sl < 2; ++sl) {
+                        Y[0] = mfma(vop[sl], as_bf16x8(op[0][sl]), Y[0]);
+                        Y[1] = mfma(vop[sl], as_bf16x8(op[1][sl]), Y[1]);
+                    }
+#pragma unroll
+                    for (int sl = 0; sl < 2; ++sl) Y[1] = mfma(vop[2 + sl], as_bf16x8(op[2][sl]), Y[1]);
                 }
-#pragma unroll
-                for (int sl = 0; sl < 2; ++sl) Y[1] = mfma(vop[2 + sl], as_bf16x8(op[2][sl]), Y[1]);
-#pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
-                    // normalise and turn the tile through LDS: a lane holds 8-byte pieces of its token's
-                    // row, and stored directly those become 16-byte write requests that stall the memory
-                    // pipeline; from LDS the tile leaves as 64-byte row segments, 16 rows a store.
-                    const float inv = __builtin_amdgcn_rcpf(dn[qt][0] + dn[qt][1] + dn[qt][2]);
-                    uint16_t *yt = &lds.f.yt[c][0][0];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        f32x4 o;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) o[i] = Y[qt][4 * j + i] * inv;
-                        const bf16x4 hv = __builtin_convertvector(o, bf16x4);
-                        *reinterpret_cast<u32x2 *>(yt + n * YT_LD + 8 * j + 4 * g) = __builtin_bit_cast(u32x2, hv);
-                    }
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    uint16_t *yc = yu + (size_t)tok0 * DV;
-                    // A full chunk stores without a per-lane condition: stores that are certain to be
-                    // issued can be counted, so the later wait for the prefetched rows (issued before
-                    // them; the counter retires in order) does not have to wait for the stores as well.
-                    u32x4 val[2];
-                    uint32_t yoff[2];
-#pragma unroll
-                    for (int it = 0; it < 2; ++it) {
-                        const int row = 16 * it + (lane >> 2), cc = lane & 3;
-                        val[it] = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * cc);
-                        yoff[it] = (uint32_t)(32 * qt + row) * (uint32_t)DV + (uint32_t)(32 * c + 8 * cc);
-                    }
-                    if (tok0 + C <= tok_end) {
-#pragma unroll
-                        for (int it = 0; it < 2; ++it) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
-                    } else {
-#pragma unroll
-                        for (int it = 0; it < 2; ++it)
-                            if (tok0 + 32 * qt + 16 * it + (lane >> 2) < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
-                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    }
-                    // the next query tile overwrites this wave's staging only after these reads: LDS
-                    // operations of one wave execute in order
-                }
-            }
-            if (more) {
-                wg_sync();   // every wave is done with this chunk's V rows, operands and output staging
-                stage(tok0 + C);
-            }
-        }
-    }
-    if (MODE != 2 && is_u) {
-        // ================================ update waves ==============================================
-        for (int tok0 = tok_begin; tok0 < tok_end; tok0 += C) {
-            wg_sync();
-            const bool more = tok0 + C < tok_end;
-            if (more) load_raw(tok0 + C);
-            // phase 1: the shared operands.  Four column tiles: 0 = denominators + phi(K) of token slab
-            // 0; c = 1..3: block c - 1 + phi(K) of token slab c.  Two: 0 = block 0, denominators, slabs 0
-            // and 1; 1 = blocks 1 and 2, slabs 2 and 3.  Increment pass: phi(K) only.
-            if (MODE == 0) {
-                if (NC == 4) {
-                    if (c == 0) {
-                        role_guard();
-                        build_den();
-                        build_phik(0);
-                    } else if (c == 1) {
-                        role_guard();
-                        const f32x16 P = block_start(0);
-                        build_phik(1);
-                        block_finish(0, P);
-                    } else if (c == 2) {
-                        role_guard();
-                        const f32x16 P = block_start(1);
-                        build_phik(2);
-                        block_finish(1, P);
-                    } else {
-                        role_guard();
-                        const f32x16 P = block_start(2);
-                        build_phik(3);
-                        block_finish(2, P);
-                    }
-                } else {
-                    if (c == 0) {
-                        role_guard();
-                        const f32x16 P = block_start(0);
-                        build_den();
-                        build_phik(0);
-                        build_phik(1);
-                        block_finish(0, P);
-                    } else {
-                        role_guard();
-                        const f32x16 P1 = block_start(1);
-                        const f32x16 P2 = block_start(2);
-                        build_phik(2);
-                        block_finish(1, P1);
-                        build_phik(3);
-                        block_finish(2, P2);
-                    }
-                }
-            } else {
+                wg_sync();   // (the producers have staged the next chunk's rows)
+
+                // ---- update: S += phi(K)^T V over all 160 rows, with the normalisation and the store of
+                // the outputs placed between the matrix instructions
+                u32x4 ok[4][NTILE];
 #pragma unroll
                 for (int ts = 0; ts < 4; ++ts)
-                    if (c == (NC == 4 ? ts : ts / 2)) build_phik(ts);
-            }
-            wg_sync();
-            // phase 2: S += phi(K)^T V over all 160 rows; column tile 0 also M' += K'^T K' (the operand of
-            // tile 4 carries k as given in rows 0..15 and the valid flag in row 16)
-            bf16x8 vop[4];
 #pragma unroll
-            for (int ts = 0; ts < 4; ++ts) vop[ts] = load_v(ts);
-            // operands in two halves of ten, the second requested while the first is being consumed
-            u32x4 ok[4][NTILE];
+                    for (int T = 0; T < NTILE; ++T) ok[ts][T] = lds.phik[b][T][ts][lane];
 #pragma unroll
-            for (int ts = 0; ts < 2; ++ts)
+                for (int half = 0; half < 2; ++half) {
 #pragma unroll
-                for (int T = 0; T < NTILE; ++T) ok[ts][T] = lds.phik[T][ts][lane];
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int ts = 2 * half; ts < 2 * half + 2; ++ts)
 #pragma unroll
-            for (int ts = 2; ts < 4; ++ts)
+                        for (int T = 0; T < NTILE; ++T) S[T] = mfma(as_bf16x8(ok[ts][T]), vop[ts], S[T]);
+                    if (MODE == 0) {
+                        const int qt = half;
+                        // normalise and turn the tile through LDS: a lane holds 8-byte pieces of its token's
+                        // row, and stored directly those become 16-byte write requests that stall the memory
+                        // pipeline; from LDS the tile leaves as 64-byte row segments, 16 rows a store.
+                        const float inv = __builtin_amdgcn_rcpf(dn[qt][0] + dn[qt][1] + dn[qt][2]);
+                        uint16_t *yt = &lds.yt[c][0][0];
 #pragma unroll
-                for (int T = 0; T < NTILE; ++T) ok[ts][T] = lds.phik[T][ts][lane];
+                        for (int j = 0; j < 4; ++j) {
+                            f32x4 o;
 #pragma unroll
-            for (int ts = 0; ts < 2; ++ts)
+                            for (int i = 0; i < 4; ++i) o[i] = Y[qt][4 * j + i] * inv;
+                            const bf16x4 hv = __builtin_convertvector(o, bf16x4);
+                            *reinterpret_cast<u32x2 *>(yt + n * YT_LD + 8 * j + 4 * g) = __builtin_bit_cast(u32x2, hv);
+                        }
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        uint16_t *yc = yu + (size_t)tok0 * DV;
+                        u32x4 val[2];
+                        uint32_t yoff[2];
 #pragma unroll
-                for (int T = 0; T < NTILE; ++T) S[T] = mfma(as_bf16x8(ok[ts][T]), vop[ts], S[T]);
-            if (c == 0) {
-                role_guard();
+                        for (int it = 0; it < 2; ++it) {
+                            const int row = 16 * it + (lane >> 2), cc = lane & 3;
+                            val[it] = *reinterpret_cast<const u32x4 *>(yt + row * YT_LD + 8 * cc);
+                            yoff[it] = (uint32_t)(32 * qt + row) * (uint32_t)DV + (uint32_t)(32 * c + 8 * cc);
+                        }
+                        if (tok0 + C <= tok_end) {
 #pragma unroll
-                for (int ts = 0; ts < 2; ++ts) X = mfma(as_bf16x8(ok[ts][NTILE - 1]), as_bf16x8(ok[ts][NTILE - 1]), X);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+                            for (int it = 0; it < 2; ++it) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+                        } else {
 #pragma unroll
-            for (int ts = 2; ts < 4; ++ts)
-#pragma unroll
-                for (int T = 0; T < NTILE; ++T) S[T] = mfma(as_bf16x8(ok[ts][T]), vop[ts], S[T]);
-            if (c == 0) {
-                role_guard();
-#pragma unroll
-                for (int ts = 2; ts < 4; ++ts) X = mfma(as_bf16x8(ok[ts][NTILE - 1]), as_bf16x8(ok[ts][NTILE - 1]), X);
-            }
-            // the readout of the next chunk starts from this state (the readout waves took their copy of
-            // the previous one in phase 1)
-            if (MODE == 0 && more) publish_state();
-            if (more) {
-                wg_sync();
-                stage(tok0 + C);
+                            for (int it = 0; it < 2; ++it)
+                                if (tok0 + 32 * qt + 16 * it + (lane >> 2) < tok_end) *reinterpret_cast<u32x4 *>(yc + yoff[it]) = val[it];
+                        }
+                        // the next tile overwrites this wave's staging only after these reads: LDS
+                        // operations of one wave execute in order
+                    }
+                }
+                wg_sync();   // the next chunk's operands are visible; this chunk's are free
             }
         }
-    }
 
-    // ---- end of segment (the update waves hold the state) -----------------------------------------
-    if (is_u) {
+        // ---- end of segment --------------------------------------------------------------------
         if (MODE != 0) {
             float *e = ws_unit + (size_t)(MODE == 1 ? 1 + seg : 0) * entry_floats(NC) + lane_off;
-            auto put = [&](int slot, const f32x16 &a) {
+#pragma unroll
+            for (int T = 0; T < NTILE; ++T)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     f32x4 o;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o[i] = a[4 * j + i];
-                    store16_coherent(e + (size_t)slot * kSlotFloats + (size_t)j * 256, o);
+                    for (int i = 0; i < 4; ++i) o[i] = S[T][4 * j + i];
+                    store16_coherent(e + (size_t)T * kSlotFloats + (size_t)j * 256, o);
                 }
-            };
-#pragma unroll
-            for (int T = 0; T < NTILE; ++T) put(T, S[T]);
-            if (c == 0) put(5, X);
         } else if (Su && seg == G - 1) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -846,7 +508,375 @@ __device__ __forceinline__ void prefill_body(
                         if (cr.r2 != cr.r1) Su[(size_t)cr.r2 * DV + col] = S[T][r];
                     }
                 }
-                if (c == 0) {
+            }
+        }
+    } else {
+        // =================================== producer waves =========================================
+        const int ptid = tid - NP;     // thread index among the producers
+        f32x16 X;                      // producer 0: the moment tile M' = [k, 1]^T [k, 1]
+        zero16(X);
+        if (MODE == 0 && holds_x) {
+            for (int p = has_init ? 0 : 1; p <= seg; ++p) {
+                const float *e = ws_unit + (size_t)p * entry_floats(NC) + lane_off;
+                f32x4 t[24];
+                load_wave_slots_coherent(e + 1 * kSlotFloats, e + 3 * kSlotFloats, e + 5 * kSlotFloats, t);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) X[r] += t[20 + (r >> 2)][r & 3];
+            }
+        }
+        if (MODE == 2 && holds_x) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
+                float m = 0.f;   // M'[fl][n]
+                if (fl < DP && n < DP) m = zu[canon_pair(fl, n, packed_state).r1] * 1.41421356237309504880f;
+                else if (fl == DP && n < DP) m = zu[1 + n];
+                else if (fl < DP && n == DP) m = zu[1 + fl];
+                else if (fl == DP && n == DP) m = zu[0];
+                X[r] = m;
+            }
+        }
+
+        if (MODE != 2) {
+            // once: the zero row of K^T, and the row sums of a block that does not exist (key tile 1
+            // against query tile 0)
+            if (ptid < C) {
+                lds.kts[DP + 2][ptid] = 0.f;
+                lds.den[0][2][ptid] = 0.f;
+                lds.den[1][2][ptid] = 0.f;
+            }
+
+            // ---- staging: global -> registers -> LDS --------------------------------------------
+            // A chunk of V is one contiguous block of 64 rows x DV columns: 16-byte piece p = ptid + NP j
+            // (j = 0..3) is row p / (DV / 8), columns 8 (p % (DV / 8)) ...  A chunk of K (and of Q) is 128
+            // pieces: piece p holds elements 8 (p % 2) .. of token p / 2.  With four producer waves the
+            // first two stage K and the other two Q; with two every thread stages one piece of each.
+            constexpr int VPR = DV / 8;   // pieces per V row
+            constexpr bool kBoth = NC == 2;
+            const int xp = ptid & 127;
+            const bool is_k = kBoth || ptid < 128;
+            const int x_tok = xp >> 1, x_h = xp & 1;
+            u32x4 raw_k = {0u, 0u, 0u, 0u}, raw_q = {0u, 0u, 0u, 0u};   // four waves: raw_k is the thread's one piece
+            u32x4 raw_v[4];
+            // Loads are unconditional (rows past the end of the segment re-read its last row and are
+            // zeroed when staged): a conditional load would have the compiler pre-zero its destination
+            // registers, and before that write it waits for every memory operation still in flight.
+            auto load_raw = [&](int tok0) {
+                const int tok = min(tok0 + x_tok, tok_end - 1);
+                if (kBoth) {
+                    raw_k = *reinterpret_cast<const u32x4 *>(ku + (size_t)tok * DP + 8 * x_h);
+                    if (MODE == 0) raw_q = *reinterpret_cast<const u32x4 *>(qu + (size_t)tok * DP + 8 * x_h);
+                } else {
+                    const uint16_t *src = (is_k || MODE != 0) ? ku : qu;   // increment pass: q is not needed
+                    raw_k = *reinterpret_cast<const u32x4 *>(src + (size_t)tok * DP + 8 * x_h);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int p = ptid + NP * j;
+                    const int row = min(tok0 + p / VPR, tok_end - 1);
+                    raw_v[j] = *reinterpret_cast<const u32x4 *>(vu + (size_t)row * DV + 8 * (p % VPR));
+                }
+            };
+            auto stage_k = [&](u32x4 raw, bool valid) {
+                const u32x4 zero4 = {0u, 0u, 0u, 0u};
+                if (!valid) raw = zero4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    lds.kts[8 * x_h + 2 * i][x_tok] = bf16lo(raw[i]) * kCK;
+                    lds.kts[8 * x_h + 2 * i + 1][x_tok] = bf16hi(raw[i]) * kCK;
+                }
+                *reinterpret_cast<u32x4 *>(&lds.krow[x_tok][8 * x_h]) = raw;
+                if (x_h == 0) {
+                    lds.kts[DP][x_tok] = valid ? 1.f / kCK : 0.f;
+                    lds.kts[DP + 1][x_tok] = valid ? kCK : 0.f;
+                }
+            };
+            auto stage_q = [&](u32x4 raw) {
+                f32x4 lo, hi;
+                lo[0] = bf16lo(raw[0]) * kCQ; lo[1] = bf16hi(raw[0]) * kCQ;
+                lo[2] = bf16lo(raw[1]) * kCQ; lo[3] = bf16hi(raw[1]) * kCQ;
+                hi[0] = bf16lo(raw[2]) * kCQ; hi[1] = bf16hi(raw[2]) * kCQ;
+                hi[2] = bf16lo(raw[3]) * kCQ; hi[3] = bf16hi(raw[3]) * kCQ;
+                *reinterpret_cast<f32x4 *>(&lds.qs[x_tok][8 * x_h]) = lo;
+                *reinterpret_cast<f32x4 *>(&lds.qs[x_tok][8 * x_h + 4]) = hi;
+                *reinterpret_cast<u32x4 *>(&lds.qrow[x_tok][8 * x_h]) = raw;
+            };
+            auto stage = [&](int tok0, int b) {
+                const bool valid = tok0 + x_tok < tok_end;
+                if (kBoth) {
+                    stage_k(raw_k, valid);
+                    if (MODE == 0) stage_q(raw_q);
+                } else if (is_k) {
+                    stage_k(raw_k, valid);
+                } else if (MODE == 0) {
+                    stage_q(raw_k);
+                }
+                const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int p = ptid + NP * j;
+                    const int row = p / VPR;
+                    *reinterpret_cast<u32x4 *>(&lds.vrow[b][row][8 * (p % VPR)]) = tok0 + row < tok_end ? raw_v[j] : zero4;
+                }
+            };
+
+            // ---- builders of the shared operands (b: the generation they write) ------------------
+            // phi(Q)^T operands of query tile qt, all ten slabs: lane (g, n) is query 32 qt + n; k-slot
+            // (jj, i) of slab s is feature row 16 s + 8 jj + 4 g + i.  xr[j] = c_q q[(4g + j) % 16] is the
+            // lane's query row rotated by 4g, so that the "a side" of k-slot (jj, i) is xr[8 jj + i] and the
+            // "b side" of delta is xr[(8 jj + i + delta) % 16]: every product is between two registers known
+            // at compile time.
+            auto build_phiq = [&](const int b, const int qt) {
+                float xr[16];
+                const float *row = lds.qs[32 * qt + n];
+                f32x4 t[4];
+#pragma unroll
+                for (int m = 0; m < 4; ++m) t[m] = *reinterpret_cast<const f32x4 *>(row + ((4 * g + 4 * m) & 15));
+                // slab 8: the linear rows; the operand is q itself, as given
+                const uint16_t *p = &lds.qrow[32 * qt + n][4 * g];
+                const u32x2 ra = *reinterpret_cast<const u32x2 *>(p);
+                const u32x2 rb = *reinterpret_cast<const u32x2 *>(p + 8);
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xr[4 * m + i] = t[m][i];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {   // pair slabs: delta = s
+                    float pr[8];
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int a = 8 * jj + i;
+                            const float av = s == 0 ? xr[a] * 0.5f : xr[a];   // delta = 0: x_a^2 / sqrt(2)
+                            pr[4 * jj + i] = av * xr[(a + s) & 15];
+                        }
+                    lds.phiq[b][qt][s][lane] = as_u32x4(pack8(pr));
+                }
+                {
+                    u32x4 o; o[0] = ra[0]; o[1] = ra[1]; o[2] = rb[0]; o[3] = rb[1];
+                    lds.phiq[b][qt][8][lane] = o;
+                }
+                {   // slab 9: the constant row (k-slot 0 of g = 0 = row 16 of the tile), padding, and the
+                    // delta = 8 rows (k-slots 4 + i = row 24 + 4g + i: sqrt(2) q_a q_(a+8), a = 4g + i)
+                    float pr[8];
+                    pr[0] = g == 0 ? 1.f : 0.f; pr[1] = 0.f; pr[2] = 0.f; pr[3] = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[4 + i] = xr[i] * xr[8 + i];
+                    lds.phiq[b][qt][9][lane] = as_u32x4(pack8(pr));
+                }
+            };
+            // phi(K)^T operands of token slab ts, all five state tiles: lane (g, n) is feature row n of a
+            // tile, its k-slots are the tokens 16 ts + 4 g + {0..3, 8..11}.  Every row is a product of two
+            // rows of the staged K^T: pair rows k_a k_b / sqrt(2); linear rows (c_k k_a)(valid / c_k); the
+            // constant row (valid c_k)(valid / c_k); padding rows 0 * 0.  (c_k k_a / c_k differs from k_a by
+            // fp32 rounding only, far below half a bf16 step, so the conversion returns k_a exactly.)  The
+            // "a" row of the four pair tiles is the same (a = n % 16), so a slab costs 14 LDS loads, all
+            // issued before the products.
+            const float *kt_a03 = &lds.kts[n & 15][4 * g];
+            const float *kt_a4 = &lds.kts[n < DP ? n : (n == DP ? DP + 1 : (n < 24 ? DP + 2 : n - 24))][4 * g];
+            const float *kt_b[NTILE];
+#pragma unroll
+            for (int T = 0; T < 4; ++T) kt_b[T] = &lds.kts[((n & 15) + 2 * T + (n >> 4)) & 15][4 * g];
+            kt_b[4] = &lds.kts[n < DP ? DP : (n == DP ? DP : (n < 24 ? DP + 2 : n - 16))][4 * g];
+            auto build_phik = [&](const int b, const int ts) {
+                f32x4 a03[2], a4[2], kb[NTILE][2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    a03[h] = *reinterpret_cast<const f32x4 *>(kt_a03 + 16 * ts + 8 * h);
+                    a4[h] = *reinterpret_cast<const f32x4 *>(kt_a4 + 16 * ts + 8 * h);
+#pragma unroll
+                    for (int T = 0; T < NTILE; ++T) kb[T][h] = *reinterpret_cast<const f32x4 *>(kt_b[T] + 16 * ts + 8 * h);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int T = 0; T < NTILE; ++T) {
+                    float pr[8];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) pr[4 * h + i] = (T < 4 ? a03[h][i] : a4[h][i]) * kb[T][h][i];
+                    lds.phik[b][T][ts][lane] = as_u32x4(pack8(pr));
+                }
+            };
+            // Intra-chunk block bb: 0 = key tile 0 against query tile 0, 1 = key tile 0 against query tile 1,
+            // 2 = key tile 1 against query tile 1 (0 and 2 are cut by the diagonal).
+            // P^T = mask(1 + A^T + A^T^2 / 2), A^T = K Q^T: lane (g, n) is query 32 qt + n, register r is key
+            // 32 kt + 8 (r / 4) + 4 g + r % 4.  Keys past the end of the segment come after every valid query
+            // and fall to the causal mask.  Split in two so that a wave can do other work under the product.
+            auto block_start = [&](const int bb) {
+                const int kt = bb == 2 ? 1 : 0, qt = bb == 0 ? 0 : 1;
+                f32x16 P;
+                zero16(P);
+                const u32x4 kop = *reinterpret_cast<const u32x4 *>(&lds.krow[32 * kt + n][8 * g]);
+                const u32x4 qop = *reinterpret_cast<const u32x4 *>(&lds.qrow[32 * qt + n][8 * g]);
+                return mfma(as_bf16x8(kop), as_bf16x8(qop), P);
+            };
+            auto block_finish = [&](const int b, const int bb, f32x16 P) {
+                const int kt = bb == 2 ? 1 : 0, qt = bb == 0 ? 0 : 1;
+                const bool diag = bb != 1;
+                float dsum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = P[r];
+                    float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
+                    const int key = 8 * (r >> 2) + 4 * g + (r & 3);
+                    pv = (!diag || key <= n) ? pv : 0.f;
+                    P[r] = pv;
+                    dsum += pv;
+                }
+                lds.pop[b][bb][0][lane] = as_u32x4(pack8_acc(P, 0));
+                lds.pop[b][bb][1][lane] = as_u32x4(pack8_acc(P, 1));
+                dsum += __shfl_xor(dsum, 32, 64);
+                if (g == 0) lds.den[b][1 + kt][32 * qt + n] = dsum;
+            };
+            // Inter-chunk denominators of both query tiles from the moments: count + q.z1 + q^T M q / 2.
+            auto build_den = [&](const int b) {
+                f32x4 a0[2], a1[2];
+                u32x2 ra[2], rb[2];
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    const float *row = lds.qs[32 * qt + n];
+                    a0[qt] = *reinterpret_cast<const f32x4 *>(row + 4 * g);
+                    a1[qt] = *reinterpret_cast<const f32x4 *>(row + 8 + 4 * g);
+                    const uint16_t *p = &lds.qrow[32 * qt + n][4 * g];
+                    ra[qt] = *reinterpret_cast<const u32x2 *>(p);
+                    rb[qt] = *reinterpret_cast<const u32x2 *>(p + 8);
+                }
+                float mres[8];
+                const bf16x8 mhi = pack8_acc(X, 0);
+                {
+                    const u32x4 hb = __builtin_bit_cast(u32x4, mhi);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        mres[2 * i] = X[2 * i] - bf16lo(hb[i]);
+                        mres[2 * i + 1] = X[2 * i + 1] - bf16hi(hb[i]);
+                    }
+                }
+                const bf16x8 mlo = pack8(mres);
+                const float cnt_prev = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(X[8]), 16));
+                f32x16 T[2];
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    u32x4 o; o[0] = ra[qt][0]; o[1] = ra[qt][1]; o[2] = rb[qt][0]; o[3] = rb[qt][1];
+                    zero16(T[qt]);
+                    T[qt] = mfma(mhi, as_bf16x8(o), T[qt]);
+                    T[qt] = mfma(mlo, as_bf16x8(o), T[qt]);
+                }
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    float d2 = 0.f;
+                    // row of T[e] = 8 (e / 4) + 4 g + e % 4
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) d2 = fmaf(T[qt][e], a0[qt][e], d2);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) d2 = fmaf(T[qt][4 + e], a1[qt][e], d2);
+                    const float d = fmaf(d2, kHalfInvCQ, T[qt][8]);   // T[8]: row 16 = q.z1 on g = 0, zero on g = 1
+                    const float tot = d + __shfl_xor(d, 32, 64) + cnt_prev;
+                    if (g == 0) lds.den[b][0][32 * qt + n] = tot;
+                }
+            };
+            // All operands of one chunk into generation b.  Roles (vector instructions, roughly even):
+            // four producer waves: 0 = denominators + phi(Q) of query tile 0; 1 = block 0 + phi(Q) of query
+            // tile 1; 2 = block 1 + phi(K) of token slabs 0, 1; 3 = block 2 + phi(K) of token slabs 2, 3.
+            // Two: 0 = block 0, denominators, phi(Q); 1 = blocks 1 and 2, phi(K).  Increment pass: phi(K).
+            auto build = [&](const int b) {
+                if (MODE == 0) {
+                    if (NC == 4) {
+                        if (c == 0) {
+                            role_guard();
+                            build_den(b);
+                            build_phiq(b, 0);
+                        } else if (c == 1) {
+                            role_guard();
+                            const f32x16 P = block_start(0);
+                            build_phiq(b, 1);
+                            block_finish(b, 0, P);
+                        } else if (c == 2) {
+                            role_guard();
+                            const f32x16 P = block_start(1);
+                            build_phik(b, 0);
+                            build_phik(b, 1);
+                            block_finish(b, 1, P);
+                        } else {
+                            role_guard();
+                            const f32x16 P = block_start(2);
+                            build_phik(b, 2);
+                            build_phik(b, 3);
+                            block_finish(b, 2, P);
+                        }
+                    } else {
+                        if (c == 0) {
+                            role_guard();
+                            const f32x16 P = block_start(0);
+                            build_den(b);
+                            build_phiq(b, 0);
+                            block_finish(b, 0, P);
+                            build_phiq(b, 1);
+                        } else {
+                            role_guard();
+                            const f32x16 P1 = block_start(1);
+                            const f32x16 P2 = block_start(2);
+                            build_phik(b, 0);
+                            build_phik(b, 1);
+                            block_finish(b, 1, P1);
+                            build_phik(b, 2);
+                            build_phik(b, 3);
+                            block_finish(b, 2, P2);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int ts = 0; ts < 4; ++ts)
+                        if (c == (NC == 4 ? ts : ts / 2)) build_phik(b, ts);
+                }
+            };
+
+            // ---- the producers' loop: one chunk ahead of the consumers -----------------------------
+            load_raw(tok_begin);
+            stage(tok_begin, 0);
+            if (n_chunks > 1) load_raw(tok_begin + C);
+            wg_sync();   // the first chunk's rows are staged
+            build(0);
+            wg_sync();   // the first chunk's operands are visible
+            for (int t = 0; t < n_chunks; ++t) {
+                const int b = t & 1;
+                const int tok_next = tok_begin + C * (t + 1);
+                const bool has_next = t + 1 < n_chunks;
+                if (has_next) stage(tok_next, b ^ 1);
+                if (t + 2 < n_chunks) load_raw(tok_next + C);   // two chunks ahead of the consumers
+                wg_sync();   // the next chunk's rows are staged
+                if (holds_x) {
+                    // M' += K'^T K' of the chunk the consumers are working on (the operand of tile 4 carries k
+                    // as given in rows 0..15 and the valid flag in row 16); the denominators of the next chunk
+                    // need it
+                    role_guard();
+#pragma unroll
+                    for (int ts = 0; ts < 4; ++ts) {
+                        const bf16x8 e = as_bf16x8(lds.phik[b][NTILE - 1][ts][lane]);
+                        X = mfma(e, e, X);
+                    }
+                }
+                if (has_next) build(b ^ 1);
+                wg_sync();   // the next chunk's operands are visible
+            }
+        }
+
+        // ---- end of segment: the moments ----------------------------------------------------------
+        if (holds_x) {
+            if (MODE != 0) {
+                float *e = ws_unit + (size_t)(MODE == 1 ? 1 + seg : 0) * entry_floats(NC) + lane_off;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = X[4 * j + i];
+                    store16_coherent(e + (size_t)5 * kSlotFloats + (size_t)j * 256, o);
+                }
+            } else if (Su && seg == G - 1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int fl = 8 * (r >> 2) + 4 * g + (r & 3);
                     const float m = X[r];
                     if (fl < DP && n < DP) {
                         if (!packed_state || fl <= n) zu[canon_pair(fl, n, packed_state).r1] = m * kRsqrt2;
@@ -872,7 +902,7 @@ __device__ __forceinline__ void prefill_body(
 // (all segment-0 workgroups first: they depend on nothing and fill the slots the increment
 // workgroups leave free).
 template <int NC>
-__global__ __launch_bounds__(128 * NC, 2) void prefill_mfma_kernel(
+__global__ __launch_bounds__(128 * NC, NC == 4 ? 2 : 1) void prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws,
     unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls, unsigned epoch, int N,
@@ -893,7 +923,7 @@ __global__ __launch_bounds__(128 * NC, 2) void prefill_mfma_kernel(
 
 // The caller's initial state into entry 0 of every unit.
 template <int NC>
-__global__ __launch_bounds__(128 * NC, 2) void prefill_mfma_import_kernel(
+__global__ __launch_bounds__(128 * NC, 1) void prefill_mfma_import_kernel(
     float *__restrict__ state, int has_init, float *__restrict__ ws, int N, SegTable segs, int G)
 {
     __shared__ __align__(16) Lds<NC> lds;
