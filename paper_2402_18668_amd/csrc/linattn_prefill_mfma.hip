@@ -55,6 +55,7 @@
 #include "common.h"
 
 #include <atomic>
+#include <type_traits>
 
 namespace based {
 
@@ -110,6 +111,7 @@ struct Lds {
     u32x4 pop[2][3][2][64];             // masked intra-chunk blocks as operands: [parity][block][slab][lane]
     float den[2][3][C];                 // per query: inter-chunk part; row sums of the blocks of key tile 0, 1
     uint16_t yt[NC][32][YT_LD];         // per consumer wave: a finished output tile on its way out
+    unsigned staged;                    // producer waves that have staged their part, summed over the chunks so far
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
@@ -149,6 +151,23 @@ __device__ __forceinline__ void zero16(f32x16 &a)
 __device__ __forceinline__ void wg_sync()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The rows of a chunk are staged by the producer waves only, and read by every wave that builds an
+// operand from them.  That hand-over does not stop the whole workgroup: a producer wave that has finished
+// its LDS writes adds one to a counter in LDS, and whoever needs the rows waits until the counter has
+// reached the number of producer waves times the number of chunks staged so far.  (LDS operations of a
+// wave complete in order, and the add is issued after the wave's own writes have completed.)
+__device__ __forceinline__ void signal_staged(unsigned *counter, int lane)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void wait_staged(unsigned *counter, unsigned target)
+{
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
+        __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");
 }
 
 // MFMA instructions ignore the EXEC mask.  A branch on the wave's role is uniform across the wave
@@ -269,7 +288,8 @@ __device__ __forceinline__ void prefill_body(
     float *__restrict__ ws, unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls,
     unsigned epoch, int N, const SegTable &segs, int G, int seg, int u)
 {
-    constexpr int NP = 64 * NC;       // producer threads
+    constexpr int NPW = 4;            // producer waves
+    constexpr int NP = 64 * NPW;      // producer threads
     constexpr int DV = 32 * NC;       // d_v
     constexpr int VR_LD = DV + 16;
     // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
@@ -319,6 +339,45 @@ __device__ __forceinline__ void prefill_body(
         __syncthreads();
     }
 
+    // Intra-chunk block bb of the chunk whose rows are staged, into generation b: 0 = key tile 0 against
+    // query tile 0, 1 = key tile 0 against query tile 1, 2 = key tile 1 against query tile 1 (0 and 2 are
+    // cut by the diagonal).  P^T = mask(1 + A^T + A^T^2 / 2), A^T = K Q^T: lane (g, n) is query 32 qt + n,
+    // register r is key 32 kt + 8 (r / 4) + 4 g + r % 4.  Keys past the end of the segment come after every
+    // valid query and fall to the causal mask.  Built by the consumer waves (one block each), which wait
+    // for the producers otherwise.
+    auto build_block = [&](const int b, const int bb) {
+        const int kt = bb == 2 ? 1 : 0, qt = bb == 0 ? 0 : 1;
+        const bool diag = bb != 1;
+        f32x16 P;
+        zero16(P);
+        const u32x4 kop = *reinterpret_cast<const u32x4 *>(&lds.krow[32 * kt + n][8 * g]);
+        const u32x4 qop = *reinterpret_cast<const u32x4 *>(&lds.qrow[32 * qt + n][8 * g]);
+        P = mfma(as_bf16x8(kop), as_bf16x8(qop), P);
+        float dsum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float x = P[r];
+            float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
+            const int key = 8 * (r >> 2) + 4 * g + (r & 3);
+            pv = (!diag || key <= n) ? pv : 0.f;
+            P[r] = pv;
+            dsum += pv;
+        }
+        lds.pop[b][bb][0][lane] = as_u32x4(pack8_acc(P, 0));
+        lds.pop[b][bb][1][lane] = as_u32x4(pack8_acc(P, 1));
+        dsum += __shfl_xor(dsum, 32, 64);
+        if (g == 0) lds.den[b][1 + kt][32 * qt + n] = dsum;
+    };
+    // which blocks a consumer builds: four consumers: c = 0..2 one each; two: 0 -> blocks 0 and 1, 1 -> block 2
+    auto build_my_blocks = [&](const int b) {
+        if (NC == 4) {
+#pragma unroll
+            for (int bb = 0; bb < 3; ++bb)
+                if (c == bb) build_block(b, bb);
+        }
+    };
+
+    if (MODE != 2 && tid == 0) lds.staged = 0u;   // ordered before its first use by the prologue's barriers
     if (!is_p) {
         // =================================== consumer waves =========================================
         f32x16 S[NTILE];       // the five state tiles of this wave's 32 columns
@@ -369,7 +428,8 @@ __device__ __forceinline__ void prefill_body(
                 return __builtin_bit_cast(bf16x8, o);
             };
 
-            wg_sync();   // (the producers stage the first chunk)
+            wg_sync();   // the producers have staged the first chunk
+            if (MODE == 0) build_my_blocks(0);
             wg_sync();   // the operands of the first chunk are visible
             for (int t = 0; t < n_chunks; ++t) {
                 const int b = t & 1;
@@ -427,7 +487,10 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
                     for (int sl = 0; sl < 2; ++sl) Y[1] = mfma(vop[2 + sl], as_bf16x8(op[2][sl]), Y[1]);
                 }
-                wg_sync();   // (the producers have staged the next chunk's rows)
+                if (MODE == 0 && NC == 4 && t + 1 < n_chunks) {
+                    wait_staged(&lds.staged, (unsigned)(NPW * (t + 1)));   // the next chunk's rows are staged
+                    build_my_blocks(b ^ 1);
+                }
 
                 // ---- update: S += phi(K)^T V over all 160 rows, with the normalisation and the store of
                 // the outputs placed between the matrix instructions
@@ -512,7 +575,7 @@ __device__ __forceinline__ void prefill_body(
         }
     } else {
         // =================================== producer waves =========================================
-        const int ptid = tid - NP;     // thread index among the producers
+        const int ptid = tid - 64 * NC;   // thread index among the producers
         f32x16 X;                      // producer 0: the moment tile M' = [k, 1]^T [k, 1]
         zero16(X);
         if (MODE == 0 && holds_x) {
@@ -540,8 +603,10 @@ __device__ __forceinline__ void prefill_body(
         if (MODE != 2) {
             // once: the zero row of K^T, and the row sums of a block that does not exist (key tile 1
             // against query tile 0)
-            if (ptid < C) {
-                lds.kts[DP + 2][ptid] = 0.f;
+            // (only the first 32 queries of den[.][2]: the other half belongs to block 2, whose builder does
+            // not wait for this wave)
+            if (ptid < C) lds.kts[DP + 2][ptid] = 0.f;
+            if (ptid < 32) {
                 lds.den[0][2][ptid] = 0.f;
                 lds.den[1][2][ptid] = 0.f;
             }
@@ -552,12 +617,13 @@ __device__ __forceinline__ void prefill_body(
             // pieces: piece p holds elements 8 (p % 2) .. of token p / 2.  With four producer waves the
             // first two stage K and the other two Q; with two every thread stages one piece of each.
             constexpr int VPR = DV / 8;   // pieces per V row
-            constexpr bool kBoth = NC == 2;
+            constexpr bool kBoth = false;
+            constexpr int NVP = VPR * C / NP;   // V pieces per producer thread
             const int xp = ptid & 127;
             const bool is_k = kBoth || ptid < 128;
             const int x_tok = xp >> 1, x_h = xp & 1;
             u32x4 raw_k = {0u, 0u, 0u, 0u}, raw_q = {0u, 0u, 0u, 0u};   // four waves: raw_k is the thread's one piece
-            u32x4 raw_v[4];
+            u32x4 raw_v[NVP];
             // Loads are unconditional (rows past the end of the segment re-read its last row and are
             // zeroed when staged): a conditional load would have the compiler pre-zero its destination
             // registers, and before that write it waits for every memory operation still in flight.
@@ -571,7 +637,7 @@ __device__ __forceinline__ void prefill_body(
                     raw_k = *reinterpret_cast<const u32x4 *>(src + (size_t)tok * DP + 8 * x_h);
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < NVP; ++j) {
                     const int p = ptid + NP * j;
                     const int row = min(tok0 + p / VPR, tok_end - 1);
                     raw_v[j] = *reinterpret_cast<const u32x4 *>(vu + (size_t)row * DV + 8 * (p % VPR));
@@ -613,7 +679,7 @@ __device__ __forceinline__ void prefill_body(
                 }
                 const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < NVP; ++j) {
                     const int p = ptid + NP * j;
                     const int row = p / VPR;
                     *reinterpret_cast<u32x4 *>(&lds.vrow[b][row][8 * (p % VPR)]) = tok0 + row < tok_end ? raw_v[j] : zero4;
@@ -679,57 +745,36 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
             for (int T = 0; T < 4; ++T) kt_b[T] = &lds.kts[((n & 15) + 2 * T + (n >> 4)) & 15][4 * g];
             kt_b[4] = &lds.kts[n < DP ? DP : (n == DP ? DP : (n < 24 ? DP + 2 : n - 16))][4 * g];
-            auto build_phik = [&](const int b, const int ts) {
-                f32x4 a03[2], a4[2], kb[NTILE][2];
+            // (NTS token slabs at a time: all their LDS loads go out before the first product)
+            auto build_phik_n = [&](const int b, const int ts0, auto nts_tag) {
+                constexpr int NTS = decltype(nts_tag)::value;
+                f32x4 a03[NTS][2], a4[NTS][2], kb[NTS][NTILE][2];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    a03[h] = *reinterpret_cast<const f32x4 *>(kt_a03 + 16 * ts + 8 * h);
-                    a4[h] = *reinterpret_cast<const f32x4 *>(kt_a4 + 16 * ts + 8 * h);
+                for (int s2 = 0; s2 < NTS; ++s2)
 #pragma unroll
-                    for (int T = 0; T < NTILE; ++T) kb[T][h] = *reinterpret_cast<const f32x4 *>(kt_b[T] + 16 * ts + 8 * h);
-                }
+                    for (int h = 0; h < 2; ++h) {
+                        const int off = 16 * (ts0 + s2) + 8 * h;
+                        a03[s2][h] = *reinterpret_cast<const f32x4 *>(kt_a03 + off);
+                        a4[s2][h] = *reinterpret_cast<const f32x4 *>(kt_a4 + off);
+#pragma unroll
+                        for (int T = 0; T < NTILE; ++T) kb[s2][T][h] = *reinterpret_cast<const f32x4 *>(kt_b[T] + off);
+                    }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int T = 0; T < NTILE; ++T) {
-                    float pr[8];
+                for (int s2 = 0; s2 < NTS; ++s2)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
+                    for (int T = 0; T < NTILE; ++T) {
+                        float pr[8];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) pr[4 * h + i] = (T < 4 ? a03[h][i] : a4[h][i]) * kb[T][h][i];
-                    lds.phik[b][T][ts][lane] = as_u32x4(pack8(pr));
-                }
-            };
-            // Intra-chunk block bb: 0 = key tile 0 against query tile 0, 1 = key tile 0 against query tile 1,
-            // 2 = key tile 1 against query tile 1 (0 and 2 are cut by the diagonal).
-            // P^T = mask(1 + A^T + A^T^2 / 2), A^T = K Q^T: lane (g, n) is query 32 qt + n, register r is key
-            // 32 kt + 8 (r / 4) + 4 g + r % 4.  Keys past the end of the segment come after every valid query
-            // and fall to the causal mask.  Split in two so that a wave can do other work under the product.
-            auto block_start = [&](const int bb) {
-                const int kt = bb == 2 ? 1 : 0, qt = bb == 0 ? 0 : 1;
-                f32x16 P;
-                zero16(P);
-                const u32x4 kop = *reinterpret_cast<const u32x4 *>(&lds.krow[32 * kt + n][8 * g]);
-                const u32x4 qop = *reinterpret_cast<const u32x4 *>(&lds.qrow[32 * qt + n][8 * g]);
-                return mfma(as_bf16x8(kop), as_bf16x8(qop), P);
-            };
-            auto block_finish = [&](const int b, const int bb, f32x16 P) {
-                const int kt = bb == 2 ? 1 : 0, qt = bb == 0 ? 0 : 1;
-                const bool diag = bb != 1;
-                float dsum = 0.f;
+                        for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float x = P[r];
-                    float pv = fmaf(x, fmaf(x, 0.5f, 1.f), 1.f);
-                    const int key = 8 * (r >> 2) + 4 * g + (r & 3);
-                    pv = (!diag || key <= n) ? pv : 0.f;
-                    P[r] = pv;
-                    dsum += pv;
-                }
-                lds.pop[b][bb][0][lane] = as_u32x4(pack8_acc(P, 0));
-                lds.pop[b][bb][1][lane] = as_u32x4(pack8_acc(P, 1));
-                dsum += __shfl_xor(dsum, 32, 64);
-                if (g == 0) lds.den[b][1 + kt][32 * qt + n] = dsum;
+                            for (int i = 0; i < 4; ++i)
+                                pr[4 * h + i] = (T < 4 ? a03[s2][h][i] : a4[s2][h][i]) * kb[s2][T][h][i];
+                        lds.phik[b][T][ts0 + s2][lane] = as_u32x4(pack8(pr));
+                    }
             };
+            auto build_phik = [&](const int b, const int ts) { build_phik_n(b, ts, std::integral_constant<int, 1>{}); };
+            auto build_phik2 = [&](const int b, const int ts) { build_phik_n(b, ts, std::integral_constant<int, 2>{}); };
             // Inter-chunk denominators of both query tiles from the moments: count + q.z1 + q^T M q / 2.
             auto build_den = [&](const int b) {
                 f32x4 a0[2], a1[2];
@@ -776,59 +821,30 @@ __device__ __forceinline__ void prefill_body(
                     if (g == 0) lds.den[b][0][32 * qt + n] = tot;
                 }
             };
-            // All operands of one chunk into generation b.  Roles (vector instructions, roughly even):
-            // four producer waves: 0 = denominators + phi(Q) of query tile 0; 1 = block 0 + phi(Q) of query
-            // tile 1; 2 = block 1 + phi(K) of token slabs 0, 1; 3 = block 2 + phi(K) of token slabs 2, 3.
-            // Two: 0 = block 0, denominators, phi(Q); 1 = blocks 1 and 2, phi(K).  Increment pass: phi(K).
+            // The producers' share of the operands of one chunk, into generation b (the intra-chunk blocks
+            // are built by the consumers, which have the time).  Four producer waves: 0 = denominators; 1 =
+            // phi(Q) of both query tiles; 2 = phi(K) of token slabs 0, 1; 3 = phi(K) of token slabs 2, 3.
+            // Two: 0 = denominators, phi(Q); 1 = phi(K).  Increment pass: phi(K) only.
             auto build = [&](const int b) {
                 if (MODE == 0) {
-                    if (NC == 4) {
-                        if (c == 0) {
-                            role_guard();
-                            build_den(b);
-                            build_phiq(b, 0);
-                        } else if (c == 1) {
-                            role_guard();
-                            const f32x16 P = block_start(0);
-                            build_phiq(b, 1);
-                            block_finish(b, 0, P);
-                        } else if (c == 2) {
-                            role_guard();
-                            const f32x16 P = block_start(1);
-                            build_phik(b, 0);
-                            build_phik(b, 1);
-                            block_finish(b, 1, P);
-                        } else {
-                            role_guard();
-                            const f32x16 P = block_start(2);
-                            build_phik(b, 2);
-                            build_phik(b, 3);
-                            block_finish(b, 2, P);
-                        }
+                    if (c == 0) {
+                        role_guard();
+                        build_den(b);
+                        build_phiq(b, 0);
+                    } else if (c == 1) {
+                        build_phiq(b, 1);
+                        if (NC == 2) build_block(b, 1);
+                    } else if (c == 2) {
+                        build_phik2(b, 0);
+                        if (NC == 2) build_block(b, 0);
                     } else {
-                        if (c == 0) {
-                            role_guard();
-                            const f32x16 P = block_start(0);
-                            build_den(b);
-                            build_phiq(b, 0);
-                            block_finish(b, 0, P);
-                            build_phiq(b, 1);
-                        } else {
-                            role_guard();
-                            const f32x16 P1 = block_start(1);
-                            const f32x16 P2 = block_start(2);
-                            build_phik(b, 0);
-                            build_phik(b, 1);
-                            block_finish(b, 1, P1);
-                            build_phik(b, 2);
-                            build_phik(b, 3);
-                            block_finish(b, 2, P2);
-                        }
+                        build_phik2(b, 2);
+                        if (NC == 2) build_block(b, 2);
                     }
                 } else {
 #pragma unroll
                     for (int ts = 0; ts < 4; ++ts)
-                        if (c == (NC == 4 ? ts : ts / 2)) build_phik(b, ts);
+                        if (c == ts) build_phik(b, ts);
                 }
             };
 
@@ -843,9 +859,12 @@ __device__ __forceinline__ void prefill_body(
                 const int b = t & 1;
                 const int tok_next = tok_begin + C * (t + 1);
                 const bool has_next = t + 1 < n_chunks;
-                if (has_next) stage(tok_next, b ^ 1);
+                if (has_next) {
+                    stage(tok_next, b ^ 1);
+                    signal_staged(&lds.staged, lane);
+                }
                 if (t + 2 < n_chunks) load_raw(tok_next + C);   // two chunks ahead of the consumers
-                wg_sync();   // the next chunk's rows are staged
+                if (has_next) wait_staged(&lds.staged, (unsigned)(NPW * (t + 1)));   // all of the next chunk's rows
                 if (holds_x) {
                     // M' += K'^T K' of the chunk the consumers are working on (the operand of tile 4 carries k
                     // as given in rows 0..15 and the valid flag in row 16); the denominators of the next chunk
@@ -902,7 +921,7 @@ __device__ __forceinline__ void prefill_body(
 // (all segment-0 workgroups first: they depend on nothing and fill the slots the increment
 // workgroups leave free).
 template <int NC>
-__global__ __launch_bounds__(128 * NC, NC == 4 ? 2 : 1) void prefill_mfma_kernel(
+__global__ __launch_bounds__(64 * (NC + 4), 2) void prefill_mfma_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     uint16_t *__restrict__ y, float *__restrict__ state, int has_init, float *__restrict__ ws,
     unsigned *__restrict__ flags, unsigned *__restrict__ status, int max_polls, unsigned epoch, int N,
@@ -923,7 +942,7 @@ __global__ __launch_bounds__(128 * NC, NC == 4 ? 2 : 1) void prefill_mfma_kernel
 
 // The caller's initial state into entry 0 of every unit.
 template <int NC>
-__global__ __launch_bounds__(128 * NC, 1) void prefill_mfma_import_kernel(
+__global__ __launch_bounds__(64 * (NC + 4), 2) void prefill_mfma_import_kernel(
     float *__restrict__ state, int has_init, float *__restrict__ ws, int N, SegTable segs, int G)
 {
     __shared__ __align__(16) Lds<NC> lds;
@@ -1004,7 +1023,7 @@ hipError_t launch(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint1
     unsigned *flags = reinterpret_cast<unsigned *>((char *)workspace + ws_entry_bytes(U, N, dv));
     hipError_t e;
     if (flags_word & 1) {
-        hipLaunchKernelGGL((prefill_mfma_import_kernel<NC>), dim3((unsigned)U), dim3(128 * NC), 0, s, state,
+        hipLaunchKernelGGL((prefill_mfma_import_kernel<NC>), dim3((unsigned)U), dim3(64 * (NC + 4)), 0, s, state,
                            flags_word, ws, N, segs, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -1012,7 +1031,7 @@ hipError_t launch(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint1
     // that has never been used hold whatever was in that memory.
     static std::atomic<unsigned> calls{0};
     const unsigned epoch = 0x5EED0000u + calls.fetch_add(1u) + 1u;
-    hipLaunchKernelGGL((prefill_mfma_kernel<NC>), dim3((unsigned)(U * (2 * G - 1))), dim3(128 * NC), 0, s, q, k, v,
+    hipLaunchKernelGGL((prefill_mfma_kernel<NC>), dim3((unsigned)(U * (2 * G - 1))), dim3(64 * (NC + 4)), 0, s, q, k, v,
                        y, state, flags_word, ws, flags, status, g_flag_poll_limit.load(), epoch, N, segs, G, U);
     return hipGetLastError();
 }
