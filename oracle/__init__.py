@@ -155,6 +155,21 @@ def linattn_recurrent(q, k, v, S=None, z=None):
     return y, S, z
 
 
+def linattn_numerator(q, k, v, S=None) -> np.ndarray:
+    """The numerator of Eq. 2 alone, every row (what Alg. 1 and Alg. 2 output as printed, and what the
+    captions of the kernel timing figures say is timed):
+    ``y_i = sum_{j<=i} (1 + q_i.k_j + (q_i.k_j)^2 / 2) v_j``, plus ``phi(q_i) S0`` for an initial
+    KV-state ``S`` ``[U, D, d_v]``.  The definition written out with library matrix products."""
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64); v = np.asarray(v, dtype=np.float64)
+    _shapes(q, k, v)
+    A = np.einsum("uia,uja->uij", q, k)
+    W = np.tril(1.0 + A + 0.5 * A * A)
+    y = np.einsum("uij,ujc->uic", W, v)
+    if S is not None:
+        y = y + np.einsum("uif,ufc->uic", feature_map(q), np.asarray(S, dtype=np.float64))
+    return y
+
+
 def swa(q, k, v, w: int, scale: float) -> np.ndarray:
     """Causal sliding-window softmax attention (Sec. 3.2 on Eq. 1), every row."""
     q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)

@@ -224,6 +224,66 @@ def test_recurrent_continuation_equals_one_pass():
         assert np.allclose(yt[:, 0], yq[:, t], rtol=1e-10, atol=1e-12)
 
 
+def test_numerator_only_pins():
+    """The undivided output: against a pure-Python sum, against numerator = y * denominator with both
+    factors from other routes, against the state route phi(q_i) S_i, and on closed forms."""
+    g = rng(77)
+    U, N, dp, dv = 2, 23, 3, 4
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp)); v = g.standard_normal((U, N, dv))
+    got = oracle.linattn_numerator(q, k, v)
+    ql, kl, vl = q.tolist(), k.tolist(), v.tolist()
+    den = np.zeros((U, N))
+    for u in range(U):
+        for i in range(N):
+            num = [0.0] * dv
+            for j in range(i + 1):
+                x = sum(ql[u][i][a] * kl[u][j][a] for a in range(dp))
+                wgt = 1.0 + x + x * x / 2.0
+                den[u, i] += wgt
+                for c in range(dv):
+                    num[c] += wgt * vl[u][j][c]
+            assert np.allclose(got[u, i], num, rtol=1e-12, atol=1e-13)
+    # Eq. 2 is numerator / denominator: the C oracle's normalised rows times the denominators above
+    assert np.allclose(got, oracle.linattn_quadratic(q, k, v) * den[:, :, None], rtol=1e-11, atol=1e-12)
+    # Eq. 3: the same row from the running KV-state (the C oracle's state of the prefix, token included)
+    for i in (0, 5, N - 1):
+        S, _ = oracle.linattn_state(k[:, :i + 1], v[:, :i + 1])
+        assert np.allclose(got[:, i], np.einsum("uf,ufc->uc", np_phi(q[:, i]), S), rtol=1e-11, atol=1e-12)
+    # continuation from a state: rows N1.. of the whole sequence
+    N1 = 9
+    S1, _ = oracle.linattn_state(k[:, :N1], v[:, :N1])
+    assert np.allclose(oracle.linattn_numerator(q[:, N1:], k[:, N1:], v[:, N1:], S1), got[:, N1:], rtol=1e-11, atol=1e-12)
+    # q = 0: every weight is 1, the numerator is the running sum of v; first row is v_0 (1 + x + x^2/2 at j = i = 0)
+    assert np.allclose(oracle.linattn_numerator(np.zeros_like(q), k, v), np.cumsum(v, axis=1), rtol=1e-13, atol=1e-13)
+    x0 = np.einsum("ua,ua->u", q[:, 0], k[:, 0])
+    assert np.allclose(got[:, 0], (1 + x0 + x0 * x0 / 2)[:, None] * v[:, 0], rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("dp", [8, 24])
+def test_ablation_feature_dimensions(dp):
+    """d' = 8 and 24 (the feature-dimension rows of the ablation table): the sizes the table prints in
+    parentheses (45 and 325, the count of distinct monomials of degree <= 2), D = 1 + d' + d'^2, and the
+    three views agreeing at those sizes."""
+    printed = {8: 45, 24: 325}
+    assert oracle.state_size_symmetric(dp, 0) == printed[dp]
+    assert oracle.feature_dim(dp) == 1 + dp + dp * dp
+    # distinct rows of the expanded state: the (a, b) and (b, a) rows coincide, leaving the printed count
+    x = rng(1000 + dp).standard_normal(dp)
+    assert len(np.unique(np.round(oracle.feature_map(x), 12))) == printed[dp]
+    g = rng(dp)
+    U, N, dv = 2, 40, 5
+    q = g.standard_normal((U, N, dp)) * 0.5; k = g.standard_normal((U, N, dp)) * 0.5
+    v = g.standard_normal((U, N, dv))
+    yq = oracle.linattn_quadratic(q, k, v)
+    yr, Sr, zr = oracle.linattn_recurrent(q, k, v)
+    assert np.allclose(yq, yr, rtol=1e-10, atol=1e-12)
+    assert np.allclose(yq, np_cumsum_form(q, k, v), rtol=1e-10, atol=1e-12)
+    assert np.allclose(Sr, np.einsum("ujf,ujc->ufc", np_phi(k), v), rtol=1e-12, atol=1e-12)
+    assert np.allclose(zr, np_phi(k).sum(1), rtol=1e-12, atol=1e-12)
+    want = np.array(brute_linattn(q[:, :9].tolist(), k[:, :9].tolist(), v[:, :9].tolist()))
+    assert np.allclose(yq[:, :9], want, rtol=1e-12, atol=1e-13)
+
+
 # --------------------------------------------------------------------------------------------
 # special cases with known answers
 # --------------------------------------------------------------------------------------------
