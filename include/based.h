@@ -23,8 +23,11 @@
  *   - dtype selects the element type of q, k, v, y (and of the window ring):
  *     BASED_F32 or BASED_BF16.  All accumulation and the recurrent state are fp32.
  *     Outputs are rounded to dtype with round-to-nearest-even.
- *   - Supported sizes: d_feat in {16, 32}; d_v, d_h in {64, 128}; w in {16, 32, 64, 128};
- *     any B, H, N >= 1 with B * H * N < 2^31.  Anything else: BASED_ERR_UNSUPPORTED.
+ *   - Supported sizes: d_feat in {8, 16, 24, 32} (the feature dimensions of the ablation table;
+ *     16 and 32 have matrix-core prefill kernels for bf16, 8 and 24 run on the fp32 vector kernel
+ *     for both dtypes; the packed-state prefill and the fused decode step exist for 16 and 32
+ *     only); d_v, d_h in {64, 128}; w in {16, 32, 64, 128}; any B, H, N >= 1 with
+ *     B * H * N < 2^31.  Anything else: BASED_ERR_UNSUPPORTED.
  *
  * Notation follows the paper: d' = d_feat is the projected feature dimension of q and k,
  * D = 1 + d' + d'^2 the expanded feature dimension (Sec. 4), d_v the value dimension.
@@ -174,6 +177,22 @@ int based_prefill_static(const void *q, const void *k, const void *v, void *y, v
  */
 int based_decode_step(const void *q, const void *k, const void *v, void *y, void *state, int B,
                       int H, int d_feat, int d_v, int dtype, void *stream);
+
+/*
+ * Numerator-only variants: what Alg. 1 (prefill) and Alg. 2 (recurrent update) compute as printed,
+ * and what the paper's kernel micro-benchmarks time (the captions of the two timing figures say
+ * they cover the numerator of the linear attention).  Same arguments, layouts, state handling and
+ * error behaviour as based_prefill / based_decode_step; the only difference is the output:
+ *   y_i = sum_{j<=i} kappa(q_i, k_j) v_j  (+ phi(q_i) S0 with an initial state),
+ * without the division by sum_{j<=i} kappa(q_i, k_j).  The K-state z is still maintained, so a
+ * state can be handed between the two kinds of call.  The magnitude of y grows with the number of
+ * tokens seen; in bf16 it is rounded like any other output.
+ */
+int based_prefill_numerator(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                            void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                            void *stream);
+int based_decode_step_numerator(const void *q, const void *k, const void *v, void *y, void *state, int B,
+                                int H, int d_feat, int d_v, int dtype, void *stream);
 
 /*
  * Sliding-window attention (Sec. 3.2): causal softmax attention (Eq. 1) in which query i sees

@@ -29,7 +29,7 @@ EXPORTS = [
     "based_swa_prefill", "based_swa_decode", "based_decode_fused",
     "based_packed_feature_dim", "based_packed_state_stride_floats", "based_packed_state_bytes",
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
-    "based_prefill_packed",
+    "based_prefill_packed", "based_prefill_numerator", "based_decode_step_numerator",
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
 ]
 
@@ -99,6 +99,10 @@ def _load() -> ctypes.CDLL:
     lib.based_decode_fused_ragged.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, f, i, i, i, vp]
     lib.based_prefill_packed.restype = i
     lib.based_prefill_packed.argtypes = lib.based_prefill.argtypes
+    lib.based_prefill_numerator.restype = i
+    lib.based_prefill_numerator.argtypes = lib.based_prefill.argtypes
+    lib.based_decode_step_numerator.restype = i
+    lib.based_decode_step_numerator.argtypes = lib.based_decode_step.argtypes
     lib.based_linear.restype = i
     lib.based_linear.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
@@ -223,8 +227,9 @@ def debug_set_poll_limit(polls: int) -> None:
     lib.based_debug_set_poll_limit(int(polls))
 
 
-def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=False):
-    """based_prefill, or based_prefill_packed (``packed=True``: ``state`` is a packed-state buffer).
+def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=False, numerator_only=False):
+    """based_prefill, based_prefill_packed (``packed=True``: ``state`` is a packed-state buffer) or
+    based_prefill_numerator (``numerator_only=True``: y is the numerator of Eq. 2, not divided).
     q, k ``[B,H,N,d']``; v ``[B,H,N,d_v]``; returns y (allocated if not given)."""
     _dev(q, k, v, y, state, workspace)
     B, H, N, dp = q.shape
@@ -244,7 +249,11 @@ def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=
         workspace = alloc_prefill_workspace(B, H, N, dp, dv, code, q.device)
     if need and workspace.numel() * workspace.element_size() < need:
         raise ValueError("workspace too small")
+    if packed and numerator_only:
+        raise ValueError("there is no packed numerator-only prefill")
     fn, what = (lib.based_prefill_packed, "based_prefill_packed") if packed else (lib.based_prefill, "based_prefill")
+    if numerator_only:
+        fn, what = lib.based_prefill_numerator, "based_prefill_numerator"
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
               _ptr(workspace), B, H, N, dp, dv, code, _stream()), what)
     return y
@@ -280,8 +289,9 @@ def state_unpack(packed, state, B, H, d_feat, d_v):
     return state
 
 
-def decode_step(q, k, v, state, y=None, packed=False):
-    """based_decode_step (``packed=True``: based_decode_step_packed on a packed state).
+def decode_step(q, k, v, state, y=None, packed=False, numerator_only=False):
+    """based_decode_step (``packed=True``: based_decode_step_packed on a packed state;
+    ``numerator_only=True``: based_decode_step_numerator, y = phi(q) S undivided).
     q, k ``[B,H,d']``; v ``[B,H,d_v]``; state updated in place."""
     _dev(q, k, v, y, state)
     B, H, dp = q.shape
@@ -293,9 +303,12 @@ def decode_step(q, k, v, state, y=None, packed=False):
         raise ValueError("state buffer too small or not fp32")
     if y is None:
         y = torch.empty_like(v)
-    fn = lib.based_decode_step_packed if packed else lib.based_decode_step
-    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), B, H, dp, dv, _dtype_code(q), _stream()),
-           "based_decode_step_packed" if packed else "based_decode_step")
+    if packed and numerator_only:
+        raise ValueError("there is no packed numerator-only decode step")
+    fn, what = (lib.based_decode_step_packed, "based_decode_step_packed") if packed else (lib.based_decode_step, "based_decode_step")
+    if numerator_only:
+        fn, what = lib.based_decode_step_numerator, "based_decode_step_numerator"
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), B, H, dp, dv, _dtype_code(q), _stream()), what)
     return y
 
 

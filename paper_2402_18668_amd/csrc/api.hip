@@ -11,7 +11,12 @@ namespace {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool ok_ptr(const void *p) { return p != nullptr && aligned16(p); }
 bool ok_dtype(int dtype) { return dtype == BASED_F32 || dtype == BASED_BF16; }
-bool ok_lin_dims(int dp, int dv) { return (dp == 16 || dp == 32) && (dv == 64 || dv == 128); }
+bool ok_lin_dims(int dp, int dv)
+{
+    return (dp == 8 || dp == 16 || dp == 24 || dp == 32) && (dv == 64 || dv == 128);
+}
+// the fused decode step is built for the feature dimensions of the trained models only
+bool ok_fused_lin_dims(int dp, int dv) { return (dp == 16 || dp == 32) && (dv == 64 || dv == 128); }
 bool ok_swa_dims(int dh, int w)
 {
     return (dh == 64 || dh == 128) && (w == 16 || w == 32 || w == 64 || w == 128);
@@ -126,7 +131,7 @@ size_t based_prefill_workspace_bytes(int B, int H, int N, int d_feat, int d_v, i
 }
 
 static int prefill_any(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
-                       int packed, void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
+                       int packed, int numerator_only, void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype,
                        void *stream)
 {
     if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
@@ -144,24 +149,32 @@ static int prefill_any(const void *q, const void *k, const void *v, void *y, voi
     void *inner = workspace ? static_cast<char *>(workspace) + kWsHeader : nullptr;
     float *st = static_cast<float *>(state);
     hipStream_t s = (hipStream_t)stream;
+    // the launchers' flag word: bit 0 an initial state is given, bit 2 numerators only
+    const int fl = (has_init ? 1 : 0) | (numerator_only ? 4 : 0);
     if (m32)
-        return status_of(launch_prefill_mfma32(q, k, v, y, st, has_init ? 1 : 0, packed, inner, U, N, d_feat, d_v, s));
+        return status_of(launch_prefill_mfma32(q, k, v, y, st, fl, packed, inner, U, N, d_feat, d_v, s));
     if (m16)
-        return status_of(launch_prefill_mfma(q, k, v, y, st, has_init ? 1 : 0, packed, inner,
+        return status_of(launch_prefill_mfma(q, k, v, y, st, fl, packed, inner,
                                              static_cast<unsigned *>(workspace), U, N, d_feat, d_v, s));
-    return status_of(launch_prefill_ref(q, k, v, y, st, has_init ? 1 : 0, inner, U, N, d_feat, d_v, dtype, s));
+    return status_of(launch_prefill_ref(q, k, v, y, st, fl, inner, U, N, d_feat, d_v, dtype, s));
 }
 
 int based_prefill(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
                   void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
 {
-    return prefill_any(q, k, v, y, state, has_init, 0, workspace, B, H, N, d_feat, d_v, dtype, stream);
+    return prefill_any(q, k, v, y, state, has_init, 0, 0, workspace, B, H, N, d_feat, d_v, dtype, stream);
+}
+
+int based_prefill_numerator(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                            void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
+{
+    return prefill_any(q, k, v, y, state, has_init, 0, 1, workspace, B, H, N, d_feat, d_v, dtype, stream);
 }
 
 int based_prefill_packed(const void *q, const void *k, const void *v, void *y, void *packed, int has_init,
                          void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
 {
-    return prefill_any(q, k, v, y, packed, has_init, 1, workspace, B, H, N, d_feat, d_v, dtype, stream);
+    return prefill_any(q, k, v, y, packed, has_init, 1, 0, workspace, B, H, N, d_feat, d_v, dtype, stream);
 }
 
 int based_prefill_static(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
@@ -184,7 +197,7 @@ int based_prefill_static(const void *q, const void *k, const void *v, void *y, v
     // before they are read, ready flags carry a per-call epoch and are cleared by their readers, and
     // the status word (zero when the array is created) is meant to persist until
     // based_prefill_status has seen it.
-    return prefill_any(q, k, v, y, state, has_init, 0, ws, B, H, N, d_feat, d_v, dtype, stream);
+    return prefill_any(q, k, v, y, state, has_init, 0, 0, ws, B, H, N, d_feat, d_v, dtype, stream);
 }
 
 int based_prefill_status(void *workspace, int B, int H, int N, int d_feat, int d_v, int dtype, void *stream)
@@ -225,7 +238,18 @@ int based_decode_step(const void *q, const void *k, const void *v, void *y, void
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
-                                        dtype, 0, (hipStream_t)stream));
+                                        dtype, 0, 0, (hipStream_t)stream));
+}
+
+int based_decode_step_numerator(const void *q, const void *k, const void *v, void *y, void *state, int B,
+                                int H, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
+        return BASED_ERR_INVALID_ARG;
+    return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
+                                        dtype, 0, 1, (hipStream_t)stream));
 }
 
 int based_packed_feature_dim(int d_feat) { return d_feat >= 1 ? packed_feature_dim(d_feat) : 0; }
@@ -269,7 +293,7 @@ int based_decode_step_packed(const void *q, const void *k, const void *v, void *
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(packed))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(packed), B * H, d_feat, d_v,
-                                        dtype, 1, (hipStream_t)stream));
+                                        dtype, 1, 0, (hipStream_t)stream));
 }
 
 size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype)
@@ -347,7 +371,7 @@ static int decode_fused_any(const void *q, const void *k, const void *v, void *y
                             int dtype, int packed, void *stream)
 {
     if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
-    if (!ok_lin_dims(d_feat, d_v) || !ok_swa_dims(d_h, w) || !ok_dtype(dtype))
+    if (!ok_fused_lin_dims(d_feat, d_v) || !ok_swa_dims(d_h, w) || !ok_dtype(dtype))
         return BASED_ERR_UNSUPPORTED;
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y_lin) || !ok_ptr(state) || !ok_ptr(swa_q) ||
         !ok_ptr(swa_k) || !ok_ptr(swa_v) || !ok_ptr(y_swa) || !ok_ptr(ring))

@@ -87,8 +87,10 @@ size_t prefill_mfma32_workspace_bytes(int U, int N, int dp, int dv);
 hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, void *y, float *state,
                                  int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                  hipStream_t s);
+// numerator_only != 0: y is phi(q) S without the division by phi(q).z
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
-                              int U, int dp, int dv, int dtype, int packed, hipStream_t s);
+                              int U, int dp, int dv, int dtype, int packed, int numerator_only,
+                              hipStream_t s);
 hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
                                   int dh, int w, float scale, int dtype, hipStream_t s);
 bool swa_prefill_mfma_supported(int dh, int w, int dtype);

@@ -35,7 +35,8 @@ __device__ __forceinline__ void zero_row(T *y, int n)
 template <int DP, int DV, typename T, bool PACKED>
 __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const T *__restrict__ k,
                                                  const T *__restrict__ v, T *__restrict__ y,
-                                                 float *__restrict__ state, int u)
+                                                 float *__restrict__ state, int u,
+                                                 bool numerator_only = false)
 {
     constexpr int D = PACKED ? packed_feature_dim(DP) : feature_dim(DP);
     constexpr int NT = kDecodeThreads;
@@ -180,7 +181,7 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < NT / 64; ++w) { num += yred[w][tid]; den += dred[w]; }
-        y[(size_t)u * DV + tid] = from_f32<T>(num / den);
+        y[(size_t)u * DV + tid] = from_f32<T>(numerator_only ? num : num / den);
     }
 }
 
@@ -325,10 +326,11 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
 template <int DP, int DV, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q, const T *k,
                                                                      const T *v, T *y, float *state,
-                                                                     int reverse)
+                                                                     int reverse, int numerator_only)
 {
     decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state,
-                                        reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x);
+                                        reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x,
+                                        numerator_only != 0);
 }
 
 template <int DH, int W, typename T>
@@ -409,24 +411,26 @@ template <int DP, int DV> static size_t state_bytes_of(int U, int packed)
 
 template <int DP, int DV, typename T>
 static void step_pick(const void *q, const void *k, const void *v, void *y, float *state, int U,
-                      int packed, hipStream_t s)
+                      int packed, int numer, hipStream_t s)
 {
     const int reverse = next_direction(state_bytes_of<DP, DV>(U, packed));
     if (packed)
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, true>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer);
     else
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, false>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer);
 }
 
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
-                              int U, int dp, int dv, int dtype, int packed, hipStream_t s)
+                              int U, int dp, int dv, int dtype, int packed, int numerator_only,
+                              hipStream_t s)
 {
 #define CALL_LIN(DP_, DV_)                                                                        \
-    if (dtype == BASED_F32) step_pick<DP_, DV_, float>(q, k, v, y, state, U, packed, s);          \
-    else step_pick<DP_, DV_, bf16_t>(q, k, v, y, state, U, packed, s)
-    BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_LIN);
+    if (dtype == BASED_F32) step_pick<DP_, DV_, float>(q, k, v, y, state, U, packed, numerator_only, s); \
+    else step_pick<DP_, DV_, bf16_t>(q, k, v, y, state, U, packed, numerator_only, s)
+    if (dp == 8 || dp == 24) BASED_PICK2(dp, 8, 24, dv, 64, 128, CALL_LIN);
+    else BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_LIN);
 #undef CALL_LIN
     return hipGetLastError();
 }

@@ -292,8 +292,10 @@ __device__ __forceinline__ void prefill_body(
     constexpr int NP = 64 * NPW;      // producer threads
     constexpr int DV = 32 * NC;       // d_v
     constexpr int VR_LD = DV + 16;
-    // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
+    // has_init carries three flags: bit 0 an initial state is given, bit 1 the state buffer is packed,
+    // bit 2 the outputs are the numerators alone (no division by the denominator)
     const bool packed_state = (has_init & 2) != 0;
+    const bool numerator_only = (has_init & 4) != 0;
     has_init &= 1;
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -510,7 +512,7 @@ __device__ __forceinline__ void prefill_body(
                         // normalise and turn the tile through LDS: a lane holds 8-byte pieces of its token's
                         // row, and stored directly those become 16-byte write requests that stall the memory
                         // pipeline; from LDS the tile leaves as 64-byte row segments, 16 rows a store.
-                        const float inv = __builtin_amdgcn_rcpf(dn[qt][0] + dn[qt][1] + dn[qt][2]);
+                        const float inv = numerator_only ? 1.f : __builtin_amdgcn_rcpf(dn[qt][0] + dn[qt][1] + dn[qt][2]);
                         uint16_t *yt = &lds.yt[c][0][0];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -1063,7 +1065,8 @@ hipError_t launch_prefill_mfma(const void *q, const void *k, const void *v, void
                                int dp, int dv, hipStream_t s)
 {
     (void)dp;
-    const int flags_word = (has_init ? 1 : 0) | (packed_state ? 2 : 0);   // the kernels' flag word
+    // the kernels' flag word (has_init arrives with bit 2 set for numerator-only outputs)
+    const int flags_word = (has_init & 1) | (packed_state ? 2 : 0) | (has_init & 4);
     const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)k, *v16 = (const uint16_t *)v;
     if (dv == 128)
         return launch<4>(q16, k16, v16, (uint16_t *)y, state, flags_word, workspace, status, U, N, s);

@@ -167,8 +167,10 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
 {
     __shared__ __align__(16) Lds lds;
 
-    // has_init carries two flags: bit 0 an initial state is given, bit 1 the state buffer is packed
+    // has_init carries three flags: bit 0 an initial state is given, bit 1 the state buffer is packed,
+    // bit 2 the outputs are the numerators alone (no division by the denominator)
     const bool packed_state = (has_init & 2) != 0;
+    const bool numerator_only = (has_init & 4) != 0;
     has_init &= 1;
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -562,7 +564,7 @@ __global__ __launch_bounds__(NT, 2) void prefill_kernel(
             {
                 // normalise and turn the tile through LDS (this wave's own exchange slots, which it has
                 // finished reading): the tile leaves as 64-byte row segments, 16 rows a store
-                const float rinv = 1.f / inv;
+                const float rinv = numerator_only ? 1.f : 1.f / inv;
                 uint16_t *yt = reinterpret_cast<uint16_t *>(&lds.xbuf[w][0][0][0][0]);   // [32][YT_LD] bf16
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -690,7 +692,8 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, vo
                                  int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                  hipStream_t s)
 {
-    has_init = (has_init ? 1 : 0) | (packed_state ? 2 : 0);   // the kernels' flag word
+    // the kernels' flag word (has_init arrives with bit 2 set for numerator-only outputs)
+    has_init = (has_init & 1) | (packed_state ? 2 : 0) | (has_init & 4);
     using namespace dp32;
     (void)dp;
     const int slices = dv / DVS;

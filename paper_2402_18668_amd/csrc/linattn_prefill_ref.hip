@@ -54,6 +54,9 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
     __shared__ float red[TB][RG][64];
     __shared__ float redd[TB][RG];
 
+    // has_init: bit 0 an initial state is given, bit 2 the outputs are the numerators alone
+    const bool numerator_only = (has_init & 4) != 0;
+    has_init &= 1;
     const int slices = dv / 64;
     const int gseg = INCREMENT ? G - 1 : G;
     const int seg = blockIdx.x % gseg, us = blockIdx.x / gseg;   // us = unit * slices + slice
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
                 float num = 0.f, den = 0.f;
 #pragma unroll
                 for (int g = 0; g < RG; ++g) { num += red[t][g][cc]; den += redd[t][g]; }
-                yu[(size_t)(tok0 + t) * dv + cc] = from_f32<T>(num / den);
+                yu[(size_t)(tok0 + t) * dv + cc] = from_f32<T>(numerator_only ? num : num / den);
             }
         }
         __syncthreads();
@@ -269,7 +272,7 @@ static hipError_t launch_ref(const void *q, const void *k, const void *v, void *
                            0, s, (const T *)q, (const T *)k, (const T *)v, (T *)y, state, has_init, N, dv, ws,
                            seg_len, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_ref_scan_kernel, dim3((unsigned)groups, 32), dim3(256), 0, s, ws, state, has_init,
+        hipLaunchKernelGGL(prefill_ref_scan_kernel, dim3((unsigned)groups, 32), dim3(256), 0, s, ws, state, has_init & 1,
                            DP, dv, G);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
@@ -282,10 +285,20 @@ hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void 
                               int has_init, void *workspace, int U, int N, int dp, int dv, int dtype,
                               hipStream_t s)
 {
+    if (dp == 8) {
+        return dtype == BASED_F32
+                   ? launch_ref<8, 256, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
+                   : launch_ref<8, 256, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
+    }
     if (dp == 16) {
         return dtype == BASED_F32
                    ? launch_ref<16, 256, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
                    : launch_ref<16, 256, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
+    }
+    if (dp == 24) {
+        return dtype == BASED_F32
+                   ? launch_ref<24, 512, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
+                   : launch_ref<24, 512, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
     }
     return dtype == BASED_F32
                ? launch_ref<32, 512, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)

@@ -62,14 +62,14 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_prefill(p, p, p, p, null, 0, null, 0, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, -3, 16, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_prefill(p, p, p, p, null, 1, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
-    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 24, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 20, 64, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 16, 96, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_prefill(p, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 7, st) == based.ERR_UNSUPPORTED
     assert lib.based_prefill(p, p, p, p, null, 0, null, 65536, 65536, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
     # status query: argument checks come before any device access; no waits in the fp32 / d' = 32 paths
     assert lib.based_prefill_status(odd, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_prefill_status(p, 0, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
-    assert lib.based_prefill_status(p, 1, 1, 8, 24, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_prefill_status(p, 1, 1, 8, 20, 64, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_prefill_status(null, 1, 1, 8, 16, 64, 0, st) == based.OK
     assert lib.based_prefill_status(null, 1, 1, 8, 32, 64, 1, st) == based.OK
     # the entry point on the library's static scratch: same host checks, and its size limit

@@ -67,6 +67,9 @@ def test_prefill_tiny_fp32(based):
     # long enough for the sequence to be cut into segments (ragged last segment and chunk)
     (16, 64, 1, 2, 1100), (16, 128, 1, 1, 1500), (16, 64, 1, 1, 2048),
     (32, 64, 1, 2, 1100), (32, 128, 1, 1, 1500), (32, 64, 1, 1, 1), (32, 128, 1, 2, 64), (32, 64, 2, 1, 65),
+    # the other feature dimensions of the ablation table (fp32 vector kernel for both dtypes)
+    (8, 64, 2, 2, 333), (8, 128, 1, 2, 1100), (24, 64, 1, 2, 150), (24, 128, 1, 1, 1100), (8, 64, 1, 1, 1),
+    (24, 64, 1, 1, 5),
 ])
 def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
     wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
@@ -86,7 +89,8 @@ def test_prefill_shapes(based, dtype, dp, dv, B, H, N):
                                                ("bf16", 16, 64, 1400, 130), ("bf16", 16, 128, 1300, 1100),
                                                # segmented second part on the fp32 vector-ALU path
                                                ("f32", 16, 64, 1400, 130), ("bf16", 32, 64, 1200, 100),
-                                               ("bf16", 32, 128, 1700, 1100)])
+                                               ("bf16", 32, 128, 1700, 1100),
+                                               ("f32", 8, 64, 300, 130), ("bf16", 24, 128, 1300, 200)])
 def test_prefill_split_with_state(based, dtype, dp, dv, N, N1):
     """prefill(N) == prefill(N1) then prefill(N - N1 | state); state import/export round trip."""
     wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
@@ -168,7 +172,8 @@ def test_prefill_deterministic(based):
 # linear attention decode
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 16, 64), ("bf16", 32, 64),
-                                         ("f32", 32, 128)])
+                                         ("f32", 32, 128), ("f32", 8, 64), ("bf16", 8, 128), ("bf16", 24, 64),
+                                         ("f32", 24, 128)])
 def test_decode_steps(based, dtype, dp, dv):
     wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, dtype=dtype)
     B, H, N0, T = 2, 3, 40, 12
@@ -201,6 +206,68 @@ def test_prefill_then_decode_equals_longer_prefill(based):
                           up(v[:, N], "bf16", (B, H, 64)), state)
     want = oracle.linattn_rows(q, k, v, np.array([N]))[:, 0]
     check_close(down(y).reshape(B * H, 64), want, TOL["bf16"], "prefill + decode")
+
+
+# ------------------------------------------------------------------------------------------------
+# numerator-only variants (the undivided output of Alg. 1 / Alg. 2)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dp,dv,N,N1", [("f32", 16, 64, 300, 130), ("bf16", 16, 64, 300, 130),
+                                               ("bf16", 16, 128, 1400, 1100), ("bf16", 32, 64, 1200, 100),
+                                               ("f32", 8, 64, 200, 70), ("bf16", 24, 128, 200, 70),
+                                               ("f32", 32, 128, 1300, 64)])
+def test_prefill_numerator_only(based, dtype, dp, dv, N, N1):
+    """based_prefill_numerator over a split sequence (the second part from the state of the first, both
+    long and short enough to be cut into segments or not) against the oracle's undivided rows; the state
+    it leaves is the same as based_prefill's."""
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H = 1, 3
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N)
+    want = oracle.linattn_numerator(q, k, v)
+
+    def part(a, lo, hi, d):
+        return up(a[:, lo:hi], dtype, (B, H, hi - lo, d))
+
+    state = based.alloc_state(B, H, dp, dv)
+    y1 = based.prefill(part(q, 0, N1, dp), part(k, 0, N1, dp), part(v, 0, N1, dv), state=state, numerator_only=True)
+    ref = based.alloc_state(B, H, dp, dv)
+    based.prefill(part(q, 0, N1, dp), part(k, 0, N1, dp), part(v, 0, N1, dv), state=ref)
+    torch.cuda.synchronize()
+    assert torch.equal(state, ref)
+    y2 = based.prefill(part(q, N1, N, dp), part(k, N1, N, dp), part(v, N1, N, dv), state=state, has_init=True,
+                       numerator_only=True)
+    torch.cuda.synchronize()
+    check_close(rows(down(y1).reshape(U, N1, dv)), rows(want[:, :N1]), TOL[dtype], "numerator prefill part 1")
+    check_close(rows(down(y2).reshape(U, N - N1, dv)), rows(want[:, N1:]), TOL[dtype], "numerator prefill part 2")
+    Sg, zg = based.state_export(state, B, H, dp, dv)
+    Sw, zw = oracle.linattn_state(k, v)
+    check_close(down(Sg).reshape(Sw.shape), Sw, TOL[dtype], "numerator prefill final S")
+    check_close(down(zg).reshape(zw.shape), zw, TOL[dtype], "numerator prefill final z")
+
+
+@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 32, 64), ("f32", 8, 128)])
+def test_decode_steps_numerator_only(based, dtype, dp, dv):
+    """based_decode_step_numerator: y = phi(q) S after the update, token by token (Alg. 2 as printed)."""
+    wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, N0, T = 2, 3, 40, 8
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N0)
+    dec = synth.decode_inputs(wl, T, units=U)
+    S, z = oracle.linattn_state(k, v)
+    state = based.alloc_state(B, H, dp, dv)
+    based.state_import(state, up(S, "f32", (B, H, S.shape[1], dv)), up(z, "f32", (B, H, z.shape[1])), dp)
+    Sd, zd = S.astype(np.float32).astype(np.float64), z.astype(np.float32).astype(np.float64)
+    for t in range(T):
+        qt, kt, vt = dec["q"][t], dec["k"][t], dec["v"][t]
+        y = based.decode_step(up(qt, dtype, (B, H, dp)), up(kt, dtype, (B, H, dp)), up(vt, dtype, (B, H, dv)), state,
+                              numerator_only=True)
+        # one token on top of the state so far: the oracle's numerator with that state as S0
+        yw = oracle.linattn_numerator(qt[:, None], kt[:, None], vt[:, None], Sd)[:, 0]
+        Sd, zd = oracle.linattn_state(kt[:, None], vt[:, None], Sd, zd)
+        check_close(down(y).reshape(U, dv), yw, TOL[dtype], f"numerator decode step {t}")
+    Sg, zg = based.state_export(state, B, H, dp, dv)
+    check_close(down(Sg).reshape(Sd.shape), Sd, TOL["f32"], "numerator decode final S")
+    check_close(down(zg).reshape(zd.shape), zd, TOL["f32"], "numerator decode final z")
 
 
 # ------------------------------------------------------------------------------------------------
@@ -721,7 +788,8 @@ def test_whole_step_graph_replay(based, dp):
 # ------------------------------------------------------------------------------------------------
 # packed state (one row per unordered feature pair)
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 32, 64), ("f32", 32, 128)])
+@pytest.mark.parametrize("dtype,dp,dv", [("f32", 16, 64), ("bf16", 16, 128), ("bf16", 32, 64), ("f32", 32, 128),
+                                         ("bf16", 8, 64), ("f32", 24, 128)])
 def test_decode_steps_packed_state(based, dtype, dp, dv):
     """Decode on the packed state gives the oracle's rows; unpacking it gives the oracle's state."""
     wl = make_wl("decode_1p3b", d_feat=dp, d_v=dv, dtype=dtype)
