@@ -194,6 +194,71 @@ def swa_rows(q, k, v, w: int, scale: float, rows) -> np.ndarray:
     return y
 
 
+def rotary(x, positions, base: float = 10000.0) -> np.ndarray:
+    """Rotary position encoding of the sliding-window layers (the training-settings table names it for
+    those layers only; the paper gives no formula, so this is the published definition of the encoding
+    it names): the head dimension is split into d_h / 2 adjacent pairs (x_{2i}, x_{2i+1}); pair i of the
+    token at position p is rotated by the angle p * base^(-2i / d_h):
+        x'_{2i}   = x_{2i} cos - x_{2i+1} sin,     x'_{2i+1} = x_{2i} sin + x_{2i+1} cos.
+    ``x [..., N, d_h]``, ``positions [N]`` (integers).  fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    pos = np.asarray(positions, dtype=np.float64)
+    dh = x.shape[-1]
+    if dh % 2 or pos.shape != (x.shape[-2],):
+        raise ValueError("x [..., N, d_h] with even d_h, positions [N]")
+    theta = base ** (-2.0 * np.arange(dh // 2) / dh)
+    ang = pos[:, None] * theta[None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    out[..., 0::2] = x[..., 0::2] * c - x[..., 1::2] * s
+    out[..., 1::2] = x[..., 0::2] * s + x[..., 1::2] * c
+    return out
+
+
+def swa_rotary(q, k, v, w: int, scale: float, pos0: int = 0, base: float = 10000.0) -> np.ndarray:
+    """Sliding-window attention with rotary-encoded queries and keys: token i of the arrays sits at
+    position pos0 + i.  The composition of the two definitions above, nothing else."""
+    N = np.asarray(q).shape[1]
+    pos = pos0 + np.arange(N)
+    return swa(rotary(q, pos, base), rotary(k, pos, base), v, w, scale)
+
+
+def short_conv_gate(a, c, h, b1, b2, c_prev=None) -> np.ndarray:
+    """The gate of a BaseConv layer (appendix on the gated convolution; training-settings table: filter
+    size 3, SiLU) between its input projections and its output projection:
+        g[t] = (a[t] + b1) * silu(sum_{j<K} h[j] * c[t - j] + b2),     silu(x) = x / (1 + exp(-x)),
+    every product per channel, ``a = u W1`` and ``c = u W2`` ``[B, N, Dc]``, filter ``h [K, Dc]`` (tap j
+    looks j tokens back: the convolution is causal), biases ``[Dc]``.  Rows before the start of the
+    sequence are zero, or the last K - 1 rows of an earlier part ``c_prev [B, K - 1, Dc]`` (oldest first).
+    fp64."""
+    a = np.asarray(a, dtype=np.float64); c = np.asarray(c, dtype=np.float64); h = np.asarray(h, dtype=np.float64)
+    b1 = np.asarray(b1, dtype=np.float64); b2 = np.asarray(b2, dtype=np.float64)
+    B, N, Dc = a.shape
+    K = h.shape[0]
+    if c.shape != a.shape or h.shape != (K, Dc) or b1.shape != (Dc,) or b2.shape != (Dc,):
+        raise ValueError("a, c [B, N, Dc]; h [K, Dc]; b1, b2 [Dc]")
+    hist = np.zeros((B, K - 1, Dc)) if c_prev is None else np.asarray(c_prev, dtype=np.float64)
+    if hist.shape != (B, K - 1, Dc):
+        raise ValueError("c_prev [B, K - 1, Dc]")
+    ext = np.concatenate([hist, c], axis=1)          # ext[:, K - 1 + t] = c[:, t]
+    conv = np.zeros_like(c)
+    for j in range(K):
+        conv += h[j][None, None, :] * ext[:, K - 1 - j:K - 1 - j + N]
+    pre = conv + b2
+    return (a + b1) * (pre / (1.0 + np.exp(-pre)))
+
+
+def baseconv(u, W1, b1, W2, b2, h, W3, b3) -> np.ndarray:
+    """A whole BaseConv layer as the appendix writes it: ((u W1 + b1) * silu(h * (u W2) + b2)) W3 + b3 with
+    ``u [B, N, d]``, ``W1, W2 [Dc, d]``, ``W3 [d, Dc]`` (weights stored output-major like ``linear``)."""
+    u = np.asarray(u, dtype=np.float64)
+    B, N, d = u.shape
+    a = linear(u.reshape(B * N, d), W1).reshape(B, N, -1)
+    c = linear(u.reshape(B * N, d), W2).reshape(B, N, -1)
+    g = short_conv_gate(a, c, h, b1, b2)
+    return linear(g.reshape(B * N, -1), W3).reshape(B, N, -1) + np.asarray(b3, dtype=np.float64)
+
+
 def linear(x, W) -> np.ndarray:
     """Bias-free linear projection ``y = x W^T`` (the q / k / v / output projections around the mixers,
     Sec. 3; the architecture listing gives them as bias-free linear layers): ``x [M, K]``, ``W [N, K]`` ->

@@ -390,6 +390,121 @@ def test_swa_special_cases():
         assert np.allclose(row, y[:, pos - 1], rtol=1e-12, atol=1e-13)
 
 
+def test_rotary_pins():
+    """The rotary encoding against its complex-number form, the 2x2 rotation matrix, and the properties
+    that define it: norms kept, position 0 the identity, angles add, and q.k depending on the positions
+    only through their difference."""
+    g = rng(5)
+    N, dh, base = 37, 8, 10000.0
+    x = g.standard_normal((2, N, dh))
+    pos = np.arange(N) * 3 + 11
+    got = oracle.rotary(x, pos, base)
+    # complex form: (x_2i + j x_2i+1) e^{j p theta_i}
+    theta = np.array([base ** (-2.0 * i / dh) for i in range(dh // 2)])
+    zc = (x[..., 0::2] + 1j * x[..., 1::2]) * np.exp(1j * pos[:, None] * theta[None, :])
+    assert np.allclose(got[..., 0::2], zc.real, rtol=1e-12, atol=1e-13)
+    assert np.allclose(got[..., 1::2], zc.imag, rtol=1e-12, atol=1e-13)
+    # d_h = 2: one textbook rotation by p radians (theta_0 = 1)
+    v2 = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -1.0]])
+    p2 = np.array([0, 1, 2])
+    r = oracle.rotary(v2, p2)
+    for t in range(3):
+        c, s_ = math.cos(p2[t]), math.sin(p2[t])
+        assert np.allclose(r[t], [v2[t, 0] * c - v2[t, 1] * s_, v2[t, 0] * s_ + v2[t, 1] * c], rtol=1e-14, atol=1e-15)
+    assert np.array_equal(oracle.rotary(x, np.zeros(N, dtype=np.int64)), x)
+    assert np.allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-13)
+    # pairwise norms too (each pair is rotated on its own)
+    assert np.allclose(got[..., 0::2] ** 2 + got[..., 1::2] ** 2, x[..., 0::2] ** 2 + x[..., 1::2] ** 2, rtol=1e-12)
+    # angles add: rotating by p then by p' is rotating by p + p'
+    again = oracle.rotary(got, pos[::-1].copy(), base)
+    assert np.allclose(again, oracle.rotary(x, pos + pos[::-1], base), rtol=1e-11, atol=1e-12)
+    # relative positions: <R_m q, R_n k> = <R_{m-n} q, k>
+    q = g.standard_normal((1, N, dh)); k = g.standard_normal((1, N, dh))
+    rq, rk = oracle.rotary(q, pos, base), oracle.rotary(k, pos, base)
+    for (m, n) in [(5, 2), (20, 20), (36, 0), (7, 30)]:
+        lhs = rq[0, m] @ rk[0, n]
+        rel = oracle.rotary(q[:, m:m + 1], np.array([pos[m] - pos[n]]), base)[0, 0] @ k[0, n]
+        assert abs(lhs - rel) < 1e-11
+    # the slowest pair: theta_{d/2 - 1} = base^(-(d-2)/d)
+    one = np.zeros((1, 1, dh)); one[0, 0, dh - 2] = 1.0
+    out = oracle.rotary(one, np.array([1000]), base)
+    ang = 1000 * base ** (-(dh - 2) / dh)
+    assert np.allclose(out[0, 0, dh - 2:], [math.cos(ang), math.sin(ang)], rtol=1e-13)
+
+
+def test_swa_rotary_pins():
+    """Window attention on rotary-encoded q, k: shifting every position by the same amount changes
+    nothing (scores depend on position differences), and it equals library attention on separately
+    rotated inputs with a band mask."""
+    g = rng(6)
+    U, N, dh, w, scale = 2, 50, 8, 16, 0.3
+    q = g.standard_normal((U, N, dh)); k = g.standard_normal((U, N, dh)); v = g.standard_normal((U, N, dh))
+    y0 = oracle.swa_rotary(q, k, v, w, scale, pos0=0)
+    assert np.allclose(y0, oracle.swa_rotary(q, k, v, w, scale, pos0=1234), rtol=1e-9, atol=1e-10)
+    assert not np.allclose(y0, oracle.swa(q, k, v, w, scale), rtol=1e-3, atol=1e-3)
+    # library route: complex-form rotation, torch attention with an explicit band mask
+    theta = 10000.0 ** (-2.0 * np.arange(dh // 2) / dh)
+    ph = np.exp(1j * np.arange(N)[:, None] * theta[None, :])
+    def rot(a):
+        zc = (a[..., 0::2] + 1j * a[..., 1::2]) * ph
+        out = np.empty_like(a); out[..., 0::2] = zc.real; out[..., 1::2] = zc.imag
+        return out
+    i = np.arange(N)[:, None]; j = np.arange(N)[None, :]
+    mask = torch.from_numpy((j <= i) & (j > i - w))
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(rot(q)), torch.from_numpy(rot(k)), torch.from_numpy(v), attn_mask=mask, scale=scale).numpy()
+    assert np.allclose(y0, want, rtol=1e-10, atol=1e-11)
+
+
+def test_short_conv_gate_pins():
+    """The BaseConv gate against library convolutions (numpy per channel, torch depthwise conv1d with left
+    padding), SiLU values, causality, the identity filter, and continuation from the previous rows."""
+    g = rng(8)
+    B, N, Dc, K = 2, 29, 6, 3
+    a = g.standard_normal((B, N, Dc)); c = g.standard_normal((B, N, Dc))
+    h = g.standard_normal((K, Dc)); b1 = g.standard_normal(Dc); b2 = g.standard_normal(Dc)
+    got = oracle.short_conv_gate(a, c, h, b1, b2)
+    silu = lambda x: x / (1.0 + np.exp(-x))
+    # numpy's full convolution per channel, truncated to the first N outputs
+    for b in range(B):
+        for ch in range(Dc):
+            conv = np.convolve(c[b, :, ch], h[:, ch])[:N]
+            assert np.allclose(got[b, :, ch], (a[b, :, ch] + b1[ch]) * silu(conv + b2[ch]), rtol=1e-12, atol=1e-13)
+    # torch: depthwise conv1d (cross-correlation, so the filter is flipped) after K - 1 zeros on the left
+    x = torch.from_numpy(c).transpose(1, 2)
+    wt = torch.from_numpy(h[::-1].copy().T).unsqueeze(1)     # [Dc, 1, K], tap K - 1 is the current token
+    conv_t = torch.nn.functional.conv1d(torch.nn.functional.pad(x, (K - 1, 0)), wt, groups=Dc).transpose(1, 2).numpy()
+    assert np.allclose(got, (a + b1) * torch.nn.functional.silu(torch.from_numpy(conv_t + b2)).numpy(), rtol=1e-12, atol=1e-13)
+    # SiLU: 0 at 0, x sigmoid(x) elsewhere; with h = [1, 0, 0], b2 = 0 the gate is (a + b1) silu(c)
+    e0 = np.zeros((K, Dc)); e0[0] = 1.0
+    assert np.allclose(oracle.short_conv_gate(a, c, e0, b1, np.zeros(Dc)), (a + b1) * c / (1 + np.exp(-c)), rtol=1e-13)
+    assert np.array_equal(oracle.short_conv_gate(a, np.zeros_like(c), h, b1, np.zeros(Dc)), np.zeros_like(a))
+    one = oracle.short_conv_gate(np.ones((1, 1, 1)), np.ones((1, 1, 1)), np.array([[1.0], [5.0], [7.0]]), np.zeros(1), np.zeros(1))
+    assert abs(one[0, 0, 0] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    # a pure delay: h = [0, 0, 1] reads the token two back
+    e2 = np.zeros((K, Dc)); e2[2] = 1.0
+    d2 = oracle.short_conv_gate(np.ones_like(a), c, e2, np.zeros(Dc), np.zeros(Dc))
+    assert np.allclose(d2[:, 2:], silu(c[:, :-2]), rtol=1e-13) and np.array_equal(d2[:, :2], np.zeros((B, 2, Dc)))
+    # causal: changing the future leaves the past alone
+    c2 = c.copy(); c2[:, 17:] += 1.0
+    assert np.array_equal(oracle.short_conv_gate(a, c2, h, b1, b2)[:, :17], got[:, :17])
+    # continuation: the second part with the last two rows of the first equals the whole
+    N1 = 11
+    part2 = oracle.short_conv_gate(a[:, N1:], c[:, N1:], h, b1, b2, c_prev=c[:, N1 - 2:N1])
+    assert np.allclose(part2, got[:, N1:], rtol=1e-13, atol=1e-14)
+    # the whole layer: the same three steps through torch's linear layers
+    d = 4
+    u = g.standard_normal((B, N, d)); W1 = g.standard_normal((Dc, d)); W2 = g.standard_normal((Dc, d))
+    W3 = g.standard_normal((d, Dc)); b3 = g.standard_normal(d)
+    tl = torch.nn.functional.linear
+    ut = torch.from_numpy(u)
+    at = tl(ut, torch.from_numpy(W1), torch.from_numpy(b1))
+    ct = tl(ut, torch.from_numpy(W2)).transpose(1, 2)
+    cv = torch.nn.functional.conv1d(torch.nn.functional.pad(ct, (K - 1, 0)), wt, groups=Dc).transpose(1, 2) + torch.from_numpy(b2)
+    want = tl(at * torch.nn.functional.silu(cv), torch.from_numpy(W3), torch.from_numpy(b3)).numpy()
+    assert np.allclose(oracle.baseconv(u, W1, b1, W2, b2, h, W3, b3), want, rtol=1e-11, atol=1e-12)
+
+
 def test_linear_projection_pins():
     """y = x W^T against what fixes it: brute-force loops, the identity and a one-hot weight (picks a
     column of x), a closed form with constant rows, and linearity in each argument (a transposed operand
