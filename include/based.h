@@ -291,6 +291,28 @@ int based_positions_advance(int *pos, int B, void *stream);
  *   misaligned pointers or non-positive sizes.
  */
 int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int dtype, void *stream);
+
+/*
+ * based_short_conv_gate -- the gate of a BaseConv layer (appendix on the gated convolution layers;
+ * training-settings table: filter size 3, SiLU activation), i.e. everything of that layer between its
+ * two input projections and its output projection (which are based_linear calls):
+ *   out[t] = (a[t] + b1) * silu(h[0] c[t] + h[1] c[t-1] + h[2] c[t-2] + b2),  silu(x) = x / (1 + e^-x),
+ * per channel; the convolution is causal and runs along the sequence.
+ *
+ *   a, c    [B][N][Dc]  in, dtype   the two projections u W1 and u W2 (Dc = expansion factor x d_model)
+ *   h       [3][Dc]     in, fp32    filter taps, tap j looks j tokens back
+ *   b1, b2  [Dc]        in, fp32
+ *   c_prev  [B][2][Dc]  in, dtype, or NULL: the two rows of c before the first token (older first);
+ *                       NULL = the sequence starts here (zeros)
+ *   out     [B][N][Dc]  out, dtype
+ *   c_last  [B][2][Dc]  out, dtype, or NULL: the last two rows of c, the state a later call passes as
+ *                       c_prev.  A decode step is the N = 1 call.  c_last may be the same buffer as
+ *                       c_prev when N <= 32 (else BASED_ERR_INVALID_ARG).
+ * Dc must be a multiple of 8 (bf16) or 4 (fp32), and at least 8; B <= 65535.
+ */
+int based_short_conv_gate(const void *a, const void *c, const float *h, const float *b1, const float *b2,
+                          const void *c_prev, void *out, void *c_last, int B, int N, int Dc, int dtype,
+                          void *stream);
 int based_swa_decode_ragged(const void *q, const void *k, const void *v, void *y, void *ring,
                             const int *pos, int B, int H, int d_h, int w, float scale, int dtype,
                             void *stream);

@@ -31,6 +31,7 @@ EXPORTS = [
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
     "based_prefill_packed", "based_prefill_numerator", "based_decode_step_numerator",
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
+    "based_short_conv_gate",
 ]
 
 
@@ -105,6 +106,8 @@ def _load() -> ctypes.CDLL:
     lib.based_decode_step_numerator.argtypes = lib.based_decode_step.argtypes
     lib.based_linear.restype = i
     lib.based_linear.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.based_short_conv_gate.restype = i
+    lib.based_short_conv_gate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
     lib.based_positions_advance.argtypes = [vp, i, vp]
     return lib
@@ -358,6 +361,28 @@ def linear(x, W, y=None):
         raise ValueError("y must be [..., N], contiguous, of x's dtype")
     _check(lib.based_linear(_ptr(x), _ptr(W), _ptr(y), M, K, N, _dtype_code(x), _stream()), "based_linear")
     return y
+
+
+def short_conv_gate(a, c, h, b1, b2, c_prev=None, c_last=None, out=None):
+    """based_short_conv_gate: ``(a + b1) * silu(causal 3-tap conv of c + b2)``; a, c ``[B,N,Dc]``, h ``[3,Dc]``
+    and b1, b2 ``[Dc]`` fp32; c_prev / c_last ``[B,2,Dc]`` (rows before / at the end of the sequence)."""
+    _dev(a, c, h, b1, b2, c_prev, c_last, out)
+    B, N, Dc = a.shape
+    if c.shape != a.shape or c.dtype != a.dtype or not a.is_contiguous() or not c.is_contiguous():
+        raise ValueError("a, c must be contiguous [B, N, Dc] of one dtype")
+    for t_, shp in ((h, (3, Dc)), (b1, (Dc,)), (b2, (Dc,))):
+        if tuple(t_.shape) != shp or t_.dtype != torch.float32 or not t_.is_contiguous():
+            raise ValueError("h [3, Dc], b1, b2 [Dc] must be contiguous fp32")
+    for t_ in (c_prev, c_last):
+        if t_ is not None and (tuple(t_.shape) != (B, 2, Dc) or t_.dtype != a.dtype or not t_.is_contiguous()):
+            raise ValueError("c_prev / c_last must be contiguous [B, 2, Dc] of a's dtype")
+    if out is None:
+        out = torch.empty_like(a)
+    elif out.shape != a.shape or out.dtype != a.dtype or not out.is_contiguous():
+        raise ValueError("out must match a")
+    _check(lib.based_short_conv_gate(_ptr(a), _ptr(c), _ptr(h), _ptr(b1), _ptr(b2), _ptr(c_prev), _ptr(out),
+                                     _ptr(c_last), B, N, Dc, _dtype_code(a), _stream()), "based_short_conv_gate")
+    return out
 
 
 def positions_advance(pos):

@@ -20,6 +20,7 @@ SOURCES = [
     "swa_prefill_ref.hip",
     "swa_prefill_mfma.hip",
     "linear_mfma.hip",
+    "baseconv.hip",
 ]
 
 FLAGS = [

@@ -351,6 +351,20 @@ int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int
     return status_of(launch_linear(x, W, y, M, K, N, (hipStream_t)stream));
 }
 
+int based_short_conv_gate(const void *a, const void *c, const float *h, const float *b1, const float *b2,
+                          const void *c_prev, void *out, void *c_last, int B, int N, int Dc, int dtype, void *stream)
+{
+    if (B < 1 || N < 1 || Dc < 1 || B > 65535) return BASED_ERR_INVALID_ARG;
+    if ((unsigned long long)B * (unsigned long long)N * (unsigned long long)Dc >= (1ull << 40)) return BASED_ERR_INVALID_ARG;
+    if (!ok_dtype(dtype) || !short_conv_gate_supported(Dc, dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(a) || !ok_ptr(c) || !ok_ptr(h) || !ok_ptr(b1) || !ok_ptr(b2) || !ok_ptr(out)) return BASED_ERR_INVALID_ARG;
+    if ((c_prev && !aligned16(c_prev)) || (c_last && !aligned16(c_last))) return BASED_ERR_INVALID_ARG;
+    // in place only when one thread both reads and writes the state rows of its channels
+    if (c_last && c_last == c_prev && N > short_conv_gate_run()) return BASED_ERR_INVALID_ARG;
+    if ((N + short_conv_gate_run() - 1) / short_conv_gate_run() > 65535) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_short_conv_gate(a, c, h, b1, b2, c_prev, out, c_last, B, N, Dc, dtype, (hipStream_t)stream));
+}
+
 int based_positions_advance(int *pos, int B, void *stream)
 {
     if (!pos || B < 1) return BASED_ERR_INVALID_ARG;

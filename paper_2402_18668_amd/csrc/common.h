@@ -118,6 +118,13 @@ hipError_t launch_state_copy(float *state, float *S, float *z, int U, int dp, in
 hipError_t launch_state_repack(float *state, float *packed, int U, int dp, int dv, int to_packed,
                                hipStream_t s);
 hipError_t launch_positions_advance(int *pos, int B, hipStream_t s);
+// BaseConv gate: out = (a + b1) * silu(causal 3-tap conv of c + b2); c_prev / c_last: the two rows before /
+// at the end of the sequence (either may be null)
+bool short_conv_gate_supported(int Dc, int dtype);
+int short_conv_gate_run();   // tokens one thread walks: c_last may alias c_prev only for N up to this
+hipError_t launch_short_conv_gate(const void *a, const void *c, const float *h, const float *b1, const float *b2,
+                                  const void *c_prev, void *out, void *c_last, int B, int N, int Dc, int dtype,
+                                  hipStream_t s);
 bool linear_supported(int M, int K, int N, int dtype);
 hipError_t launch_linear(const void *x, const void *W, void *y, int M, int K, int N, hipStream_t s);
 

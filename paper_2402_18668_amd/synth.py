@@ -149,3 +149,18 @@ def linear_inputs(index: int, M: int, K: int, N: int, dtype: str = "bf16"):
     x = round_to(normal(seed_for(index, T_LINEAR), (M, K), 1.0), dtype)
     W = round_to(normal(seed_for(index, T_LINEAR + 1), (N, K), 1.0 / np.sqrt(K)), dtype)
     return x, W
+
+
+T_BASECONV = 50   # tensor indices of the BaseConv gate inputs
+
+
+def baseconv_gate_inputs(index: int, B: int, N: int, Dc: int, dtype: str = "bf16"):
+    """Inputs of the BaseConv gate: the two projected activations a, c ``[B, N, Dc]`` ~ N(0, 1) (unit-variance
+    outputs of the input projections), rounded to ``dtype``; filter taps h ``[3, Dc]`` ~ N(0, 1) / sqrt(3) and
+    biases b1, b2 ``[Dc]`` ~ N(0, 0.1), fp32; ``index`` keys the draw."""
+    a = round_to(normal(seed_for(index, T_BASECONV), (B, N, Dc), 1.0), dtype)
+    c = round_to(normal(seed_for(index, T_BASECONV + 1), (B, N, Dc), 1.0), dtype)
+    h = normal(seed_for(index, T_BASECONV + 2), (3, Dc), 1.0 / np.sqrt(3.0))
+    b1 = normal(seed_for(index, T_BASECONV + 3), (Dc,), 0.1)
+    b2 = normal(seed_for(index, T_BASECONV + 4), (Dc,), 0.1)
+    return a, c, h, b1, b2

@@ -107,6 +107,17 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_linear(p, p, p, 8, 48, 128, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 100, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 128, 0, st) == based.ERR_UNSUPPORTED
+    # BaseConv gate
+    assert lib.based_short_conv_gate(null, p, p, p, p, null, p, null, 1, 4, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_short_conv_gate(p, p, p, p, p, null, p, null, 1, 0, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_short_conv_gate(p, p, p, p, p, null, p, null, 1, 4, 60, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_short_conv_gate(p, p, p, p, p, p, p, p, 1, 33, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_short_conv_gate(p, p, p, p, p, odd, p, null, 1, 4, 64, 1, st) == based.ERR_INVALID_ARG
+    # numerator-only variants validate like the calls they mirror
+    assert lib.based_prefill_numerator(null, p, p, p, null, 0, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill_numerator(p, p, p, p, null, 0, null, 1, 1, 8, 20, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_decode_step_numerator(p, p, p, p, null, 1, 1, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_step_numerator(p, p, p, p, p, 1, 1, 12, 64, 1, st) == based.ERR_UNSUPPORTED
     # position bookkeeping
     assert lib.based_positions_advance(null, 4, st) == based.ERR_INVALID_ARG
     assert lib.based_positions_advance(p, 0, st) == based.ERR_INVALID_ARG

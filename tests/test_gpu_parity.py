@@ -1105,6 +1105,50 @@ def test_linear_projection_full_size_sampled(based):
 # ------------------------------------------------------------------------------------------------
 # seeded random shapes (segment boundaries, ragged chunks, splits at arbitrary tokens)
 # ------------------------------------------------------------------------------------------------
+# ------------------------------------------------------------------------------------------------
+# BaseConv gate
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,N,Dc", [(2, 100, 256), (1, 1, 8), (3, 33, 1032), (1, 2, 64), (2, 65, 4096)])
+def test_short_conv_gate(based, dtype, B, N, Dc):
+    """based_short_conv_gate against the oracle: whole sequences (several runs of tokens, ragged last run,
+    channel counts that leave a workgroup partly idle), and the state rows it hands on."""
+    a, c, h, b1, b2 = synth.baseconv_gate_inputs(7, B, N, Dc, dtype)
+    want = oracle.short_conv_gate(a, c, h, b1, b2)
+    th, tb1, tb2 = up(h, "f32"), up(b1, "f32"), up(b2, "f32")
+    last = torch.full((B, 2, Dc), 7.0, dtype=TORCH_DTYPE[dtype], device="cuda")
+    got = based.short_conv_gate(up(a, dtype), up(c, dtype), th, tb1, tb2, c_last=last)
+    torch.cuda.synchronize()
+    check_close(rows(down(got)), rows(want), TOL[dtype], f"conv gate {dtype} N={N} Dc={Dc}")
+    ext = np.concatenate([np.zeros((B, 2, Dc)), c], axis=1)
+    assert np.array_equal(down(last), ext[:, -2:])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_short_conv_gate_continuation_and_steps(based, dtype):
+    """A sequence in two parts (the second from the state rows of the first), then token by token with the
+    state updated in place: every row equals the oracle's row of the whole sequence."""
+    B, N, Dc, N1, T = 2, 150, 512, 77, 5
+    a, c, h, b1, b2 = synth.baseconv_gate_inputs(8, B, N + T, Dc, dtype)
+    want = oracle.short_conv_gate(a, c, h, b1, b2)
+    th, tb1, tb2 = up(h, "f32"), up(b1, "f32"), up(b2, "f32")
+    state = torch.zeros((B, 2, Dc), dtype=TORCH_DTYPE[dtype], device="cuda")
+    g1 = based.short_conv_gate(up(a[:, :N1], dtype), up(c[:, :N1], dtype), th, tb1, tb2, c_last=state)
+    state2 = torch.empty_like(state)
+    g2 = based.short_conv_gate(up(a[:, N1:N], dtype), up(c[:, N1:N], dtype), th, tb1, tb2, c_prev=state, c_last=state2)
+    torch.cuda.synchronize()
+    check_close(rows(down(g1)), rows(want[:, :N1]), TOL[dtype], "conv gate part 1")
+    check_close(rows(down(g2)), rows(want[:, N1:N]), TOL[dtype], "conv gate part 2")
+    for t in range(N, N + T):
+        g = based.short_conv_gate(up(a[:, t:t + 1], dtype), up(c[:, t:t + 1], dtype), th, tb1, tb2,
+                                  c_prev=state2, c_last=state2)
+        check_close(rows(down(g)), rows(want[:, t:t + 1]), TOL[dtype], f"conv gate step {t}")
+    assert np.array_equal(down(state2), c[:, N + T - 2:N + T].astype(np.float64))
+    # in place is refused where the reader and the writer of the state are different threads
+    with pytest.raises(based.BasedError):
+        based.short_conv_gate(up(a[:, :40], dtype), up(c[:, :40], dtype), th, tb1, tb2, c_prev=state2, c_last=state2)
+
+
 def _random_prefill_cases():
     g = np.random.Generator(np.random.Philox(key=2402))
     cases = []
