@@ -222,6 +222,37 @@ int based_swa_decode(const void *q, const void *k, const void *v, void *y, void 
                      int B, int H, int d_h, int w, float scale, int dtype, void *stream);
 
 /*
+ * Rotary position encoding for the sliding-window layers (the training-settings table lists it as the
+ * positional encoding of those layers and of no others; the paper prints no formula, so the definition
+ * is the published one of the encoding it names): the head dimension is d_h / 2 adjacent pairs
+ * (x_2i, x_2i+1), and pair i of the q and k rows of the token at position p is rotated by the angle
+ * p * base^(-2i / d_h) before the scores are taken.  v is not touched.
+ *
+ * based_rotary_table -- the cosines and sines, computed once in fp64 and stored as fp32:
+ *   table  [N][d_h / 2][2]  out, fp32: (cos, sin) of (pos0 + t) * base^(-2i / d_h) at [t][i]
+ * base > 1 (10000 is the customary value), pos0 >= 0, pos0 + N <= 2^30.
+ *
+ * based_swa_prefill_rotary -- based_swa_prefill on rotated q and k, rotated while the rows are staged
+ * (the rotated rows are never written to global memory).  Row t of `table` belongs to token t of the
+ * call, so a call that continues a sequence passes a table built with pos0 = the number of tokens
+ * before it.  The ring, if given, receives ROTATED keys.  Everything else as based_swa_prefill.
+ *
+ * based_swa_decode_rotary -- based_swa_decode / based_swa_decode_ragged on a ring of rotated keys: the
+ * new q and k are rotated by the table row of the token's position pos - 1 (`table` built with
+ * pos0 = 0, table_rows rows); the rotated k, rounded to dtype, goes into the ring.  pos_per_seq == NULL:
+ * every sequence is at `pos`, 1 <= pos <= table_rows (else BASED_ERR_INVALID_ARG).  Otherwise `pos` is
+ * ignored and pos_per_seq [B] (device, int32) gives each sequence's position as in
+ * based_swa_decode_ragged; the host cannot see those values, and a position beyond the table uses the
+ * table's last row.
+ */
+int based_rotary_table(float *table, int pos0, int N, int d_h, float base, void *stream);
+int based_swa_prefill_rotary(const void *q, const void *k, const void *v, void *y, void *ring, const float *table,
+                             int B, int H, int N, int d_h, int w, float scale, int dtype, void *stream);
+int based_swa_decode_rotary(const void *q, const void *k, const void *v, void *y, void *ring, const float *table,
+                            int table_rows, int pos, const int *pos_per_seq, int B, int H, int d_h, int w,
+                            float scale, int dtype, void *stream);
+
+/*
  * based_decode_fused -- based_decode_step and based_swa_decode for the same token in ONE
  * kernel launch.  The two mixers belong to different layers of the model, so their outputs
  * stay separate (y_lin, y_swa).  Arguments as in the two calls above.

@@ -31,7 +31,7 @@ EXPORTS = [
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
     "based_prefill_packed", "based_prefill_numerator", "based_decode_step_numerator",
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
-    "based_short_conv_gate",
+    "based_short_conv_gate", "based_rotary_table", "based_swa_prefill_rotary", "based_swa_decode_rotary",
 ]
 
 
@@ -106,6 +106,12 @@ def _load() -> ctypes.CDLL:
     lib.based_decode_step_numerator.argtypes = lib.based_decode_step.argtypes
     lib.based_linear.restype = i
     lib.based_linear.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    lib.based_rotary_table.restype = i
+    lib.based_rotary_table.argtypes = [vp, i, i, i, f, vp]
+    lib.based_swa_prefill_rotary.restype = i
+    lib.based_swa_prefill_rotary.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
+    lib.based_swa_decode_rotary.restype = i
+    lib.based_swa_decode_rotary.argtypes = [vp, vp, vp, vp, vp, vp, i, i, vp, i, i, i, i, f, i, vp]
     lib.based_short_conv_gate.restype = i
     lib.based_short_conv_gate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
@@ -327,8 +333,17 @@ def alloc_swa_ring(B, H, w, d_h, dtype, device="cuda") -> torch.Tensor:
     return torch.zeros((B, H, 2, w, d_h), dtype=dtype, device=device)
 
 
-def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
-    """based_swa_prefill.  q, k, v ``[B,H,N,d_h]``."""
+def rotary_table(N: int, d_h: int, pos0: int = 0, base: float = 10000.0, device="cuda") -> torch.Tensor:
+    """based_rotary_table: ``[N, d_h / 2, 2]`` fp32 (cos, sin) for positions pos0 .. pos0 + N - 1."""
+    table = torch.empty((N, d_h // 2, 2), dtype=torch.float32, device=device)
+    _check(lib.based_rotary_table(_ptr(table), int(pos0), int(N), int(d_h), float(base), _stream()),
+           "based_rotary_table")
+    return table
+
+
+def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None, rotary=None):
+    """based_swa_prefill, or based_swa_prefill_rotary (``rotary``: a table from ``rotary_table`` whose row t
+    belongs to token t).  q, k, v ``[B,H,N,d_h]``."""
     _dev(q, k, v, y, ring)
     B, H, N, dh = q.shape
     if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
@@ -337,6 +352,14 @@ def swa_prefill(q, k, v, w: int, scale: float, y=None, ring=None):
         y = torch.empty_like(v)
     if ring is not None and (ring.dtype != q.dtype or ring.numel() != B * H * 2 * w * dh):
         raise ValueError("ring must be [B,H,2,w,d_h] of the input dtype")
+    if rotary is not None:
+        _dev(rotary)
+        if rotary.dtype != torch.float32 or tuple(rotary.shape) != (N, dh // 2, 2) or not rotary.is_contiguous():
+            raise ValueError("rotary table must be contiguous fp32 [N, d_h / 2, 2]")
+        _check(lib.based_swa_prefill_rotary(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), _ptr(rotary), B, H, N,
+                                            dh, int(w), float(scale), _dtype_code(q), _stream()),
+               "based_swa_prefill_rotary")
+        return y
     _check(lib.based_swa_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), B, H, N, dh, int(w),
                                  float(scale), _dtype_code(q), _stream()), "based_swa_prefill")
     return y
@@ -391,9 +414,10 @@ def positions_advance(pos):
     _check(lib.based_positions_advance(_ptr(pos), pos.numel(), _stream()), "based_positions_advance")
 
 
-def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None):
+def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None, rotary=None):
     """based_swa_decode (``pos`` an int) or based_swa_decode_ragged (``pos`` an int32 device tensor
-    ``[B]``).  q, k, v ``[B,H,d_h]``; ring updated in place."""
+    ``[B]``); with ``rotary`` (a table from position 0) based_swa_decode_rotary for either kind of ``pos``.
+    q, k, v ``[B,H,d_h]``; ring updated in place."""
     _dev(q, k, v, y, ring)
     B, H, dh = q.shape
     if k.shape != q.shape or v.shape != q.shape or k.dtype != q.dtype or v.dtype != q.dtype:
@@ -402,6 +426,19 @@ def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None):
         raise ValueError("ring must be [B,H,2,w,d_h] of the input dtype")
     if y is None:
         y = torch.empty_like(v)
+    if rotary is not None:
+        _dev(rotary)
+        if rotary.dtype != torch.float32 or rotary.dim() != 3 or tuple(rotary.shape[1:]) != (dh // 2, 2) \
+                or not rotary.is_contiguous():
+            raise ValueError("rotary table must be contiguous fp32 [rows, d_h / 2, 2]")
+        ragged = isinstance(pos, torch.Tensor)
+        if ragged:
+            _check_pos(pos, B)
+        _check(lib.based_swa_decode_rotary(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), _ptr(rotary),
+                                           int(rotary.shape[0]), 0 if ragged else int(pos),
+                                           _ptr(pos) if ragged else None, B, H, dh, int(w), float(scale),
+                                           _dtype_code(q), _stream()), "based_swa_decode_rotary")
+        return y
     if isinstance(pos, torch.Tensor):   # per-sequence positions in device memory
         _check_pos(pos, B)
         _check(lib.based_swa_decode_ragged(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(ring), _ptr(pos), B, H, dh,

@@ -21,6 +21,7 @@ SOURCES = [
     "swa_prefill_mfma.hip",
     "linear_mfma.hip",
     "baseconv.hip",
+    "rotary.hip",
 ]
 
 FLAGS = [

@@ -302,8 +302,8 @@ size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype)
     return (size_t)B * H * 2 * w * d_h * (dtype == BASED_F32 ? 4 : 2);
 }
 
-int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void *ring, int B, int H,
-                      int N, int d_h, int w, float scale, int dtype, void *stream)
+static int swa_prefill_any(const void *q, const void *k, const void *v, void *y, void *ring, const float *rot,
+                           int B, int H, int N, int d_h, int w, float scale, int dtype, void *stream)
 {
     if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
     if (!ok_swa_dims(d_h, w) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
@@ -313,15 +313,55 @@ int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void
     hipError_t e;
     // the matrix-core kernel takes the row maximum of the unscaled scores, which is the maximum of
     // the scaled ones only for a positive scale; anything else goes to the vector-ALU kernel
-    if (swa_prefill_mfma_supported(d_h, w, dtype) && scale > 0.f) {
+    if (swa_prefill_mfma_supported(d_h, w, dtype, rot != nullptr) && scale > 0.f) {
         // this kernel also fills the ring
-        e = launch_swa_prefill_mfma(q, k, v, y, ring, U, N, d_h, w, scale, (hipStream_t)stream);
+        e = launch_swa_prefill_mfma(q, k, v, y, ring, rot, U, N, d_h, w, scale, (hipStream_t)stream);
     } else {
-        e = launch_swa_prefill_ref(q, k, v, y, U, N, d_h, w, scale, dtype, (hipStream_t)stream);
+        e = launch_swa_prefill_ref(q, k, v, y, rot, U, N, d_h, w, scale, dtype, (hipStream_t)stream);
         if (e == hipSuccess && ring)
-            e = launch_swa_ring_fill(k, v, ring, U, N, d_h, w, dtype, (hipStream_t)stream);
+            e = launch_swa_ring_fill(k, v, ring, rot, U, N, d_h, w, dtype, (hipStream_t)stream);
     }
     return status_of(e);
+}
+
+int based_swa_prefill(const void *q, const void *k, const void *v, void *y, void *ring, int B, int H,
+                      int N, int d_h, int w, float scale, int dtype, void *stream)
+{
+    return swa_prefill_any(q, k, v, y, ring, nullptr, B, H, N, d_h, w, scale, dtype, stream);
+}
+
+int based_rotary_table(float *table, int pos0, int N, int d_h, float base, void *stream)
+{
+    if (N < 1 || pos0 < 0 || (long long)pos0 + N > (1ll << 30)) return BASED_ERR_INVALID_ARG;
+    if (!(base > 1.f)) return BASED_ERR_INVALID_ARG;
+    if (d_h != 64 && d_h != 128) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(table)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_rotary_table(table, pos0, N, d_h, base, (hipStream_t)stream));
+}
+
+int based_swa_prefill_rotary(const void *q, const void *k, const void *v, void *y, void *ring, const float *table,
+                             int B, int H, int N, int d_h, int w, float scale, int dtype, void *stream)
+{
+    if (!ok_ptr(table)) return BASED_ERR_INVALID_ARG;
+    return swa_prefill_any(q, k, v, y, ring, table, B, H, N, d_h, w, scale, dtype, stream);
+}
+
+static int swa_decode_any(const void *q, const void *k, const void *v, void *y, void *ring, PosArg pos,
+                          int B, int H, int d_h, int w, float scale, int dtype, void *stream);
+
+int based_swa_decode_rotary(const void *q, const void *k, const void *v, void *y, void *ring, const float *table,
+                            int table_rows, int pos, const int *pos_per_seq, int B, int H, int d_h, int w,
+                            float scale, int dtype, void *stream)
+{
+    if (!ok_ptr(table) || table_rows < 1) return BASED_ERR_INVALID_ARG;
+    if (pos_per_seq) {
+        if (reinterpret_cast<uintptr_t>(pos_per_seq) & 3u) return BASED_ERR_INVALID_ARG;
+        return swa_decode_any(q, k, v, y, ring, PosArg{0, pos_per_seq, H, 0, table, table_rows}, B, H, d_h, w, scale,
+                              dtype, stream);
+    }
+    if (pos < 1 || pos > table_rows) return BASED_ERR_INVALID_ARG;
+    return swa_decode_any(q, k, v, y, ring, PosArg{pos, nullptr, H, 0, table, table_rows}, B, H, d_h, w, scale, dtype,
+                          stream);
 }
 
 static int swa_decode_any(const void *q, const void *k, const void *v, void *y, void *ring, PosArg pos,

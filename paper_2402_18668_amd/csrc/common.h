@@ -65,6 +65,22 @@ __device__ __forceinline__ float wave_max(float x)
     return x;
 }
 
+// Rotary encoding of one 16-byte chunk of a q or k row (CE / 2 adjacent pairs): pair j becomes
+// (x0 cos - x1 sin, x0 sin + x1 cos) with (cos, sin) = t[j], the table entries of the row's position and of
+// the chunk's pairs.  Chunk: get(i), set(float[CE]), CE.
+template <typename Chunk> __device__ __forceinline__ void rotate_chunk(Chunk &c, const float2 *t)
+{
+    float o[Chunk::CE];
+#pragma unroll
+    for (int j = 0; j < Chunk::CE / 2; ++j) {
+        const float2 cs = t[j];
+        const float x0 = c.get(2 * j), x1 = c.get(2 * j + 1);
+        o[2 * j] = fmaf(x0, cs.x, -x1 * cs.y);
+        o[2 * j + 1] = fmaf(x0, cs.y, x1 * cs.x);
+    }
+    c.set(o);
+}
+
 // ---- launchers implemented in the kernel translation units ---------------------------------
 // Each returns a hipError_t from the launch (hipGetLastError), never synchronises.
 hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void *y, float *state,
@@ -91,13 +107,16 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, vo
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
                               int U, int dp, int dv, int dtype, int packed, int numerator_only,
                               hipStream_t s);
-hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                  int dh, int w, float scale, int dtype, hipStream_t s);
-bool swa_prefill_mfma_supported(int dh, int w, int dtype);
-hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
-                                   int N, int dh, int w, float scale, hipStream_t s);
-hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, int U, int N, int dh, int w,
-                                int dtype, hipStream_t s);
+// rot (everywhere below): the rotary table, (cos, sin) per [position][pair], row 0 = the first token of
+// the call (prefill) or position 0 of the sequence (decode); null = no rotation
+hipError_t launch_rotary_table(float *table, int pos0, int N, int dh, float base, hipStream_t s);
+hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, const float *rot, int U,
+                                  int N, int dh, int w, float scale, int dtype, hipStream_t s);
+bool swa_prefill_mfma_supported(int dh, int w, int dtype, int rotary);
+hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring,
+                                   const float *rot, int U, int N, int dh, int w, float scale, hipStream_t s);
+hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, const float *rot, int U, int N, int dh,
+                                int w, int dtype, hipStream_t s);
 // Position of the decoded token: one value for every sequence, or (per_seq != NULL) one per batch
 // element in device memory, where a value < 1 marks a sequence that does not take part in the step.
 struct PosArg {
@@ -105,6 +124,8 @@ struct PosArg {
     const int *per_seq;
     int H;
     int ring_stream;   // set by the fused launcher: read the ring with non-temporal loads (see there)
+    const float *rot;  // rotary table from position 0 (null: none); the token at position pos - 1 uses row pos - 1
+    int rot_rows;      // rows in it (a position beyond the table uses its last row)
 };
 hipError_t launch_swa_decode(const void *q, const void *k, const void *v, void *y, void *ring,
                              PosArg pos, int U, int dh, int w, float scale, int dtype, hipStream_t s);

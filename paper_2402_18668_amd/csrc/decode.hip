@@ -193,6 +193,7 @@ template <> struct Chunk<float> {
     static constexpr int CE = 4;
     float4 raw;
     __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
+    __device__ __forceinline__ void set(const float *a) { raw = make_float4(a[0], a[1], a[2], a[3]); }
 };
 template <> struct Chunk<bf16_t> {
     static constexpr int CE = 8;
@@ -202,13 +203,20 @@ template <> struct Chunk<bf16_t> {
         const uint32_t w = (&raw.x)[i >> 1];
         return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
     }
+    __device__ __forceinline__ void set(const float *a)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            (&raw.x)[i] = (uint32_t)f32_to_bf16_bits(a[2 * i]) | ((uint32_t)f32_to_bf16_bits(a[2 * i + 1]) << 16);
+    }
 };
 
 template <int DH, int W, typename T>
 __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T *__restrict__ k,
                                                 const T *__restrict__ v, T *__restrict__ y,
                                                 T *__restrict__ ring, int pos, float scale, int u,
-                                                bool ring_stream)
+                                                bool ring_stream, const float2 *__restrict__ rot = nullptr,
+                                                int rot_rows = 0)
 {
     using Ch = Chunk<T>;
     constexpr int NT = kDecodeThreads;
@@ -238,6 +246,13 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
     qc.raw = *reinterpret_cast<const Raw *>(q + (size_t)u * DH + chunk * CE);
     knew.raw = *reinterpret_cast<const Raw *>(k + (size_t)u * DH + chunk * CE);
     vnew.raw = *reinterpret_cast<const Raw *>(v + (size_t)u * DH + chunk * CE);
+    // rotary: the token sits at position pos - 1; its (cos, sin) pairs are requested with the rest
+    float2 cs[CE / 2];
+    if (rot) {
+        const float2 *t = rot + (size_t)min(pos - 1, rot_rows - 1) * (DH / 2) + chunk * (CE / 2);
+#pragma unroll
+        for (int j = 0; j < CE / 2; ++j) cs[j] = t[j];
+    }
     if (ring_stream) {
         // non-temporal: the ring is read once per step and should not push the state, which the next
         // step reads again, out of the last-level cache
@@ -267,6 +282,12 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
             kc[p].raw = *reinterpret_cast<const Raw *>(Kr + (size_t)jr * DH + chunk * CE);
             vc[p].raw = *reinterpret_cast<const Raw *>(Vr + (size_t)jr * DH + chunk * CE);
         }
+    }
+    if (rot) {
+        // the ring holds rotated keys: the new key is rotated (and rounded to the ring's type) before it
+        // is scored and stored
+        rotate_chunk(qc, cs);
+        rotate_chunk(knew, cs);
     }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
@@ -340,7 +361,8 @@ __global__ __launch_bounds__(kDecodeThreads) void swa_decode_kernel(const T *q, 
 {
     const int u = blockIdx.x, pos = resolve_pos(pa, u);
     if (pos < 1) { zero_row(y + (size_t)u * DH, DH); return; }
-    swa_decode_body<DH, W, T>(q, k, v, y, ring, pos, scale, u, pa.ring_stream != 0);
+    swa_decode_body<DH, W, T>(q, k, v, y, ring, pos, scale, u, pa.ring_stream != 0,
+                              reinterpret_cast<const float2 *>(pa.rot), pa.rot_rows);
 }
 
 // Blocks [0, U) run the linear-attention step (the heavy one, scheduled first), blocks [U, 2U)
@@ -366,7 +388,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_fused_kernel(
     if (lin)
         decode_step_body<DP, DV, T, PACKED>(q, k, v, y_lin, state, u);
     else
-        swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, u, pa.ring_stream != 0);
+        swa_decode_body<DH, W, T>(sq, sk, sv, y_swa, ring, pos, scale, u, pa.ring_stream != 0,
+                                  reinterpret_cast<const float2 *>(pa.rot), pa.rot_rows);
 }
 
 // ---------------------------------------------------------------------------------------------

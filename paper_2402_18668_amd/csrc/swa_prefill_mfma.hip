@@ -26,6 +26,20 @@
 // turned through a per-wave LDS staging area so that it is stored as whole 128-byte segments.
 // The last w rows of K and V of a sequence are also written to the decode ring buffer by the
 // workgroup that owns the last segment.
+//
+// Rotary encoding (ROT).  Query and key rows are rotated between their arrival in registers and their
+// use: keys before they are written to the LDS ring (and to the decode ring, which therefore holds
+// rotated keys), queries before they become the score operand.  A 16-byte chunk of a row is four
+// adjacent pairs, so the rotation is local to the registers that hold the chunk; the (cos, sin) values
+// come from a table indexed by [token][pair] that all units share.  Reading the table entry of every
+// chunk would double what the kernel pulls through the memory system (8 bytes of cos / sin per 4 bytes of
+// bf16 pair; measured + 57 % time).  Instead: (a) the new query rows of a step are the same tokens as its
+// new key rows, so the queries are fetched with the same thread-to-chunk mapping as the keys, rotated with
+// the same values and handed to the waves through LDS (in the space the output tiles use later in the
+// step); (b) a thread's chunks are the same four pairs of rows a fixed distance apart, so it reads the
+// table entry of its first row only (requested with that row, a step ahead) and advances it by a constant
+// rotation, the ratio of two table rows, for each further row.  The table traffic drops to 1 / 16 (1 / 8
+// at d_h = 64).
 #include "common.h"
 
 #include <type_traits>
@@ -57,7 +71,14 @@ template <int DH, int WIN> struct SwaCfg {
     static constexpr int NKT = W / 32 + 1;     // key tiles per query tile
     static constexpr int Y_LD = 64 + 8;        // bf16 elements per row of a wave's output staging tile (64 columns a pass)
     static constexpr size_t lds_bytes = ((size_t)NK * (V_LD + K_LD) + (size_t)4 * 32 * Y_LD) * 2;
+    // rotary variant: the per-wave region holds either the wave's 32 rotated query rows or its output tile
+    static constexpr int Q_LD = DH + 8;
+    static constexpr int WREG = 32 * (Q_LD > Y_LD ? Q_LD : Y_LD);   // elements of a wave's region
+    static constexpr size_t lds_bytes_rotary = ((size_t)NK * (V_LD + K_LD) + (size_t)4 * WREG) * 2;
 };
+
+// (cos, sin) of four adjacent pairs
+struct Rot4 { f32x4 t01, t23; };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
 {
@@ -65,15 +86,59 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c)
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 w) { return __builtin_bit_cast(bf16x8, w); }
 
+// Eight bf16 elements (four adjacent pairs) rotated by the table entries t[0..3] = (cos, sin) of their
+// position and pairs; results rounded to bf16 (nearest even).
+__device__ __forceinline__ Rot4 load_rot4(const float2 *__restrict__ t)
+{
+    Rot4 r;
+    r.t01 = *reinterpret_cast<const f32x4 *>(t);
+    r.t23 = *reinterpret_cast<const f32x4 *>(t + 2);
+    return r;
+}
+__device__ __forceinline__ u32x4 rotate8(u32x4 x, const Rot4 &r)
+{
+    const f32x4 t01 = r.t01, t23 = r.t23;
+    const float cs[8] = {t01[0], t01[1], t01[2], t01[3], t23[0], t23[1], t23[2], t23[3]};
+    u32x4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float x0 = __uint_as_float(x[j] << 16), x1 = __uint_as_float(x[j] & 0xffff0000u);
+        const float c = cs[2 * j], s = cs[2 * j + 1];
+        const float r0 = fmaf(x0, c, -x1 * s), r1 = fmaf(x0, s, x1 * c);
+        o[j] = (uint32_t)f32_to_bf16_bits(r0) | ((uint32_t)f32_to_bf16_bits(r1) << 16);
+    }
+    return o;
+}
+// a * b as rotations (complex products pair by pair); conj_b: a * conj(b)
+__device__ __forceinline__ Rot4 rot_mul(const Rot4 &a, const Rot4 &b, bool conj_b = false)
+{
+    Rot4 o;
+    const float sg = conj_b ? -1.f : 1.f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const f32x4 x = h ? a.t23 : a.t01, y = h ? b.t23 : b.t01;
+        f32x4 z;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float ac = x[2 * j], as = x[2 * j + 1], bc = y[2 * j], bs = sg * y[2 * j + 1];
+            z[2 * j] = fmaf(ac, bc, -as * bs);
+            z[2 * j + 1] = fmaf(as, bc, ac * bs);
+        }
+        if (h) o.t23 = z; else o.t01 = z;
+    }
+    return o;
+}
+
 }  // namespace
 
-template <int DH, int WIN>
-__global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__restrict__ q,
-                                                              const uint16_t *__restrict__ k,
-                                                              const uint16_t *__restrict__ v,
-                                                              uint16_t *__restrict__ y,
-                                                              uint16_t *__restrict__ ring, int N,
-                                                              int seg_len, int nseg, float scale_log2e)
+template <int DH, int WIN, bool ROT>
+__device__ __forceinline__ void swa_prefill_mfma_body(const uint16_t *__restrict__ q,
+                                                      const uint16_t *__restrict__ k,
+                                                      const uint16_t *__restrict__ v,
+                                                      uint16_t *__restrict__ y,
+                                                      uint16_t *__restrict__ ring,
+                                                      const float2 *__restrict__ rot, int N,
+                                                      int seg_len, int nseg, float scale_log2e)
 {
     using Cfg = SwaCfg<DH, WIN>;
     constexpr int W = Cfg::W;
@@ -87,7 +152,11 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     uint16_t *Vs = reinterpret_cast<uint16_t *>(lds_raw);      // [NK][V_LD]: ring of staged V rows
     uint16_t *Ks = Vs + (size_t)NK * V_LD;                     // [NK][K_LD]: ring of staged K rows
     constexpr int Y_LD = Cfg::Y_LD;
-    uint16_t *Ysh = Ks + (size_t)NK * K_LD;                    // [4 waves][32][Y_LD]: output tiles on their way out
+    // [4 waves][32][Y_LD]: output tiles on their way out.  Rotary: a wave's region is WREG elements and
+    // starts the step as its 32 rotated query rows [32][Q_LD].
+    uint16_t *Ysh = Ks + (size_t)NK * K_LD;
+    constexpr int Q_LD = Cfg::Q_LD;
+    constexpr int WREG = ROT ? Cfg::WREG : 32 * Y_LD;
 
     const int tid = threadIdx.x;
     // wave index as a scalar, so that branches on it are scalar branches (MFMA ignores EXEC)
@@ -121,6 +190,9 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             if (key < 0 || key >= N) {
                 const u32x4 zero = {0u, 0u, 0u, 0u};
                 fk[it] = zero; fv[it] = zero;
+            } else if (ROT) {
+                // (once per segment: every chunk reads its own table entry)
+                fk[it] = rotate8(fk[it], load_rot4(rot + (size_t)key * (DH / 2) + 4 * c));
             }
             *reinterpret_cast<u32x4 *>(Vs + (size_t)r * V_LD + c * 8) = fv[it];
             *reinterpret_cast<u32x4 *>(Ks + (size_t)r * K_LD + c * 8) = fk[it];
@@ -135,7 +207,30 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
     }
 
     u32x4 nk[NEWIT], nv[NEWIT];   // next step's new rows, in flight during this step
-    u32x4 qop[SLABS], qnext[SLABS];
+    u32x4 qop[SLABS], qnext[SLABS];   // rotary: qnext holds the new query rows in the key rows' chunk mapping
+    static_assert(NEWIT == SLABS, "a thread stages as many query chunks as a lane holds operand slabs");
+    Rot4 tk0;        // rotary: the table entry of the thread's first new row
+    Rot4 rot_step;   // rotary: rotation by the NT / CPR rows between a thread's consecutive chunks
+    // where row r (of the BQ rows of a step) of the rotated queries sits: wave r / 32's region
+    auto q_stage = [&](int r) { return Ysh + (size_t)(r >> 5) * WREG + (size_t)(r & 31) * Q_LD; };
+    auto read_qop = [&]() {
+        const uint16_t *row = Ysh + (size_t)wv * WREG + (size_t)n * Q_LD + 8 * g;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) qop[s] = *reinterpret_cast<const u32x4 *>(row + 16 * s);
+    };
+    if constexpr (ROT) {
+        const int c = tid % CPR;
+        const int dl = min(NT / CPR, N - 1);   // (a sequence shorter than that has a single step and no use for it)
+        rot_step = rot_mul(load_rot4(rot + (size_t)dl * (DH / 2) + 4 * c), load_rot4(rot + 4 * c), true);
+        // the first step's queries: fetched and rotated chunk by chunk, each with its own table entry
+#pragma unroll
+        for (int it = 0; it < NEWIT; ++it) {
+            const int idx = tid + it * NT, r = idx / CPR;
+            const int row = min(q0 + r, N - 1);
+            const u32x4 x = *reinterpret_cast<const u32x4 *>(q + base + (size_t)row * DH + c * 8);
+            *reinterpret_cast<u32x4 *>(q_stage(r) + c * 8) = rotate8(x, load_rot4(rot + (size_t)row * (DH / 2) + 4 * c));
+        }
+    }
     // Loads of the pipeline are unconditional (a row past the end of the sequence re-reads the last
     // row; it is zeroed when staged, or belongs to a query that is never stored).  With a conditional
     // load the compiler cannot tell how many memory operations are in flight, waits for all of them
@@ -146,13 +241,16 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
         for (int s = 0; s < SLABS; ++s)
             dst[s] = *reinterpret_cast<const u32x4 *>(q + base + (size_t)query * DH + 16 * s + 8 * g);
     };
-    load_q(q0, qop);
-    // The first queries have arrived before the pipeline starts (an asm statement that takes them as
-    // operands): otherwise every step would wait for "loads that may still be in flight from before
-    // the loop", which at that point means waiting for the prefetch it has just issued.
+    if constexpr (!ROT) {
+        load_q(q0, qop);
+        // The first queries have arrived before the pipeline starts (an asm statement that takes them as
+        // operands): otherwise every step would wait for "loads that may still be in flight from before
+        // the loop", which at that point means waiting for the prefetch it has just issued.
 #pragma unroll
-    for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qop[s]));
+        for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qop[s]));
+    }
     __syncthreads();
+    if constexpr (ROT) read_qop();
 
     // One step of BQ queries.  Steps that have a successor are instantiated apart from the last one
     // of the segment, so that inside them every prefetch and every store is unconditional code and
@@ -169,6 +267,9 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                     const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
                     const int key = min(sq0 + BQ + r, N - 1);
                     nk[it] = *reinterpret_cast<const u32x4 *>(k + base + (size_t)key * DH + c * 8);
+                    if constexpr (ROT) {
+                        if (it == 0) tk0 = load_rot4(rot + (size_t)key * (DH / 2) + 4 * c);
+                    }
                 }
             }
         };
@@ -183,7 +284,18 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             }
         };
         auto prefetch_q = [&]() {
-            if constexpr (more) load_q(sq0 + BQ, qnext);
+            if constexpr (more) {
+                if constexpr (ROT) {
+#pragma unroll
+                    for (int it = 0; it < NEWIT; ++it) {
+                        const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
+                        const int row = min(sq0 + BQ + r, N - 1);
+                        qnext[it] = *reinterpret_cast<const u32x4 *>(q + base + (size_t)row * DH + c * 8);
+                    }
+                } else {
+                    load_q(sq0 + BQ, qnext);
+                }
+            }
         };
         prefetch_q();
 
@@ -299,7 +411,7 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
             // whole 128-byte row segments, 64 columns a pass: lane l writes 16 bytes of row l / 8.
             {
                 const float inv = q_ok ? 1.f / sum : 0.f;
-                uint16_t *yt = Ysh + (size_t)wv * 32 * Y_LD;
+                uint16_t *yt = Ysh + (size_t)wv * WREG;
 #pragma unroll
                 for (int cp = 0; cp < DH / 64; ++cp) {
 #pragma unroll
@@ -339,6 +451,19 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
         }
 
         if constexpr (more) {
+            if constexpr (ROT) {
+                // The rotations happen in registers, ahead of the barrier: a wave that is early does them
+                // while the others finish the step.  rcur: the entry of the chunk at hand; a row past the
+                // end of the sequence got the last row's entry, and so do all rows after it, which are
+                // not used.
+                Rot4 rcur = tk0;
+#pragma unroll
+                for (int it = 0; it < NEWIT; ++it) {
+                    if (it > 0) rcur = rot_mul(rcur, rot_step);
+                    nk[it] = rotate8(nk[it], rcur);
+                    qnext[it] = rotate8(qnext[it], rcur);
+                }
+            }
             __syncthreads();   // every wave is done with the rows that are overwritten now
             const int rel_new = (sq0 + BQ) - (q0 - W);   // ring position of the first new key
 #pragma unroll
@@ -346,6 +471,7 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                 const int idx = tid + it * NT, r = idx / CPR, c = idx % CPR;
                 const int key = sq0 + BQ + r;
                 const int slot = (rel_new + r) % NK;
+                if constexpr (ROT) *reinterpret_cast<u32x4 *>(q_stage(r) + c * 8) = qnext[it];
                 if (key >= N) {
                     const u32x4 zero = {0u, 0u, 0u, 0u};
                     nk[it] = zero; nv[it] = zero;
@@ -359,8 +485,10 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
                 }
             }
 #pragma unroll
-            for (int s = 0; s < SLABS; ++s) qop[s] = qnext[s];
+            for (int s = 0; s < SLABS; ++s)
+                if constexpr (!ROT) qop[s] = qnext[s];
             __syncthreads();
+            if constexpr (ROT) read_qop();
         }
     };
     int sq0 = q0;
@@ -369,20 +497,44 @@ __global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__
 }
 
 template <int DH, int WIN>
-static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
-                                  int N, float scale, hipStream_t s)
+__global__ __launch_bounds__(NT) void swa_prefill_mfma_kernel(const uint16_t *__restrict__ q,
+                                                              const uint16_t *__restrict__ k,
+                                                              const uint16_t *__restrict__ v,
+                                                              uint16_t *__restrict__ y,
+                                                              uint16_t *__restrict__ ring, int N,
+                                                              int seg_len, int nseg, float scale_log2e)
+{
+    swa_prefill_mfma_body<DH, WIN, false>(q, k, v, y, ring, nullptr, N, seg_len, nseg, scale_log2e);
+}
+
+// The rotary variant keeps the table entries of the rows in flight in registers: where the LDS ring
+// leaves room for one workgroup per CU only, a wave may have the whole register file of its SIMD.
+template <int DH, int WIN>
+__global__ __launch_bounds__(NT, (SwaCfg<DH, WIN>::lds_bytes_rotary > 80u * 1024u ? 1 : 2)) void swa_prefill_mfma_rotary_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    uint16_t *__restrict__ y, uint16_t *__restrict__ ring, const float2 *__restrict__ rot, int N, int seg_len,
+    int nseg, float scale_log2e)
+{
+    swa_prefill_mfma_body<DH, WIN, true>(q, k, v, y, ring, rot, N, seg_len, nseg, scale_log2e);
+}
+
+template <int DH, int WIN, bool ROT>
+static hipError_t launch_swa_mfma_rot(const void *q, const void *k, const void *v, void *y, void *ring,
+                                      const float *rot, int U, int N, float scale, hipStream_t s)
 {
     using Cfg = SwaCfg<DH, WIN>;
-    auto kern = swa_prefill_mfma_kernel<DH, WIN>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::lds_bytes);
+    constexpr size_t lds_bytes = ROT ? Cfg::lds_bytes_rotary : Cfg::lds_bytes;
+    if (lds_bytes > 160u * 1024u) return hipErrorInvalidValue;   // callers ask swa_prefill_mfma_supported first
+    const void *kern = ROT ? reinterpret_cast<const void *>(swa_prefill_mfma_rotary_kernel<DH, WIN>)
+                           : reinterpret_cast<const void *>(swa_prefill_mfma_kernel<DH, WIN>);
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
     // Segments per sequence.  The launch should be whole rounds of resident workgroups (256 CUs x as
     // many workgroups as the LDS ring lets a CU hold: a partial last round costs as much as a full
     // one), with segments long next to the W-row halo and the ring fill every segment starts with.
     // Score of a candidate: fill of its rounds / (1 + (W + 64) / tokens per segment).
     const int steps = (N + BQ - 1) / BQ;
-    const int per_cu = (int)((160u * 1024u) / Cfg::lds_bytes) < 1 ? 1 : (int)((160u * 1024u) / Cfg::lds_bytes);
+    const int per_cu = (int)((160u * 1024u) / lds_bytes) < 1 ? 1 : (int)((160u * 1024u) / lds_bytes);
     const long slots = 256L * per_cu;
     int nseg = 1;
     double best = -1.0;
@@ -396,28 +548,45 @@ static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, v
     }
     const int seg_len = ((steps + nseg - 1) / nseg) * BQ;
     nseg = (N + seg_len - 1) / seg_len;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)nseg * U)), dim3(NT), Cfg::lds_bytes, s,
-                       (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y,
-                       (uint16_t *)ring, N, seg_len, nseg, scale * 1.44269504088896340736f);
+    const dim3 grid((unsigned)((size_t)nseg * U));
+    const float scale_log2e = scale * 1.44269504088896340736f;
+    if (ROT)
+        hipLaunchKernelGGL((swa_prefill_mfma_rotary_kernel<DH, WIN>), grid, dim3(NT), lds_bytes, s,
+                           (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y,
+                           (uint16_t *)ring, reinterpret_cast<const float2 *>(rot), N, seg_len, nseg, scale_log2e);
+    else
+        hipLaunchKernelGGL((swa_prefill_mfma_kernel<DH, WIN>), grid, dim3(NT), Cfg::lds_bytes, s,
+                           (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)y,
+                           (uint16_t *)ring, N, seg_len, nseg, scale_log2e);
     return hipGetLastError();
 }
 
-bool swa_prefill_mfma_supported(int dh, int w, int dtype)
+template <int DH, int WIN>
+static hipError_t launch_swa_mfma(const void *q, const void *k, const void *v, void *y, void *ring,
+                                  const float *rot, int U, int N, float scale, hipStream_t s)
 {
+    return rot ? launch_swa_mfma_rot<DH, WIN, true>(q, k, v, y, ring, rot, U, N, scale, s)
+               : launch_swa_mfma_rot<DH, WIN, false>(q, k, v, y, ring, nullptr, U, N, scale, s);
+}
+
+bool swa_prefill_mfma_supported(int dh, int w, int dtype, int rotary)
+{
+    // the rotary variant stages the queries in LDS as well, which the largest ring leaves no room for
+    if (rotary && dh == 128 && w == 128) return false;
     return dtype == BASED_BF16 && (dh == 64 || dh == 128) && (w == 16 || w == 32 || w == 64 || w == 128);
 }
 
-hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring, int U,
-                                   int N, int dh, int w, float scale, hipStream_t s)
+hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring,
+                                   const float *rot, int U, int N, int dh, int w, float scale, hipStream_t s)
 {
-    if (dh == 64 && w == 16) return launch_swa_mfma<64, 16>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 64 && w == 32) return launch_swa_mfma<64, 32>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 128 && w == 16) return launch_swa_mfma<128, 16>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 128 && w == 32) return launch_swa_mfma<128, 32>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 64 && w == 64) return launch_swa_mfma<64, 64>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 64 && w == 128) return launch_swa_mfma<64, 128>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 128 && w == 64) return launch_swa_mfma<128, 64>(q, k, v, y, ring, U, N, scale, s);
-    if (dh == 128 && w == 128) return launch_swa_mfma<128, 128>(q, k, v, y, ring, U, N, scale, s);
+    if (dh == 64 && w == 16) return launch_swa_mfma<64, 16>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 64 && w == 32) return launch_swa_mfma<64, 32>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 128 && w == 16) return launch_swa_mfma<128, 16>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 128 && w == 32) return launch_swa_mfma<128, 32>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 64 && w == 64) return launch_swa_mfma<64, 64>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 64 && w == 128) return launch_swa_mfma<64, 128>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 128 && w == 64) return launch_swa_mfma<128, 64>(q, k, v, y, ring, rot, U, N, scale, s);
+    if (dh == 128 && w == 128) return launch_swa_mfma<128, 128>(q, k, v, y, ring, rot, U, N, scale, s);
     return hipErrorInvalidValue;
 }
 

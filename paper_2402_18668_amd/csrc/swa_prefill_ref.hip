@@ -46,7 +46,8 @@ template <int DH, int W, typename T>
 __global__ __launch_bounds__(kSwaThreads) void swa_prefill_ref_kernel(const T *__restrict__ q,
                                                                       const T *__restrict__ k,
                                                                       const T *__restrict__ v,
-                                                                      T *__restrict__ y, int N,
+                                                                      T *__restrict__ y,
+                                                                      const float2 *__restrict__ rot, int N,
                                                                       float scale)
 {
     using Cfg = SwaRefCfg<DH, W, T>;
@@ -70,12 +71,25 @@ __global__ __launch_bounds__(kSwaThreads) void swa_prefill_ref_kernel(const T *_
 
     for (int idx = tid; idx < rows * LPR; idx += kSwaThreads) {
         const int r = idx / LPR, c = idx % LPR;
-        *reinterpret_cast<decltype(V16::raw) *>(Ks + (size_t)r * STRIDE + c * CE) =
-            *reinterpret_cast<const decltype(V16::raw) *>(k + base + (size_t)(j_lo + r) * DH + c * CE);
+        V16 kc;
+        kc.raw = *reinterpret_cast<const decltype(V16::raw) *>(k + base + (size_t)(j_lo + r) * DH + c * CE);
+        if (rot) rotate_chunk(kc, rot + (size_t)(j_lo + r) * (DH / 2) + c * (CE / 2));
+        *reinterpret_cast<decltype(V16::raw) *>(Ks + (size_t)r * STRIDE + c * CE) = kc.raw;
     }
-    for (int idx = tid; idx < QB * DH; idx += kSwaThreads) {
-        const int qi = idx / DH, c = idx % DH;
-        qs[idx] = (i0 + qi < N) ? to_f32(q[base + (size_t)(i0 + qi) * DH + c]) * scale : 0.f;
+    for (int idx = tid; idx < QB * DH / 2; idx += kSwaThreads) {
+        const int qi = idx / (DH / 2), pr = idx % (DH / 2);
+        float x0 = 0.f, x1 = 0.f;
+        if (i0 + qi < N) {
+            x0 = to_f32(q[base + (size_t)(i0 + qi) * DH + 2 * pr]);
+            x1 = to_f32(q[base + (size_t)(i0 + qi) * DH + 2 * pr + 1]);
+            if (rot) {
+                const float2 cs = rot[(size_t)(i0 + qi) * (DH / 2) + pr];
+                const float r0 = fmaf(x0, cs.x, -x1 * cs.y), r1 = fmaf(x0, cs.y, x1 * cs.x);
+                x0 = r0; x1 = r1;
+            }
+        }
+        qs[qi * DH + 2 * pr] = x0 * scale;
+        qs[qi * DH + 2 * pr + 1] = x1 * scale;
     }
     __syncthreads();
 
@@ -148,25 +162,35 @@ __global__ __launch_bounds__(kSwaThreads) void swa_prefill_ref_kernel(const T *_
     }
 }
 
-// Copies the last min(N, w) rows of k and v into ring slots j mod w.
+// Copies the last min(N, w) rows of k (rotated, if a table is given) and v into ring slots j mod w.
 template <typename T>
 __global__ void swa_ring_fill_kernel(const T *__restrict__ k, const T *__restrict__ v,
-                                     T *__restrict__ ring, int N, int dh, int w)
+                                     T *__restrict__ ring, const float2 *__restrict__ rot, int N, int dh, int w)
 {
     const int u = blockIdx.x;
     const int first = N > w ? N - w : 0;
-    const int total = (N - first) * dh;
+    const int total = (N - first) * (dh / 2);
     T *Kr = ring + (size_t)u * 2 * w * dh, *Vr = Kr + (size_t)w * dh;
-    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
-        const int j = first + idx / dh, c = idx % dh;
-        Kr[(size_t)(j % w) * dh + c] = k[((size_t)u * N + j) * dh + c];
-        Vr[(size_t)(j % w) * dh + c] = v[((size_t)u * N + j) * dh + c];
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {   // one adjacent pair of columns at a time
+        const int j = first + idx / (dh / 2), pr = idx % (dh / 2);
+        const size_t src = ((size_t)u * N + j) * dh + 2 * pr, dst = (size_t)(j % w) * dh + 2 * pr;
+        if (rot) {
+            const float2 cs = rot[(size_t)j * (dh / 2) + pr];
+            const float x0 = to_f32(k[src]), x1 = to_f32(k[src + 1]);
+            Kr[dst] = from_f32<T>(fmaf(x0, cs.x, -x1 * cs.y));
+            Kr[dst + 1] = from_f32<T>(fmaf(x0, cs.y, x1 * cs.x));
+        } else {
+            Kr[dst] = k[src];
+            Kr[dst + 1] = k[src + 1];
+        }
+        Vr[dst] = v[src];
+        Vr[dst + 1] = v[src + 1];
     }
 }
 
 template <int DH, int W, typename T>
-static hipError_t launch_swa_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                 float scale, hipStream_t s)
+static hipError_t launch_swa_ref(const void *q, const void *k, const void *v, void *y, const float *rot, int U,
+                                 int N, float scale, hipStream_t s)
 {
     using Cfg = SwaRefCfg<DH, W, T>;
     auto kern = swa_prefill_ref_kernel<DH, W, T>;
@@ -176,17 +200,17 @@ static hipError_t launch_swa_ref(const void *q, const void *k, const void *v, vo
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)((N + kSwaQB - 1) / kSwaQB) * U));
     hipLaunchKernelGGL(kern, grid, dim3(kSwaThreads), Cfg::lds_bytes, s, (const T *)q, (const T *)k,
-                       (const T *)v, (T *)y, N, scale);
+                       (const T *)v, (T *)y, reinterpret_cast<const float2 *>(rot), N, scale);
     return hipGetLastError();
 }
 
-hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, int U, int N,
-                                  int dh, int w, float scale, int dtype, hipStream_t s)
+hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, void *y, const float *rot, int U,
+                                  int N, int dh, int w, float scale, int dtype, hipStream_t s)
 {
 #define SWA_CASE(DH_, W_)                                                                    \
     if (dh == DH_ && w == W_)                                                                \
-        return dtype == BASED_F32 ? launch_swa_ref<DH_, W_, float>(q, k, v, y, U, N, scale, s) \
-                                  : launch_swa_ref<DH_, W_, bf16_t>(q, k, v, y, U, N, scale, s)
+        return dtype == BASED_F32 ? launch_swa_ref<DH_, W_, float>(q, k, v, y, rot, U, N, scale, s) \
+                                  : launch_swa_ref<DH_, W_, bf16_t>(q, k, v, y, rot, U, N, scale, s)
     SWA_CASE(64, 16);
     SWA_CASE(64, 32);
     SWA_CASE(128, 16);
@@ -199,15 +223,15 @@ hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, v
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, int U, int N, int dh, int w,
-                                int dtype, hipStream_t s)
+hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, const float *rot, int U, int N, int dh,
+                                int w, int dtype, hipStream_t s)
 {
     if (dtype == BASED_F32)
         hipLaunchKernelGGL(swa_ring_fill_kernel<float>, dim3(U), dim3(256), 0, s, (const float *)k,
-                           (const float *)v, (float *)ring, N, dh, w);
+                           (const float *)v, (float *)ring, reinterpret_cast<const float2 *>(rot), N, dh, w);
     else
         hipLaunchKernelGGL(swa_ring_fill_kernel<bf16_t>, dim3(U), dim3(256), 0, s, (const bf16_t *)k,
-                           (const bf16_t *)v, (bf16_t *)ring, N, dh, w);
+                           (const bf16_t *)v, (bf16_t *)ring, reinterpret_cast<const float2 *>(rot), N, dh, w);
     return hipGetLastError();
 }
 

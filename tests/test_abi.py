@@ -107,6 +107,16 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_linear(p, p, p, 8, 48, 128, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 100, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 128, 0, st) == based.ERR_UNSUPPORTED
+    # rotary
+    assert lib.based_rotary_table(null, 0, 4, 64, 10000.0, st) == based.ERR_INVALID_ARG
+    assert lib.based_rotary_table(p, -1, 4, 64, 10000.0, st) == based.ERR_INVALID_ARG
+    assert lib.based_rotary_table(p, 0, 4, 64, 1.0, st) == based.ERR_INVALID_ARG
+    assert lib.based_rotary_table(p, 0, 4, 80, 10000.0, st) == based.ERR_UNSUPPORTED
+    assert lib.based_swa_prefill_rotary(p, p, p, p, null, null, 1, 1, 8, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_prefill_rotary(p, p, p, p, null, p, 1, 1, 8, 64, 48, 0.125, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_swa_decode_rotary(p, p, p, p, p, p, 4, 5, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_decode_rotary(p, p, p, p, p, null, 4, 1, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_swa_decode_rotary(p, p, p, p, p, p, 4, 0, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
     # BaseConv gate
     assert lib.based_short_conv_gate(null, p, p, p, p, null, p, null, 1, 4, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_short_conv_gate(p, p, p, p, p, null, p, null, 1, 0, 64, 1, st) == based.ERR_INVALID_ARG

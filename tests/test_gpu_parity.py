@@ -1106,6 +1106,80 @@ def test_linear_projection_full_size_sampled(based):
 # seeded random shapes (segment boundaries, ragged chunks, splits at arbitrary tokens)
 # ------------------------------------------------------------------------------------------------
 # ------------------------------------------------------------------------------------------------
+# rotary encoding in the window-attention staging
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dh,pos0,N", [(64, 0, 300), (128, 1000, 77), (64, 16000, 400)])
+def test_rotary_table(based, dh, pos0, N):
+    """The table against cos / sin of the fp64 angles: correct to fp32 rounding."""
+    t = down(based.rotary_table(N, dh, pos0=pos0))
+    theta = 10000.0 ** (-2.0 * np.arange(dh // 2) / dh)
+    ang = (pos0 + np.arange(N))[:, None] * theta[None, :]
+    assert np.abs(t[..., 0] - np.cos(ang)).max() <= 2.0 ** -24 and np.abs(t[..., 1] - np.sin(ang)).max() <= 2.0 ** -24
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dh,w,B,H,N,pos0", [(64, 64, 2, 2, 300, 0), (128, 64, 1, 2, 150, 37), (64, 128, 1, 2, 333, 0),
+                                             (128, 16, 1, 1, 1300, 5000), (64, 32, 1, 2, 1, 9), (128, 128, 1, 1, 1500, 0),
+                                             (64, 64, 1, 1, 2100, 14000)])
+def test_swa_prefill_rotary(based, dtype, dh, w, B, H, N, pos0):
+    """based_swa_prefill_rotary against the oracle (rotation, then window attention), several steps and
+    segments, a ragged tail, and a sequence that starts far from position 0; the ring holds rotated keys."""
+    wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
+    U = B * H
+    q, k, v = synth.swa_inputs(wl, units=U, N=N)
+    scale = 1.0 / math.sqrt(dh)
+    want = oracle.swa_rotary(q, k, v, w, scale, pos0=pos0)
+    table = based.rotary_table(N, dh, pos0=pos0)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    y = based.swa_prefill(up(q, dtype, (B, H, N, dh)), up(k, dtype, (B, H, N, dh)), up(v, dtype, (B, H, N, dh)),
+                          w, scale, ring=ring, rotary=table)
+    torch.cuda.synchronize()
+    check_close(rows(down(y).reshape(U, N, dh)), rows(want), TOL[dtype], f"rotary window attention {dtype}")
+    rk = oracle.rotary(k, pos0 + np.arange(N))
+    r = down(ring).reshape(U, 2, w, dh)
+    for j in range(max(0, N - w), N):
+        check_close(r[:, 0, j % w], rk[:, j], TOL[dtype] / 4, f"ring key {j}")
+        assert np.array_equal(r[:, 1, j % w], v[:, j].astype(np.float64))
+
+
+def test_swa_prefill_rotary_non_positive_scale(based):
+    """bf16 with a scale the matrix-core kernel does not take: the vector kernel rotates too."""
+    wl = make_wl("prefill_360m", d_h=64, w=64)
+    B, H, N = 1, 2, 200
+    q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
+    table = based.rotary_table(N, 64)
+    y = based.swa_prefill(up(q, "bf16", (B, H, N, 64)), up(k, "bf16", (B, H, N, 64)), up(v, "bf16", (B, H, N, 64)),
+                          64, -0.11, rotary=table)
+    check_close(rows(down(y).reshape(B * H, N, 64)), rows(oracle.swa_rotary(q, k, v, 64, -0.11)), TOL["bf16"],
+                "rotary, negative scale")
+
+
+@pytest.mark.parametrize("dtype,dh,w", [("bf16", 128, 64), ("f32", 64, 64), ("bf16", 64, 16), ("f32", 128, 128)])
+@pytest.mark.parametrize("ragged", [False, True])
+def test_swa_rotary_prefill_then_decode(based, dtype, dh, w, ragged):
+    """Rotary prefill fills the ring with rotated keys; rotary decode steps continue from it, with one
+    position for all sequences or one per sequence in device memory: every step is the oracle's row of the
+    whole sequence."""
+    wl = make_wl("decode_1p3b", d_h=dh, w=w, dtype=dtype)
+    B, H, N, T = 2, 2, 100, 6
+    U = B * H
+    q, k, v = synth.swa_inputs(wl, units=U, N=N + T)
+    scale = 1.0 / math.sqrt(dh)
+    want = oracle.swa_rotary(q, k, v, w, scale)
+    table = based.rotary_table(N + T, dh)
+    ring = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    based.swa_prefill(up(q[:, :N], dtype, (B, H, N, dh)), up(k[:, :N], dtype, (B, H, N, dh)),
+                      up(v[:, :N], dtype, (B, H, N, dh)), w, scale, ring=ring, rotary=table[:N].contiguous())
+    pos = torch.full((B,), N + 1, dtype=torch.int32, device="cuda")
+    for t in range(N, N + T):
+        y = based.swa_decode(up(q[:, t], dtype, (B, H, dh)), up(k[:, t], dtype, (B, H, dh)),
+                             up(v[:, t], dtype, (B, H, dh)), ring, pos if ragged else t + 1, w, scale, rotary=table)
+        check_close(down(y).reshape(U, dh), want[:, t], TOL[dtype], f"rotary decode token {t}")
+        if ragged:
+            based.positions_advance(pos)
+
+
+# ------------------------------------------------------------------------------------------------
 # BaseConv gate
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
