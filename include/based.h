@@ -324,6 +324,30 @@ int based_positions_advance(int *pos, int B, void *stream);
 int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int dtype, void *stream);
 
 /*
+ * The projections of a linear-attention layer, reading and writing the mixer's own layout (architecture
+ * of Sec. 3 and the appendix's layer listing: bias-free projections of the d_model-wide input to H heads
+ * of d' features for q and k and of d_v for v, and of the concatenated heads back to d_model).  The
+ * mixers work on head-major tensors [B][H][N][d]; a plain GEMM produces token-major [B][N][H d] and
+ * would need a transposing pass (one more trip of q, k, v and of the mixer output through HBM) on either
+ * side.  These two calls are the GEMM of based_linear with that addressing folded into their stores
+ * and loads, and with q, k, v produced from one pass over x:
+ *
+ * based_project_qkv    q = x Wq^T, k = x Wk^T, v = x Wv^T
+ *   x  [B][N][d_model]            in, bf16
+ *   W  [H (2 d' + d_v)][d_model]  in, bf16: the rows of Wq (head-major: row h d' + j), then Wk, then Wv
+ *   q, k  [B][H][N][d']           out, bf16        v  [B][H][N][d_v]  out, bf16
+ *   d_model % 64 == 0; d', d_v multiples of 8; H (2 d' + d_v) % 128 == 0.
+ * based_project_out    out = concat_heads(y) Wo^T
+ *   y_heads  [B][H][N][d_v]  in, bf16      W  [d_model][H d_v]  in, bf16      out  [B][N][d_model]  out, bf16
+ *   d_v % 64 == 0; d_model % 128 == 0.
+ * bf16 only (BASED_ERR_UNSUPPORTED otherwise); fp32 accumulation, outputs rounded to nearest even.
+ */
+int based_project_qkv(const void *x, const void *W, void *q, void *k, void *v, int B, int N, int d_model, int H,
+                      int d_feat, int d_v, int dtype, void *stream);
+int based_project_out(const void *y_heads, const void *W, void *out, int B, int N, int H, int d_v, int d_model,
+                      int dtype, void *stream);
+
+/*
  * based_short_conv_gate -- the gate of a BaseConv layer (appendix on the gated convolution layers;
  * training-settings table: filter size 3, SiLU activation), i.e. everything of that layer between its
  * two input projections and its output projection (which are based_linear calls):

@@ -194,6 +194,26 @@ def swa_rows(q, k, v, w: int, scale: float, rows) -> np.ndarray:
     return y
 
 
+def project_heads(x, W, H: int) -> np.ndarray:
+    """A projection of the layer input into per-head rows (Sec. 3; the layer listing of the appendix
+    projects, splits the features into H heads and moves the head axis in front of the token axis):
+    ``x [B, N, d_model]``, ``W [H d, d_model]`` (row ``h d + j`` is feature j of head h) -> ``[B, H, N, d]``."""
+    x = np.asarray(x, dtype=np.float64)
+    B, N, dm = x.shape
+    y = linear(x.reshape(B * N, dm), W)
+    d = y.shape[1] // H
+    return np.ascontiguousarray(y.reshape(B, N, H, d).transpose(0, 2, 1, 3))
+
+
+def project_out(y_heads, W) -> np.ndarray:
+    """The output projection of a mixer layer: the heads of ``y_heads [B, H, N, d_v]`` are concatenated along
+    the feature axis (head h at columns ``h d_v ..``) and projected with ``W [d_model, H d_v]`` -> ``[B, N, d_model]``."""
+    y = np.asarray(y_heads, dtype=np.float64)
+    B, H, N, dv = y.shape
+    cat = y.transpose(0, 2, 1, 3).reshape(B * N, H * dv)
+    return linear(cat, W).reshape(B, N, -1)
+
+
 def rotary(x, positions, base: float = 10000.0) -> np.ndarray:
     """Rotary position encoding of the sliding-window layers (the training-settings table names it for
     those layers only; the paper gives no formula, so this is the published definition of the encoding

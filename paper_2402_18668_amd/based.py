@@ -31,6 +31,7 @@ EXPORTS = [
     "based_state_pack", "based_state_unpack", "based_decode_step_packed", "based_decode_fused_packed",
     "based_prefill_packed", "based_prefill_numerator", "based_decode_step_numerator",
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
+    "based_project_qkv", "based_project_out",
     "based_short_conv_gate", "based_rotary_table", "based_swa_prefill_rotary", "based_swa_decode_rotary",
 ]
 
@@ -112,6 +113,10 @@ def _load() -> ctypes.CDLL:
     lib.based_swa_prefill_rotary.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
     lib.based_swa_decode_rotary.restype = i
     lib.based_swa_decode_rotary.argtypes = [vp, vp, vp, vp, vp, vp, i, i, vp, i, i, i, i, f, i, vp]
+    lib.based_project_qkv.restype = i
+    lib.based_project_qkv.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.based_project_out.restype = i
+    lib.based_project_out.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
     lib.based_short_conv_gate.restype = i
     lib.based_short_conv_gate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
@@ -384,6 +389,36 @@ def linear(x, W, y=None):
         raise ValueError("y must be [..., N], contiguous, of x's dtype")
     _check(lib.based_linear(_ptr(x), _ptr(W), _ptr(y), M, K, N, _dtype_code(x), _stream()), "based_linear")
     return y
+
+
+def project_qkv(x, W, H: int, d_feat: int, d_v: int):
+    """based_project_qkv: x ``[B,N,d_model]``, W ``[H (2 d' + d_v), d_model]`` (rows of Wq, Wk, Wv) ->
+    head-major q, k ``[B,H,N,d']`` and v ``[B,H,N,d_v]``."""
+    _dev(x, W)
+    B, N, dm = x.shape
+    if tuple(W.shape) != (H * (2 * d_feat + d_v), dm) or W.dtype != x.dtype or not x.is_contiguous() \
+            or not W.is_contiguous():
+        raise ValueError("x [B, N, d_model] and W [H (2 d' + d_v), d_model] must be contiguous and of one dtype")
+    q = torch.empty((B, H, N, d_feat), dtype=x.dtype, device=x.device)
+    k = torch.empty_like(q)
+    v = torch.empty((B, H, N, d_v), dtype=x.dtype, device=x.device)
+    _check(lib.based_project_qkv(_ptr(x), _ptr(W), _ptr(q), _ptr(k), _ptr(v), B, N, dm, H, d_feat, d_v,
+                                 _dtype_code(x), _stream()), "based_project_qkv")
+    return q, k, v
+
+
+def project_out(y_heads, W):
+    """based_project_out: head-major ``[B,H,N,d_v]`` times W ``[d_model, H d_v]`` -> ``[B,N,d_model]``."""
+    _dev(y_heads, W)
+    B, H, N, dv = y_heads.shape
+    dm = W.shape[0]
+    if tuple(W.shape) != (dm, H * dv) or W.dtype != y_heads.dtype or not y_heads.is_contiguous() \
+            or not W.is_contiguous():
+        raise ValueError("y [B, H, N, d_v] and W [d_model, H d_v] must be contiguous and of one dtype")
+    out = torch.empty((B, N, dm), dtype=y_heads.dtype, device=y_heads.device)
+    _check(lib.based_project_out(_ptr(y_heads), _ptr(W), _ptr(out), B, N, H, dv, dm, _dtype_code(y_heads),
+                                 _stream()), "based_project_out")
+    return out
 
 
 def short_conv_gate(a, c, h, b1, b2, c_prev=None, c_last=None, out=None):

@@ -391,6 +391,29 @@ int based_linear(const void *x, const void *W, void *y, int M, int K, int N, int
     return status_of(launch_linear(x, W, y, M, K, N, (hipStream_t)stream));
 }
 
+int based_project_qkv(const void *x, const void *W, void *q, void *k, void *v, int B, int N, int d_model, int H,
+                      int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N) || d_model < 1 || d_feat < 1 || d_v < 1) return BASED_ERR_INVALID_ARG;
+    if ((unsigned long long)B * N * (unsigned long long)(d_model > H * (2 * d_feat + d_v) ? d_model : H * (2 * d_feat + d_v)) >=
+        (1ull << 40))
+        return BASED_ERR_INVALID_ARG;
+    if (!project_qkv_supported(d_model, H, d_feat, d_v, dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(x) || !ok_ptr(W) || !ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_project_qkv(x, W, q, k, v, B, N, d_model, H, d_feat, d_v, (hipStream_t)stream));
+}
+
+int based_project_out(const void *y_heads, const void *W, void *out, int B, int N, int H, int d_v, int d_model,
+                      int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N) || d_model < 1 || d_v < 1) return BASED_ERR_INVALID_ARG;
+    if ((unsigned long long)B * N * (unsigned long long)(d_model > H * d_v ? d_model : H * d_v) >= (1ull << 40))
+        return BASED_ERR_INVALID_ARG;
+    if (!project_out_supported(H, d_v, d_model, dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(y_heads) || !ok_ptr(W) || !ok_ptr(out)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_project_out(y_heads, W, out, B, N, H, d_v, d_model, (hipStream_t)stream));
+}
+
 int based_short_conv_gate(const void *a, const void *c, const float *h, const float *b1, const float *b2,
                           const void *c_prev, void *out, void *c_last, int B, int N, int Dc, int dtype, void *stream)
 {

@@ -148,5 +148,13 @@ hipError_t launch_short_conv_gate(const void *a, const void *c, const float *h, 
                                   hipStream_t s);
 bool linear_supported(int M, int K, int N, int dtype);
 hipError_t launch_linear(const void *x, const void *W, void *y, int M, int K, int N, hipStream_t s);
+// x [B seq_len][K] times W [H (2 d' + d_v)][K] (rows: q heads, k heads, v heads) into head-major q, k, v
+bool project_qkv_supported(int K, int H, int d_feat, int d_v, int dtype);
+hipError_t launch_project_qkv(const void *x, const void *W, void *q, void *k, void *v, int B, int seq_len, int K,
+                              int H, int d_feat, int d_v, hipStream_t s);
+// head-major mixer output [B][H][seq_len][d_v] times W [N][H d_v] into token-major [B seq_len][N]
+bool project_out_supported(int H, int d_v, int N, int dtype);
+hipError_t launch_project_out(const void *y_heads, const void *W, void *out, int B, int seq_len, int H, int d_v,
+                              int N, hipStream_t s);
 
 }  // namespace based

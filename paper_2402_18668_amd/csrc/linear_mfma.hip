@@ -12,6 +12,13 @@
 // registers while the current one is multiplied and written to LDS between two barriers.  The
 // finished tile is turned through LDS and leaves as 128-byte row segments.
 //
+// Layouts.  The mixers read and write head-major tensors [B][H][N][d], the projections' natural output is
+// token-major [B N][H d].  Rather than a transposing pass in between (one more read and write of q, k,
+// v and of the mixer output through HBM), the kernel addresses head-major tensors directly:
+//   SPLIT_OUT  the output features are three groups of heads (q, k, v: H d' + H d' + H d_v rows of W in
+//              that order) and go to three head-major tensors; x is read once for all three;
+//   HEADS_IN   the A operand is a head-major tensor (the mixer output): a K step of 64 lies inside one head.
+//
 // Workgroups that share rows of x run back to back on the same XCD (its L2 then serves x once per
 // row of tiles): block b belongs to XCD b % 8, which walks its own rows of tiles one after another.
 #include "common.h"
@@ -49,11 +56,21 @@ __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c)
                                                    0, 0);
 }
 
+// Head-major addressing: seq_len tokens per sequence, H heads; d[0..2] the head dims of the (up to) three
+// output groups, y1 / y2 the second and third output tensor; d_in the head dim of a head-major input.
+struct HeadLayout {
+    int seq_len, H;
+    int d[3];
+    uint16_t *y1, *y2;
+    int d_in;
+};
+
 // K % 64 == 0, N % 128 == 0 (checked by the launcher); any M >= 1.
+template <bool SPLIT_OUT, bool HEADS_IN>
 __global__ __launch_bounds__(NT, 2) void linear_kernel(const uint16_t *__restrict__ x,
                                                        const uint16_t *__restrict__ W,
                                                        uint16_t *__restrict__ y, int M, int K, int N,
-                                                       int tiles_m, int tiles_n)
+                                                       int tiles_m, int tiles_n, HeadLayout hl)
 {
     __shared__ __align__(16) Lds lds;
 
@@ -73,14 +90,23 @@ __global__ __launch_bounds__(NT, 2) void linear_kernel(const uint16_t *__restric
     const int s_chunk = tid & 7, s_row = tid >> 3;
     const uint16_t *xa[AIT], *wb[BIT];
 #pragma unroll
-    for (int it = 0; it < AIT; ++it)   // rows past M re-read the last one
-        xa[it] = x + (size_t)min(row0 + s_row + 32 * it, M - 1) * K + 8 * s_chunk;
+    for (int it = 0; it < AIT; ++it) {   // rows past M re-read the last one
+        const int row = min(row0 + s_row + 32 * it, M - 1);
+        if (HEADS_IN)   // token t of sequence b, head 0: [b][h][t][d_in]
+            xa[it] = x + ((size_t)(row / hl.seq_len) * hl.H * hl.seq_len + row % hl.seq_len) * hl.d_in + 8 * s_chunk;
+        else
+            xa[it] = x + (size_t)row * K + 8 * s_chunk;
+    }
 #pragma unroll
     for (int it = 0; it < BIT; ++it) wb[it] = W + (size_t)(col0 + s_row + 32 * it) * K + 8 * s_chunk;
     u32x4 ra[AIT], rb[BIT];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int it = 0; it < AIT; ++it) ra[it] = *reinterpret_cast<const u32x4 *>(xa[it] + k0);
+        for (int it = 0; it < AIT; ++it) {
+            // head-major input: feature k0 is column k0 % d_in of head k0 / d_in, one head = seq_len rows on
+            const size_t off = HEADS_IN ? (size_t)(k0 / hl.d_in) * hl.seq_len * hl.d_in + k0 % hl.d_in : (size_t)k0;
+            ra[it] = *reinterpret_cast<const u32x4 *>(xa[it] + off);
+        }
 #pragma unroll
         for (int it = 0; it < BIT; ++it) rb[it] = *reinterpret_cast<const u32x4 *>(wb[it] + k0);
     };
@@ -153,7 +179,20 @@ __global__ __launch_bounds__(NT, 2) void linear_kernel(const uint16_t *__restric
             const int r = 8 * it + (lane >> 3), c = lane & 7;
             const u32x4 val = *reinterpret_cast<const u32x4 *>(out + (size_t)r * OUT_LD + 8 * c);
             const int row = row0 + (BM / 2) * wm + 64 * half + r;
-            if (row < M) *reinterpret_cast<u32x4 *>(y + (size_t)row * N + col0 + 64 * wn + 8 * c) = val;
+            if (row < M) {
+                const int f = col0 + 64 * wn + 8 * c;   // first of this lane's 8 features
+                if (SPLIT_OUT) {
+                    // group of the feature (boundaries are multiples of 8: a chunk lies inside one head)
+                    const int n0 = hl.H * hl.d[0], n1 = n0 + hl.H * hl.d[1];
+                    uint16_t *dst = f < n0 ? y : (f < n1 ? hl.y1 : hl.y2);
+                    const int dh = f < n0 ? hl.d[0] : (f < n1 ? hl.d[1] : hl.d[2]);
+                    const int ff = f < n0 ? f : (f < n1 ? f - n0 : f - n1);
+                    const size_t o = (((size_t)(row / hl.seq_len) * hl.H + ff / dh) * hl.seq_len + row % hl.seq_len) * dh + ff % dh;
+                    *reinterpret_cast<u32x4 *>(dst + o) = val;
+                } else {
+                    *reinterpret_cast<u32x4 *>(y + (size_t)row * N + f) = val;
+                }
+            }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read back before the next piece overwrites it
     }
@@ -171,8 +210,45 @@ hipError_t launch_linear(const void *x, const void *W, void *y, int M, int K, in
     using namespace lin;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     const int rows_padded = (tiles_m + kXcds - 1) / kXcds * kXcds;
-    hipLaunchKernelGGL(linear_kernel, dim3((unsigned)((size_t)rows_padded * tiles_n)), dim3(NT), 0, s,
-                       (const uint16_t *)x, (const uint16_t *)W, (uint16_t *)y, M, K, N, tiles_m, tiles_n);
+    hipLaunchKernelGGL((linear_kernel<false, false>), dim3((unsigned)((size_t)rows_padded * tiles_n)), dim3(NT), 0, s,
+                       (const uint16_t *)x, (const uint16_t *)W, (uint16_t *)y, M, K, N, tiles_m, tiles_n, HeadLayout{});
+    return hipGetLastError();
+}
+
+bool project_qkv_supported(int K, int H, int d_feat, int d_v, int dtype)
+{
+    return dtype == BASED_BF16 && K >= lin::BK && K % lin::BK == 0 && H >= 1 && d_feat >= 8 && d_feat % 8 == 0 &&
+           d_v >= 8 && d_v % 8 == 0 && (H * (2 * d_feat + d_v)) % lin::BN == 0;
+}
+
+hipError_t launch_project_qkv(const void *x, const void *W, void *q, void *k, void *v, int B, int seq_len, int K,
+                              int H, int d_feat, int d_v, hipStream_t s)
+{
+    using namespace lin;
+    const int M = B * seq_len, N = H * (2 * d_feat + d_v);
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int rows_padded = (tiles_m + kXcds - 1) / kXcds * kXcds;
+    HeadLayout hl{seq_len, H, {d_feat, d_feat, d_v}, (uint16_t *)k, (uint16_t *)v, 0};
+    hipLaunchKernelGGL((linear_kernel<true, false>), dim3((unsigned)((size_t)rows_padded * tiles_n)), dim3(NT), 0, s,
+                       (const uint16_t *)x, (const uint16_t *)W, (uint16_t *)q, M, K, N, tiles_m, tiles_n, hl);
+    return hipGetLastError();
+}
+
+bool project_out_supported(int H, int d_v, int N, int dtype)
+{
+    return dtype == BASED_BF16 && H >= 1 && d_v >= lin::BK && d_v % lin::BK == 0 && N >= lin::BN && N % lin::BN == 0;
+}
+
+hipError_t launch_project_out(const void *y_heads, const void *W, void *out, int B, int seq_len, int H, int d_v,
+                              int N, hipStream_t s)
+{
+    using namespace lin;
+    const int M = B * seq_len, K = H * d_v;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int rows_padded = (tiles_m + kXcds - 1) / kXcds * kXcds;
+    HeadLayout hl{seq_len, H, {0, 0, 0}, nullptr, nullptr, d_v};
+    hipLaunchKernelGGL((linear_kernel<false, true>), dim3((unsigned)((size_t)rows_padded * tiles_n)), dim3(NT), 0, s,
+                       (const uint16_t *)y_heads, (const uint16_t *)W, (uint16_t *)out, M, K, N, tiles_m, tiles_n, hl);
     return hipGetLastError();
 }
 

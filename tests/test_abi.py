@@ -107,6 +107,12 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_linear(p, p, p, 8, 48, 128, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 100, 1, st) == based.ERR_UNSUPPORTED
     assert lib.based_linear(p, p, p, 8, 64, 128, 0, st) == based.ERR_UNSUPPORTED
+    # head-major projections
+    assert lib.based_project_qkv(null, p, p, p, p, 1, 8, 64, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_project_qkv(p, p, p, p, p, 1, 8, 64, 8, 16, 64, 0, st) == based.ERR_UNSUPPORTED
+    assert lib.based_project_qkv(p, p, p, p, p, 1, 8, 64, 3, 16, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_project_out(p, p, null, 1, 8, 8, 64, 128, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_project_out(p, p, p, 1, 8, 8, 32, 128, 1, st) == based.ERR_UNSUPPORTED
     # rotary
     assert lib.based_rotary_table(null, 0, 4, 64, 10000.0, st) == based.ERR_INVALID_ARG
     assert lib.based_rotary_table(p, -1, 4, 64, 10000.0, st) == based.ERR_INVALID_ARG

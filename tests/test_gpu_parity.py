@@ -1106,6 +1106,51 @@ def test_linear_projection_full_size_sampled(based):
 # seeded random shapes (segment boundaries, ragged chunks, splits at arbitrary tokens)
 # ------------------------------------------------------------------------------------------------
 # ------------------------------------------------------------------------------------------------
+# projections in the mixers' layout
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,N,dm,H,dp,dv", [(2, 300, 256, 4, 16, 64), (1, 129, 128, 16, 16, 128), (3, 50, 192, 2, 32, 64),
+                                            (1, 1, 64, 8, 8, 16)])
+def test_project_qkv_and_out(based, B, N, dm, H, dp, dv):
+    """based_project_qkv / based_project_out against the oracle's head-major projections (several tiles of
+    tokens and features, ragged token tile, chunks of 8 features that end on head boundaries)."""
+    Ntot = H * (2 * dp + dv)
+    x, W = synth.linear_inputs(21, B * N, dm, Ntot)
+    x = x.reshape(B, N, dm)
+    q, k, v = based.project_qkv(up(x, "bf16"), up(W, "bf16"), H, dp, dv)
+    torch.cuda.synchronize()
+    Wq, Wk, Wv = W[:H * dp], W[H * dp:2 * H * dp], W[2 * H * dp:]
+    for name, got, Wp in (("q", q, Wq), ("k", k, Wk), ("v", v, Wv)):
+        want = oracle.project_heads(x, Wp, H)
+        check_close(rows(down(got).reshape(B * H, N, -1)), rows(want.reshape(B * H, N, -1)), TOL["bf16"], f"project {name}")
+    if dv % 64 == 0:
+        dmo = 256
+        yh, Wo = synth.linear_inputs(22, B * H * N, dv, 8)[0].reshape(B, H, N, dv), synth.linear_inputs(23, 8, H * dv, dmo)[1]
+        out = based.project_out(up(yh, "bf16"), up(Wo, "bf16"))
+        check_close(rows(down(out)), rows(oracle.project_out(yh, Wo)), TOL["bf16"], "project out")
+
+
+def test_linear_attention_layer_chain(based):
+    """A linear-attention layer end to end in the library's own layouts (project q, k, v -> prefill -> project
+    out, no transposing pass in between) against the same chain in the oracle, each stage fed the GPU's
+    rounded output of the stage before so that the comparison stays stage by stage."""
+    B, N, dm, H, dp, dv = 2, 200, 256, 4, 16, 64
+    x, W = synth.linear_inputs(24, B * N, dm, H * (2 * dp + dv))
+    W = W * 0.5
+    W = synth.round_to(W, "bf16")
+    x = x.reshape(B, N, dm)
+    q, k, v = based.project_qkv(up(x, "bf16"), up(W, "bf16"), H, dp, dv)
+    y = based.prefill(q, k, v)
+    Wo = synth.linear_inputs(25, 8, H * dv, dm)[1]
+    out = based.project_out(y, up(Wo, "bf16"))
+    torch.cuda.synchronize()
+    qd, kd, vd = (down(t).reshape(B * H, N, -1) for t in (q, k, v))
+    check_close(rows(qd), rows(oracle.project_heads(x, W[:H * dp], H).reshape(B * H, N, dp)), TOL["bf16"], "chain q")
+    yw = oracle.linattn_quadratic(qd, kd, vd)
+    check_close(rows(down(y).reshape(B * H, N, dv)), rows(yw), TOL["bf16"], "chain mixer")
+    check_close(rows(down(out)), rows(oracle.project_out(down(y), Wo)), TOL["bf16"], "chain out")
+
+
+# ------------------------------------------------------------------------------------------------
 # rotary encoding in the window-attention staging
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dh,pos0,N", [(64, 0, 300), (128, 1000, 77), (64, 16000, 400)])

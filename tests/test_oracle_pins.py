@@ -390,6 +390,26 @@ def test_swa_special_cases():
         assert np.allclose(row, y[:, pos - 1], rtol=1e-12, atol=1e-13)
 
 
+def test_head_projection_pins():
+    """Head-major projections against einsum written per head and torch's linear + view + transpose."""
+    g = rng(9)
+    B, N, dm, H, d = 2, 7, 12, 3, 4
+    x = g.standard_normal((B, N, dm)); W = g.standard_normal((H * d, dm))
+    got = oracle.project_heads(x, W, H)
+    assert got.shape == (B, H, N, d)
+    assert np.allclose(got, np.einsum("bnk,hjk->bhnj", x, W.reshape(H, d, dm)), rtol=1e-12, atol=1e-13)
+    t = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(W)).view(B, N, H, d).transpose(1, 2)
+    assert np.allclose(got, t.numpy(), rtol=1e-12, atol=1e-13)
+    # one-hot weight: head h, feature j picks input column h d + j
+    E = np.zeros((H * d, dm)); E[np.arange(H * d), np.arange(H * d)] = 1.0
+    assert np.array_equal(oracle.project_heads(x, E, H)[:, 2, :, 1], x[:, :, 2 * d + 1])
+    y = g.standard_normal((B, H, N, d)); Wo = g.standard_normal((dm, H * d))
+    out = oracle.project_out(y, Wo)
+    assert np.allclose(out, np.einsum("bhnj,mhj->bnm", y, Wo.reshape(dm, H, d)), rtol=1e-12, atol=1e-13)
+    to = torch.nn.functional.linear(torch.from_numpy(y).transpose(1, 2).reshape(B, N, H * d), torch.from_numpy(Wo))
+    assert np.allclose(out, to.numpy(), rtol=1e-12, atol=1e-13)
+
+
 def test_rotary_pins():
     """The rotary encoding against its complex-number form, the 2x2 rotation matrix, and the properties
     that define it: norms kept, position 0 the identity, angles add, and q.k depending on the positions
