@@ -42,10 +42,12 @@ PEAK_HBM_GBS = 8000.0
 # of those sources is the one recorded here, and as null after any change to them.
 MEASURED_TRAFFIC = {
     # key: (entry point, workload) -> (bytes per launch, source files the kernel is built from, their hash)
-    ("based_prefill", "prefill_360m"): (158776377, ("linattn_prefill_mfma.hip",), "stale"),
-    ("based_swa_prefill", "prefill_360m"): (142835642, ("swa_prefill_mfma.hip",), "5623f30ea1c8"),
-    ("based_decode_step", "decode_1p3b"): (579130768, ("decode.hip",), "13e81ff1e8ef"),
-    ("based_decode_step_packed", "decode_1p3b"): (325370100, ("decode.hip",), "13e81ff1e8ef"),
+    ("based_prefill", "prefill_1p3b"): (338596491, ("linattn_prefill_mfma.hip",), "7568cc9b398f"),
+    ("based_prefill", "prefill_360m"): (171984736, ("linattn_prefill_mfma.hip",), "7568cc9b398f"),
+    ("based_swa_prefill", "prefill_1p3b"): (545564752, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
+    ("based_swa_prefill", "prefill_360m"): (142847571, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
+    ("based_decode_step", "decode_1p3b"): (579171327, ("decode.hip",), "6ccbc9b9aa4a"),
+    ("based_decode_step_packed", "decode_1p3b"): (325378674, ("decode.hip",), "6ccbc9b9aa4a"),
 }
 
 
@@ -83,7 +85,8 @@ def lin_prefill_flops_per_token_head(dp: int, dv: int, C: int = 64, packed: bool
 
 
 PREFILL_KERNEL = {
-    16: "based_prefill (d' = 16 matrix-core kernel; segment increments and main chunked pass in one launch)",
+    16: "based_prefill (prefill_mfma_kernel: producer and consumer waves; segment increments and main chunked "
+        "pass in one launch)",
     32: "based_prefill (dp32::prefill_kernel: increment launch + main launch, both inside the bracket)",
 }
 
@@ -300,8 +303,9 @@ def main() -> int:
 
     # ---- the projections around the mixers (not part of the step or of `value`) ---------------------
     if not args.no_projection_leg:
-        optional("projection", lambda: projection_leg(torch, based, dev, wl.B * wl.N, 1024 if wl.d_v == 64 else 2048,
-                                                      wl.H * (2 * wl.d_feat + wl.d_v), wl.H * wl.d_v))
+        # model widths of the two trained sizes (training-settings table): 1024 and 1792
+        optional("projection", lambda: projection_leg(torch, based, dev, wl.B, wl.N, 1024 if wl.d_v == 64 else 1792,
+                                                      wl.H, wl.d_feat, wl.d_v))
     del runner
     torch.cuda.empty_cache()
 
@@ -443,32 +447,35 @@ def decode_leg(torch, based, synth, dev, steps: int, with_graph: bool = True):
     }
 
 
-def projection_leg(torch, based, dev, M: int, d_model: int, n_qkv: int, n_o: int):
-    """based_linear on the layer's fused q/k/v projection (d_model -> H (2 d' + d_v)) and its output projection
-    (H d_v -> d_model): time per call and fraction of the bf16 MFMA peak (2 M K N flop)."""
+def projection_leg(torch, based, dev, B: int, N: int, d_model: int, H: int, dp: int, dv: int):
+    """The layer's projections in the mixers' own layout: based_project_qkv (d_model -> H (2 d' + d_v), q, k, v
+    written head-major from one pass over x) and based_project_out (head-major H d_v -> d_model): time per call
+    and fraction of the bf16 MFMA peak (2 M K N flop)."""
     bf = torch.bfloat16
     res = {}
-    for name, K, N in (("qkv", d_model, n_qkv), ("out", n_o, d_model)):
-        if K % 64 or N % 128:
-            continue
-        g = torch.Generator(device="cpu").manual_seed(11)
-        xs = [(torch.randn((M, K), generator=g)).to(bf).to(dev) for _ in range(3)]
-        W = (torch.randn((N, K), generator=g) / math.sqrt(K)).to(bf).to(dev)
-        y = torch.empty((M, N), dtype=bf, device=dev)
+    M = B * N
+    g = torch.Generator(device="cpu").manual_seed(11)
+    xs = [(torch.randn((B, N, d_model), generator=g)).to(bf).to(dev) for _ in range(3)]
+    Wqkv = (torch.randn((H * (2 * dp + dv), d_model), generator=g) / math.sqrt(d_model)).to(bf).to(dev)
+    ys = [(torch.randn((B, H, N, dv), generator=g)).to(bf).to(dev) for _ in range(3)]
+    Wo = (torch.randn((d_model, H * dv), generator=g) / math.sqrt(H * dv)).to(bf).to(dev)
+    calls = (("qkv", d_model, H * (2 * dp + dv), "based_project_qkv", lambda i: based.project_qkv(xs[i % 3], Wqkv, H, dp, dv)),
+             ("out", H * dv, d_model, "based_project_out", lambda i: based.project_out(ys[i % 3], Wo)))
+    for name, K, Nf, entry, fn in calls:
         for i in range(3):
-            based.linear(xs[i % 3], W, y=y)
+            fn(i)
         a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record()
-        R = 30
+        R = 20
         for i in range(R):
-            based.linear(xs[i % 3], W, y=y)
+            fn(i)
         b.record()
         torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / R
-        tf = 2.0 * M * K * N / (ms * 1e-3) / 1e12
-        res[name] = {"M": M, "K": K, "N": N, "ms": round(ms, 4),
-                     "roofline": {"kernel": "based_linear (lin::linear_kernel)", "bound": "mfma", "achieved": round(tf, 1),
+        ms = a.elapsed_time(b) / R   # (includes the allocation of the outputs by the binding's caching allocator)
+        tf = 2.0 * M * K * Nf / (ms * 1e-3) / 1e12
+        res[name] = {"M": M, "K": K, "N": Nf, "ms": round(ms, 4),
+                     "roofline": {"kernel": f"{entry} (lin::linear_kernel)", "bound": "mfma", "achieved": round(tf, 1),
                                   "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4)}}
     return res
 
