@@ -20,21 +20,25 @@
 // 0..15, a = row) and delta = 2T + 1 (rows 16..31); tile 4 holds the 16 linear rows, the constant
 // row (16), seven rows of padding and the eight rows of delta = 8 (24..31).
 //
-// Work split.  One workgroup per (unit, sequence segment), one wave per 32 columns of d_v (two
-// waves at d_v = 64, four at 128).  A wave owns ALL 160 state rows of its 32 columns: five 32x32
-// fp32 accumulator tiles that stay in its registers for the whole segment (the paper keeps its
-// 2nd-order state in registers for the same reason).  With the columns split this way the readout
-// Y^T = S^T phi(Q)^T and the update S += phi(K)^T V of a wave need nothing from the other waves'
-// accumulators: no partial outputs are exchanged or summed.  What the waves share is the feature
-// operands, which do not depend on the column: each operand (32 x 16 bf16, one kilobyte) is built
-// ONCE per chunk by one wave, written to LDS in MFMA operand layout (16 bytes per lane), and read
-// by every wave with one 16-byte LDS load per lane, so that the vector-ALU cost of the feature map
-// is paid once per workgroup and every LDS byte read feeds a whole MFMA.  The masked intra-chunk
-// block P is shared the same way (it is just another operand of the output product).
+// Work split.  One workgroup per (unit, sequence segment): one CONSUMER wave per 32 columns of d_v
+// (two at d_v = 64, four at 128) and four PRODUCER waves.  A consumer owns ALL 160 state rows of its
+// 32 columns: five 32x32 fp32 accumulator tiles that stay in its registers for the whole segment (the
+// paper keeps its 2nd-order state in registers for the same reason), and issues every matrix
+// instruction for those columns: readout Y^T = S^T phi(Q)^T, intra-chunk Y^T += V^T P^T, update
+// S += phi(K)^T V; then it normalises and stores its piece of y.  With the columns split this way
+// nothing of one consumer's accumulators is needed by another: no partial outputs are exchanged.
+// What the waves share is the operands, which do not depend on the column: each operand (32 x 16
+// bf16, one kilobyte) is built ONCE per chunk by a producer, written to LDS in MFMA operand layout
+// (16 bytes per lane), and read by every consumer with one 16-byte LDS load per lane, so that the
+// vector-ALU cost of the feature map is paid once per workgroup.  The masked intra-chunk blocks P
+// and the denominators are shared the same way.
 //
-// Per chunk: [stage q, k, v rows] barrier [build: feature operands, P blocks, denominators] barrier
-// [consume: readout + P.V -> normalise -> store y; update] barrier.  Global loads of the next
-// chunk are issued at the top of the chunk and land in registers underneath all of it.
+// Pipeline.  The producers run one chunk ahead of the consumers: while the consumers multiply the
+// operands of chunk t (LDS generation t % 2), the producers stage the rows of chunk t + 1 (fetched
+// into registers during chunk t - 1), and build its operands into the other generation.  Per chunk
+// there is one workgroup barrier (chunk t + 1's operands are visible, chunk t's are free) and one
+// counter in LDS that the producer waves bump when their rows are staged and that only the waves
+// building from those rows poll.
 //
 // MFMA 32x32x16 register layouts used throughout (lane = 32 g + n):
 //   A operand: row n, k-slots 8g .. 8g+7;  B operand: column n, k-slots 8g .. 8g+7;
@@ -955,9 +959,9 @@ __global__ __launch_bounds__(64 * (NC + 4), 2) void prefill_mfma_import_kernel(
 // ---- host side ----------------------------------------------------------------------------------
 namespace {
 
-// Segments per sequence: enough workgroups to fill the chip (one workgroup of four waves per CU at
-// d_v = 128, two of two waves at d_v = 64), but segments of at least 512 tokens so that the state
-// increments stay small next to q, k, v, y.
+// Segments per sequence: enough workgroups to fill the chip (one workgroup per CU fits; 256 at
+// d_v = 128, 512 at d_v = 64, where a workgroup has fewer matrix waves and the tail of a round costs
+// less), but segments of at least 512 tokens so that the state increments stay small next to q, k, v, y.
 int pick_segments(int U, int N, int dv)
 {
     const long want = dv == 128 ? 256 : 512;
