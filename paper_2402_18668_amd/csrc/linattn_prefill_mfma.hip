@@ -959,12 +959,13 @@ __global__ __launch_bounds__(64 * (NC + 4), 2) void prefill_mfma_import_kernel(
 // ---- host side ----------------------------------------------------------------------------------
 namespace {
 
-// Segments per sequence: enough workgroups to fill the chip (one workgroup per CU fits; 256 at
-// d_v = 128, 512 at d_v = 64, where a workgroup has fewer matrix waves and the tail of a round costs
-// less), but segments of at least 512 tokens so that the state increments stay small next to q, k, v, y.
+// Segments per sequence: enough main-pass workgroups to fill the chip once (one workgroup per CU fits),
+// but segments of at least 512 tokens so that the state increments stay small next to q, k, v, y.
+// More segments than that only add increment work and workspace traffic (360M-shaped prefill, 128 units:
+// 4 segments 72 us, 3 segments 71 us, 2 segments 60.5 us).
 int pick_segments(int U, int N, int dv)
 {
-    const long want = dv == 128 ? 256 : 512;
+    const long want = 256;
     int G = (int)((want + U - 1) / U);
     const int max_by_len = N / 512;
     if (G > max_by_len) G = max_by_len;
