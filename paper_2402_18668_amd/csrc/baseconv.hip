@@ -2,7 +2,8 @@
 // size 3, SiLU): between the layer's two input projections a = u W1, c = u W2 and its output projection,
 //     g[t] = (a[t] + b1) * silu(h[0] c[t] + h[1] c[t - 1] + h[2] c[t - 2] + b2),
 // every product per channel.  Pure streaming work: each element of a and c is read once and each element
-// of g written once, so the kernel is laid out for the memory system and nothing else.
+// of g written once, so the kernel is laid out for the memory system and nothing else (loads and stores
+// carry the streaming hint: nothing is touched twice; 306 -> 290 us on the 1.3B shape).
 //
 // Work split.  A thread owns 16 bytes of channels (8 bf16 or 4 fp32) and walks a run of kRun tokens with
 // the two previous rows of c in registers, so c is read once (plus a two-row halo per run).  The threads
@@ -56,6 +57,7 @@ __global__ __launch_bounds__(kThreads) void short_conv_gate_kernel(
     const int t0 = blockIdx.y * kRun, t1 = min(N, t0 + kRun);
     const size_t seq = (size_t)b * N * Dc;
     using Raw = decltype(V::raw);
+    typedef uint32_t nt16 __attribute__((ext_vector_type(4)));   // 16 bytes, the type the streaming hints take
 
     float h0[CE], h1[CE], h2[CE], bb1[CE], bb2[CE];
 #pragma unroll
@@ -81,8 +83,8 @@ __global__ __launch_bounds__(kThreads) void short_conv_gate_kernel(
 #pragma unroll 4
     for (int t = t0; t < t1; ++t) {
         V av, cv, o;
-        av.raw = *reinterpret_cast<const Raw *>(a + seq + (size_t)t * Dc + ch0);
-        cv.raw = *reinterpret_cast<const Raw *>(c + seq + (size_t)t * Dc + ch0);
+        av.raw = __builtin_bit_cast(Raw, __builtin_nontemporal_load(reinterpret_cast<const nt16 *>(a + seq + (size_t)t * Dc + ch0)));
+        cv.raw = __builtin_bit_cast(Raw, __builtin_nontemporal_load(reinterpret_cast<const nt16 *>(c + seq + (size_t)t * Dc + ch0)));
         float g[CE];
 #pragma unroll
         for (int i = 0; i < CE; ++i) {
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void short_conv_gate_kernel(
             g[i] = (av.get(i) + bb1[i]) * sg;
         }
         o.set(g);
-        *reinterpret_cast<Raw *>(out + seq + (size_t)t * Dc + ch0) = o.raw;
+        __builtin_nontemporal_store(__builtin_bit_cast(nt16, o.raw), reinterpret_cast<nt16 *>(out + seq + (size_t)t * Dc + ch0));
         p2 = p1; p1 = cv;
     }
     if (owns_end) {
