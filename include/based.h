@@ -251,6 +251,17 @@ int based_swa_prefill_rotary(const void *q, const void *k, const void *v, void *
 int based_swa_decode_rotary(const void *q, const void *k, const void *v, void *y, void *ring, const float *table,
                             int table_rows, int pos, const int *pos_per_seq, int B, int H, int d_h, int w,
                             float scale, int dtype, void *stream);
+/*
+ * based_decode_fused_rotary -- based_decode_fused / _packed / _ragged with the window half of the step on
+ * rotary-encoded q and k, as in based_swa_decode_rotary (same `table`, `table_rows`, `pos`,
+ * `pos_per_seq` rules); `packed` != 0 selects the packed linear-attention state.  The linear-attention
+ * half is unchanged (those layers carry no positional encoding).
+ */
+int based_decode_fused_rotary(const void *q, const void *k, const void *v, void *y_lin, void *state, int packed,
+                              int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
+                              void *y_swa, void *ring, const float *table, int table_rows, int pos,
+                              const int *pos_per_seq, int d_h, int w, float scale, int B, int H, int dtype,
+                              void *stream);
 
 /*
  * based_decode_fused -- based_decode_step and based_swa_decode for the same token in ONE

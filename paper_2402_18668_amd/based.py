@@ -33,6 +33,7 @@ EXPORTS = [
     "based_swa_decode_ragged", "based_decode_fused_ragged", "based_positions_advance", "based_linear",
     "based_project_qkv", "based_project_out",
     "based_short_conv_gate", "based_rotary_table", "based_swa_prefill_rotary", "based_swa_decode_rotary",
+    "based_decode_fused_rotary",
 ]
 
 
@@ -117,6 +118,8 @@ def _load() -> ctypes.CDLL:
     lib.based_project_qkv.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.based_project_out.restype = i
     lib.based_project_out.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
+    lib.based_decode_fused_rotary.restype = i
+    lib.based_decode_fused_rotary.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, vp, i, i, f, i, i, i, vp]
     lib.based_short_conv_gate.restype = i
     lib.based_short_conv_gate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
@@ -486,9 +489,10 @@ def swa_decode(q, k, v, ring, pos, w: int, scale: float, y=None, rotary=None):
 
 
 def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos, w: int, scale: float,
-                 y_lin=None, y_swa=None, packed=False):
-    """based_decode_fused (``packed=True``: based_decode_fused_packed): both decode steps in one
-    launch; returns ``(y_lin, y_swa)``."""
+                 y_lin=None, y_swa=None, packed=False, rotary=None):
+    """based_decode_fused (``packed=True``: based_decode_fused_packed; ``pos`` a device tensor:
+    based_decode_fused_ragged; ``rotary``: a table from position 0, based_decode_fused_rotary): both decode
+    steps in one launch; returns ``(y_lin, y_swa)``."""
     _dev(q, k, v, state, swa_q, swa_k, swa_v, ring, y_lin, y_swa)
     B, H, dp = q.shape
     dv = v.shape[-1]
@@ -509,6 +513,20 @@ def decode_fused(q, k, v, state, swa_q, swa_k, swa_v, ring, pos, w: int, scale: 
         y_lin = torch.empty_like(v)
     if y_swa is None:
         y_swa = torch.empty_like(swa_v)
+    if rotary is not None:
+        _dev(rotary)
+        if rotary.dtype != torch.float32 or rotary.dim() != 3 or tuple(rotary.shape[1:]) != (dh // 2, 2) \
+                or not rotary.is_contiguous():
+            raise ValueError("rotary table must be contiguous fp32 [rows, d_h / 2, 2]")
+        ragged = isinstance(pos, torch.Tensor)
+        if ragged:
+            _check_pos(pos, B)
+        _check(lib.based_decode_fused_rotary(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), int(bool(packed)),
+                                             dp, dv, _ptr(swa_q), _ptr(swa_k), _ptr(swa_v), _ptr(y_swa), _ptr(ring),
+                                             _ptr(rotary), int(rotary.shape[0]), 0 if ragged else int(pos),
+                                             _ptr(pos) if ragged else None, dh, int(w), float(scale), B, H,
+                                             _dtype_code(q), _stream()), "based_decode_fused_rotary")
+        return y_lin, y_swa
     if isinstance(pos, torch.Tensor):   # per-sequence positions in device memory
         _check_pos(pos, B)
         _check(lib.based_decode_fused_ragged(_ptr(q), _ptr(k), _ptr(v), _ptr(y_lin), _ptr(state), int(bool(packed)),

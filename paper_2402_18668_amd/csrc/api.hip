@@ -479,6 +479,25 @@ int based_decode_fused_packed(const void *q, const void *k, const void *v, void 
                             PosArg{pos, nullptr, H, 0}, d_h, w, scale, B, H, dtype, 1, stream);
 }
 
+int based_decode_fused_rotary(const void *q, const void *k, const void *v, void *y_lin, void *state, int packed,
+                              int d_feat, int d_v, const void *swa_q, const void *swa_k, const void *swa_v,
+                              void *y_swa, void *ring, const float *table, int table_rows, int pos,
+                              const int *pos_per_seq, int d_h, int w, float scale, int B, int H, int dtype,
+                              void *stream)
+{
+    if (!ok_ptr(table) || table_rows < 1) return BASED_ERR_INVALID_ARG;
+    if (pos_per_seq) {
+        if (reinterpret_cast<uintptr_t>(pos_per_seq) & 3u) return BASED_ERR_INVALID_ARG;
+        return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
+                                PosArg{0, pos_per_seq, H, 0, table, table_rows}, d_h, w, scale, B, H, dtype,
+                                packed ? 1 : 0, stream);
+    }
+    if (pos < 1 || pos > table_rows) return BASED_ERR_INVALID_ARG;
+    return decode_fused_any(q, k, v, y_lin, state, d_feat, d_v, swa_q, swa_k, swa_v, y_swa, ring,
+                            PosArg{pos, nullptr, H, 0, table, table_rows}, d_h, w, scale, B, H, dtype, packed ? 1 : 0,
+                            stream);
+}
+
 int based_decode_fused_ragged(const void *q, const void *k, const void *v, void *y_lin, void *state,
                               int packed, int d_feat, int d_v, const void *swa_q, const void *swa_k,
                               const void *swa_v, void *y_swa, void *ring, const int *pos, int d_h, int w,

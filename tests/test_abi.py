@@ -123,6 +123,9 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_swa_decode_rotary(p, p, p, p, p, p, 4, 5, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_swa_decode_rotary(p, p, p, p, p, null, 4, 1, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_swa_decode_rotary(p, p, p, p, p, p, 4, 0, null, 1, 1, 64, 64, 0.125, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 16, 64, p, p, p, p, p, null, 4, 1, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 16, 64, p, p, p, p, p, p, 4, 5, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 8, 64, p, p, p, p, p, p, 4, 1, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_UNSUPPORTED
     # BaseConv gate
     assert lib.based_short_conv_gate(null, p, p, p, p, null, p, null, 1, 4, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_short_conv_gate(p, p, p, p, p, null, p, null, 1, 0, 64, 1, st) == based.ERR_INVALID_ARG

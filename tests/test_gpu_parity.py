@@ -1224,6 +1224,34 @@ def test_swa_rotary_prefill_then_decode(based, dtype, dh, w, ragged):
             based.positions_advance(pos)
 
 
+@pytest.mark.parametrize("dtype,packed,ragged", [("bf16", False, False), ("f32", False, True), ("bf16", True, True)])
+def test_decode_fused_rotary(based, dtype, packed, ragged):
+    """The fused step with a rotary window half: bit-equal to the two separate calls (linear-attention step,
+    rotary window step) on copies of the same state and ring, over several steps through the ring's wrap."""
+    wl = make_wl("decode_1p3b", d_v=64, d_h=64, w=16, dtype=dtype)
+    B, H, T, dp, dv, dh, w = 2, 3, 20, wl.d_feat, 64, 64, 16
+    dec = synth.decode_inputs(wl, T, units=B * H)
+    scale = 1.0 / math.sqrt(dh)
+    table = based.rotary_table(T, dh)
+    alloc = based.alloc_packed_state if packed else based.alloc_state
+    st_a, st_b = alloc(B, H, dp, dv), alloc(B, H, dp, dv)
+    ring_a = based.alloc_swa_ring(B, H, w, dh, TORCH_DTYPE[dtype])
+    ring_b = torch.zeros_like(ring_a)
+    pos = torch.ones((B,), dtype=torch.int32, device="cuda")
+    for t in range(T):
+        a = [up(dec[n][t], dtype, (B, H, d)) for n, d in (("q", dp), ("k", dp), ("v", dv), ("swa_q", dh), ("swa_k", dh), ("swa_v", dh))]
+        p_arg = pos if ragged else t + 1
+        yl, ys = based.decode_fused(a[0], a[1], a[2], st_a, a[3], a[4], a[5], ring_a, p_arg, w, scale, packed=packed,
+                                    rotary=table)
+        yl2 = based.decode_step(a[0], a[1], a[2], st_b, packed=packed)
+        ys2 = based.swa_decode(a[3], a[4], a[5], ring_b, p_arg, w, scale, rotary=table)
+        torch.cuda.synchronize()
+        assert torch.equal(yl, yl2) and torch.equal(ys, ys2), t
+        if ragged:
+            based.positions_advance(pos)
+    assert torch.equal(st_a, st_b) and torch.equal(ring_a, ring_b)
+
+
 # ------------------------------------------------------------------------------------------------
 # BaseConv gate
 # ------------------------------------------------------------------------------------------------
