@@ -42,10 +42,10 @@ PEAK_HBM_GBS = 8000.0
 # of those sources is the one recorded here, and as null after any change to them.
 MEASURED_TRAFFIC = {
     # key: (entry point, workload) -> (bytes per launch, source files the kernel is built from, their hash)
-    ("based_prefill", "prefill_1p3b"): (338596491, ("linattn_prefill_mfma.hip",), "e54e56a732a3"),
-    ("based_prefill", "prefill_360m"): (171984736, ("linattn_prefill_mfma.hip",), "e54e56a732a3"),
+    ("based_prefill", "prefill_1p3b"): (338596491, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
+    ("based_prefill", "prefill_360m"): (110228369, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
     ("based_swa_prefill", "prefill_1p3b"): (545564752, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
-    ("based_swa_prefill", "prefill_360m"): (142847571, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
+    ("based_swa_prefill", "prefill_360m"): (142845731, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
     ("based_decode_step", "decode_1p3b"): (579171327, ("decode.hip",), "6ccbc9b9aa4a"),
     ("based_decode_step_packed", "decode_1p3b"): (325378674, ("decode.hip",), "6ccbc9b9aa4a"),
 }
