@@ -170,6 +170,32 @@ def linattn_numerator(q, k, v, S=None) -> np.ndarray:
     return y
 
 
+def linattn_decay(q, k, v, gamma, S=None, z=None, gate=None):
+    """Taylor linear attention with a fixed decay rate per unit (appendix paragraph on decay: one rate per
+    head, the same for all inputs; the formula is the customary one of the works that paragraph cites):
+    the recurrence of Eq. 3 with the state multiplied by gamma at every token,
+        S_i = gamma S_{i-1} + phi(k_i) v_i^T,   z_i = gamma z_{i-1} + phi(k_i),   y_i = phi(q_i) S_i / phi(q_i).z_i,
+    token by token in fp64; ``gamma [U]``; ``gate [U, N]`` (optional) scales row i of y (the input-dependent
+    weight with which that paragraph combines the heads).  Returns ``(y, S_final, z_final)``."""
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64); v = np.asarray(v, dtype=np.float64)
+    U, N, dp, dv = _shapes(q, k, v)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    if gamma.shape != (U,):
+        raise ValueError("gamma [U]")
+    D = feature_dim(dp)
+    S = np.zeros((U, D, dv)) if S is None else np.array(S, dtype=np.float64)
+    z = np.zeros((U, D)) if z is None else np.array(z, dtype=np.float64)
+    pq, pk = feature_map(q), feature_map(k)
+    y = np.empty((U, N, dv))
+    for i in range(N):
+        S = gamma[:, None, None] * S + pk[:, i, :, None] * v[:, i, None, :]
+        z = gamma[:, None] * z + pk[:, i]
+        y[:, i] = np.einsum("uf,ufc->uc", pq[:, i], S) / np.einsum("uf,uf->u", pq[:, i], z)[:, None]
+    if gate is not None:
+        y = y * np.asarray(gate, dtype=np.float64)[:, :, None]
+    return y, S, z
+
+
 def swa(q, k, v, w: int, scale: float) -> np.ndarray:
     """Causal sliding-window softmax attention (Sec. 3.2 on Eq. 1), every row."""
     q, pq = _d(q); k, pk = _d(k); v, pv = _d(v)

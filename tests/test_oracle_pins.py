@@ -259,6 +259,46 @@ def test_numerator_only_pins():
     assert np.allclose(got[:, 0], (1 + x0 + x0 * x0 / 2)[:, None] * v[:, 0], rtol=1e-13, atol=1e-13)
 
 
+def test_decay_pins():
+    """The decayed recurrence against the weighted quadratic form written with pure-Python loops, against the
+    undecayed oracle at gamma = 1, an exponential moving average at q = 0, and continuation from a state."""
+    g = rng(12)
+    U, N, dp, dv = 2, 17, 3, 4
+    q = g.standard_normal((U, N, dp)); k = g.standard_normal((U, N, dp)); v = g.standard_normal((U, N, dv))
+    gamma = np.array([0.9, 0.5])
+    y, S, z = oracle.linattn_decay(q, k, v, gamma)
+    for u in range(U):
+        for i in range(N):
+            num = np.zeros(dv); den = 0.0
+            for j in range(i + 1):
+                x = float(q[u, i] @ k[u, j])
+                wgt = gamma[u] ** (i - j) * (1.0 + x + x * x / 2.0)
+                num += wgt * v[u, j]; den += wgt
+            assert np.allclose(y[u, i], num / den, rtol=1e-11, atol=1e-12)
+    # final state: decayed sums of phi(k) v^T and phi(k)
+    wts = gamma[:, None] ** (N - 1 - np.arange(N))[None, :]
+    assert np.allclose(S, np.einsum("uj,ujf,ujc->ufc", wts, np_phi(k), v), rtol=1e-11, atol=1e-12)
+    assert np.allclose(z, np.einsum("uj,ujf->uf", wts, np_phi(k)), rtol=1e-11, atol=1e-12)
+    # gamma = 1: the plain method (C oracle)
+    y1, S1, z1 = oracle.linattn_decay(q, k, v, np.ones(U))
+    yr, Sr, zr = oracle.linattn_recurrent(q, k, v)
+    assert np.allclose(y1, yr, rtol=1e-11, atol=1e-12) and np.allclose(S1, Sr, rtol=1e-11) and np.allclose(z1, zr, rtol=1e-11)
+    # q = 0: every weight is gamma^(i - j), an exponential moving average of v
+    y0, _, _ = oracle.linattn_decay(np.zeros_like(q), k, v, gamma)
+    for u in range(U):
+        acc = np.zeros(dv); cnt = 0.0
+        for i in range(N):
+            acc = gamma[u] * acc + v[u, i]; cnt = gamma[u] * cnt + 1.0
+            assert np.allclose(y0[u, i], acc / cnt, rtol=1e-12, atol=1e-13)
+    # continuation from the state of a prefix, and the gate
+    N1 = 6
+    _, Sa, za = oracle.linattn_decay(q[:, :N1], k[:, :N1], v[:, :N1], gamma)
+    gt = g.standard_normal((U, N - N1))
+    yb, Sb, zb = oracle.linattn_decay(q[:, N1:], k[:, N1:], v[:, N1:], gamma, Sa, za, gate=gt)
+    assert np.allclose(yb, y[:, N1:] * gt[:, :, None], rtol=1e-11, atol=1e-12)
+    assert np.allclose(Sb, S, rtol=1e-12) and np.allclose(zb, z, rtol=1e-12)
+
+
 @pytest.mark.parametrize("dp", [8, 24])
 def test_ablation_feature_dimensions(dp):
     """d' = 8 and 24 (the feature-dimension rows of the ablation table): the sizes the table prints in
