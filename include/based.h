@@ -195,6 +195,28 @@ int based_decode_step_numerator(const void *q, const void *k, const void *v, voi
                                 int H, int d_feat, int d_v, int dtype, void *stream);
 
 /*
+ * Decay variant (appendix paragraph on decay; the main experiments use none, the ablation table has a
+ * row for it).  That paragraph describes a fixed decay rate per head and a learned projection of the
+ * layer input to one scalar per (token, head) that weights the heads when they are combined; it gives
+ * no formula, so the recurrence is the customary one of the works it cites:
+ *   S_i = gamma_h S_{i-1} + phi(k_i) v_i^T,   z_i = gamma_h z_{i-1} + phi(k_i),
+ *   y_i = gate_i,h * phi(q_i) S_i / (phi(q_i).z_i)
+ * i.e. key j enters row i with weight gamma_h^(i-j) kappa(q_i, k_j), in numerator and denominator alike.
+ *
+ *   gamma  [H]        in, fp32, device: the rate of every head (1 = no decay)
+ *   gate   [B][N][H]  in, dtype, device, or NULL (based_decode_step_decay: [B][H]): scales the rows of y
+ * Everything else as based_prefill / based_decode_step (canonical state).  Both dtypes run on the fp32
+ * vector kernels (there is no matrix-core kernel for this variant), so based_prefill_decay needs a
+ * workspace of based_prefill_decay_workspace_bytes, which differs from based_prefill's for bf16.
+ */
+size_t based_prefill_decay_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype);
+int based_prefill_decay(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                        void *workspace, const float *gamma, const void *gate, int B, int H, int N, int d_feat,
+                        int d_v, int dtype, void *stream);
+int based_decode_step_decay(const void *q, const void *k, const void *v, void *y, void *state, const float *gamma,
+                            const void *gate, int B, int H, int d_feat, int d_v, int dtype, void *stream);
+
+/*
  * Sliding-window attention (Sec. 3.2): causal softmax attention (Eq. 1) in which query i sees
  * the w keys i-w+1 .. i (fewer at the start of the sequence), logits scale * q_i.k_j.
  *

@@ -34,6 +34,7 @@ EXPORTS = [
     "based_project_qkv", "based_project_out",
     "based_short_conv_gate", "based_rotary_table", "based_swa_prefill_rotary", "based_swa_decode_rotary",
     "based_decode_fused_rotary",
+    "based_prefill_decay_workspace_bytes", "based_prefill_decay", "based_decode_step_decay",
 ]
 
 
@@ -120,6 +121,12 @@ def _load() -> ctypes.CDLL:
     lib.based_project_out.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
     lib.based_decode_fused_rotary.restype = i
     lib.based_decode_fused_rotary.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp, vp, vp, vp, i, i, vp, i, i, f, i, i, i, vp]
+    lib.based_prefill_decay_workspace_bytes.restype = sz
+    lib.based_prefill_decay_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.based_prefill_decay.restype = i
+    lib.based_prefill_decay.argtypes = [vp, vp, vp, vp, vp, i, vp, vp, vp, i, i, i, i, i, i, vp]
+    lib.based_decode_step_decay.restype = i
+    lib.based_decode_step_decay.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     lib.based_short_conv_gate.restype = i
     lib.based_short_conv_gate.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
     lib.based_positions_advance.restype = i
@@ -273,6 +280,50 @@ def prefill(q, k, v, y=None, state=None, has_init=False, workspace=None, packed=
         fn, what = lib.based_prefill_numerator, "based_prefill_numerator"
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
               _ptr(workspace), B, H, N, dp, dv, code, _stream()), what)
+    return y
+
+
+def prefill_decay(q, k, v, gamma, y=None, state=None, has_init=False, gate=None):
+    """based_prefill_decay: per-head decay ``gamma [H]`` (fp32), optional ``gate [B,N,H]`` in the input dtype."""
+    _dev(q, k, v, y, state, gamma, gate)
+    B, H, N, dp = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:3]) != (B, H, N) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if gamma.dtype != torch.float32 or tuple(gamma.shape) != (H,) or not gamma.is_contiguous():
+        raise ValueError("gamma must be contiguous fp32 [H]")
+    if gate is not None and (gate.dtype != q.dtype or tuple(gate.shape) != (B, N, H) or not gate.is_contiguous()):
+        raise ValueError("gate must be contiguous [B, N, H] of the input dtype")
+    code = _dtype_code(q)
+    if y is None:
+        y = torch.empty_like(v)
+    if state is not None and (state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv)):
+        raise ValueError("state buffer too small or not fp32")
+    need = int(lib.based_prefill_decay_workspace_bytes(B, H, N, dp, dv, code))
+    workspace = torch.zeros((need + 3) // 4, dtype=torch.int32, device=q.device) if need else None
+    _check(lib.based_prefill_decay(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), int(bool(has_init)),
+                                   _ptr(workspace), _ptr(gamma), _ptr(gate), B, H, N, dp, dv, code, _stream()),
+           "based_prefill_decay")
+    return y
+
+
+def decode_step_decay(q, k, v, state, gamma, y=None, gate=None):
+    """based_decode_step_decay: per-head decay ``gamma [H]`` (fp32), optional ``gate [B,H]`` in the input dtype."""
+    _dev(q, k, v, y, state, gamma, gate)
+    B, H, dp = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or tuple(v.shape[:2]) != (B, H) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes / dtypes disagree")
+    if gamma.dtype != torch.float32 or tuple(gamma.shape) != (H,) or not gamma.is_contiguous():
+        raise ValueError("gamma must be contiguous fp32 [H]")
+    if gate is not None and (gate.dtype != q.dtype or tuple(gate.shape) != (B, H) or not gate.is_contiguous()):
+        raise ValueError("gate must be contiguous [B, H] of the input dtype")
+    if state.dtype != torch.float32 or state.numel() * 4 < state_bytes(B, H, dp, dv):
+        raise ValueError("state buffer too small or not fp32")
+    if y is None:
+        y = torch.empty_like(v)
+    _check(lib.based_decode_step_decay(_ptr(q), _ptr(k), _ptr(v), _ptr(y), _ptr(state), _ptr(gamma), _ptr(gate), B, H,
+                                       dp, dv, _dtype_code(q), _stream()), "based_decode_step_decay")
     return y
 
 

@@ -238,7 +238,7 @@ int based_decode_step(const void *q, const void *k, const void *v, void *y, void
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
-                                        dtype, 0, 0, (hipStream_t)stream));
+                                        dtype, 0, 0, nullptr, nullptr, 1, (hipStream_t)stream));
 }
 
 int based_decode_step_numerator(const void *q, const void *k, const void *v, void *y, void *state, int B,
@@ -249,7 +249,45 @@ int based_decode_step_numerator(const void *q, const void *k, const void *v, voi
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v,
-                                        dtype, 0, 1, (hipStream_t)stream));
+                                        dtype, 0, 1, nullptr, nullptr, 1, (hipStream_t)stream));
+}
+
+size_t based_prefill_decay_workspace_bytes(int B, int H, int N, int d_feat, int d_v, int dtype)
+{
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype) || !ok_counts(B, H, N)) return 0;
+    const size_t scratch_bytes = prefill_ref_workspace_bytes(B * H, N, d_feat, d_v);
+    return scratch_bytes ? kWsHeader + scratch_bytes : 0;
+}
+
+int based_prefill_decay(const void *q, const void *k, const void *v, void *y, void *state, int has_init,
+                        void *workspace, const float *gamma, const void *gate, int B, int H, int N, int d_feat,
+                        int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, N)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y)) return BASED_ERR_INVALID_ARG;
+    if (!gamma || (reinterpret_cast<uintptr_t>(gamma) & 3u)) return BASED_ERR_INVALID_ARG;
+    if (gate && (reinterpret_cast<uintptr_t>(gate) & 3u)) return BASED_ERR_INVALID_ARG;
+    if (state && !aligned16(state)) return BASED_ERR_INVALID_ARG;
+    if (has_init && !state) return BASED_ERR_INVALID_ARG;
+    const int U = B * H;
+    const size_t need = prefill_ref_workspace_bytes(U, N, d_feat, d_v);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return BASED_ERR_INVALID_ARG;
+    void *inner = workspace ? static_cast<char *>(workspace) + kWsHeader : nullptr;
+    return status_of(launch_prefill_ref_decay(q, k, v, y, static_cast<float *>(state), has_init ? 1 : 0, inner, gamma,
+                                              gate, H, U, N, d_feat, d_v, dtype, (hipStream_t)stream));
+}
+
+int based_decode_step_decay(const void *q, const void *k, const void *v, void *y, void *state, const float *gamma,
+                            const void *gate, int B, int H, int d_feat, int d_v, int dtype, void *stream)
+{
+    if (!ok_counts(B, H, 1)) return BASED_ERR_INVALID_ARG;
+    if (!ok_lin_dims(d_feat, d_v) || !ok_dtype(dtype)) return BASED_ERR_UNSUPPORTED;
+    if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(state)) return BASED_ERR_INVALID_ARG;
+    if (!gamma || (reinterpret_cast<uintptr_t>(gamma) & 3u)) return BASED_ERR_INVALID_ARG;
+    if (gate && (reinterpret_cast<uintptr_t>(gate) & 3u)) return BASED_ERR_INVALID_ARG;
+    return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(state), B * H, d_feat, d_v, dtype, 0, 0,
+                                        gamma, gate, H, (hipStream_t)stream));
 }
 
 int based_packed_feature_dim(int d_feat) { return d_feat >= 1 ? packed_feature_dim(d_feat) : 0; }
@@ -293,7 +331,7 @@ int based_decode_step_packed(const void *q, const void *k, const void *v, void *
     if (!ok_ptr(q) || !ok_ptr(k) || !ok_ptr(v) || !ok_ptr(y) || !ok_ptr(packed))
         return BASED_ERR_INVALID_ARG;
     return status_of(launch_decode_step(q, k, v, y, static_cast<float *>(packed), B * H, d_feat, d_v,
-                                        dtype, 1, 0, (hipStream_t)stream));
+                                        dtype, 1, 0, nullptr, nullptr, 1, (hipStream_t)stream));
 }
 
 size_t based_swa_ring_bytes(int B, int H, int w, int d_h, int dtype)

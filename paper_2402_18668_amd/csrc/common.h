@@ -104,9 +104,14 @@ hipError_t launch_prefill_mfma32(const void *q, const void *k, const void *v, vo
                                  int has_init, int packed_state, void *workspace, int U, int N, int dp, int dv,
                                  hipStream_t s);
 // numerator_only != 0: y is phi(q) S without the division by phi(q).z
+// gamma [H] (device, or null): per-head decay of the state; gate [U] in the dtype of y (or null): scales y
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
                               int U, int dp, int dv, int dtype, int packed, int numerator_only,
-                              hipStream_t s);
+                              const float *gamma, const void *gate, int H, hipStream_t s);
+// the fp32 vector kernel with a per-head decay gamma [H] and an optional gate [B][N][H] in the dtype of y
+hipError_t launch_prefill_ref_decay(const void *q, const void *k, const void *v, void *y, float *state,
+                                    int has_init, void *workspace, const float *gamma, const void *gate, int H,
+                                    int U, int N, int dp, int dv, int dtype, hipStream_t s);
 // rot (everywhere below): the rotary table, (cos, sin) per [position][pair], row 0 = the first token of
 // the call (prefill) or position 0 of the sequence (decode); null = no rotation
 hipError_t launch_rotary_table(float *table, int pos0, int N, int dh, float base, hipStream_t s);

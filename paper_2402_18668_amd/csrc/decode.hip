@@ -36,7 +36,7 @@ template <int DP, int DV, typename T, bool PACKED>
 __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const T *__restrict__ k,
                                                  const T *__restrict__ v, T *__restrict__ y,
                                                  float *__restrict__ state, int u,
-                                                 bool numerator_only = false)
+                                                 bool numerator_only = false, float gm = 1.f, float gate = 1.f)
 {
     constexpr int D = PACKED ? packed_feature_dim(DP) : feature_dim(DP);
     constexpr int NT = kDecodeThreads;
@@ -115,7 +115,7 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
     for (int i = 0; i < ZPT; ++i) {
         const int f = tid + i * NT;
         if (f < D) {
-            const float zn = zv[i] + pk[f];
+            const float zn = fmaf(gm, zv[i], pk[f]);   // gm: the decay rate (1 without decay: exact)
             zu[f] = zn;
             dpart = fmaf(pq[f], zn, dpart);
         }
@@ -132,8 +132,8 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
         for (int j = 0; j < UNR; ++j) {
             const int f = min((st0 + j) * RPS + row, DPAD - 1);   // features D .. DPAD - 1 are zero
             const float a = pk[f], b = pq[f];
-            cur[j].x = fmaf(a, v4.x, cur[j].x); cur[j].y = fmaf(a, v4.y, cur[j].y);
-            cur[j].z = fmaf(a, v4.z, cur[j].z); cur[j].w = fmaf(a, v4.w, cur[j].w);
+            cur[j].x = fmaf(a, v4.x, gm * cur[j].x); cur[j].y = fmaf(a, v4.y, gm * cur[j].y);
+            cur[j].z = fmaf(a, v4.z, gm * cur[j].z); cur[j].w = fmaf(a, v4.w, gm * cur[j].w);
             acc.x = fmaf(b, cur[j].x, acc.x); acc.y = fmaf(b, cur[j].y, acc.y);
             acc.z = fmaf(b, cur[j].z, acc.z); acc.w = fmaf(b, cur[j].w, acc.w);
         }
@@ -181,7 +181,7 @@ __device__ __forceinline__ void decode_step_body(const T *__restrict__ q, const 
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < NT / 64; ++w) { num += yred[w][tid]; den += dred[w]; }
-        y[(size_t)u * DV + tid] = from_f32<T>(numerator_only ? num : num / den);
+        y[(size_t)u * DV + tid] = from_f32<T>((numerator_only ? num : num / den) * gate);
     }
 }
 
@@ -347,11 +347,13 @@ __device__ __forceinline__ void swa_decode_body(const T *__restrict__ q, const T
 template <int DP, int DV, typename T, bool PACKED>
 __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(const T *q, const T *k,
                                                                      const T *v, T *y, float *state,
-                                                                     int reverse, int numerator_only)
+                                                                     int reverse, int numerator_only,
+                                                                     const float *gamma, const T *gate, int H)
 {
-    decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state,
-                                        reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x,
-                                        numerator_only != 0);
+    const int u = reverse ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    // decay variant: a rate per head, an optional gate per (sequence, head)
+    decode_step_body<DP, DV, T, PACKED>(q, k, v, y, state, u, numerator_only != 0, gamma ? gamma[u % H] : 1.f,
+                                        gate ? to_f32(gate[u]) : 1.f);
 }
 
 template <int DH, int W, typename T>
@@ -434,24 +436,26 @@ template <int DP, int DV> static size_t state_bytes_of(int U, int packed)
 
 template <int DP, int DV, typename T>
 static void step_pick(const void *q, const void *k, const void *v, void *y, float *state, int U,
-                      int packed, int numer, hipStream_t s)
+                      int packed, int numer, const float *gamma, const void *gate, int H, hipStream_t s)
 {
     const int reverse = next_direction(state_bytes_of<DP, DV>(U, packed));
     if (packed)
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, true>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer, gamma,
+                           (const T *)gate, H);
     else
         hipLaunchKernelGGL((decode_step_kernel<DP, DV, T, false>), dim3(U), dim3(kDecodeThreads), 0, s,
-                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer);
+                           (const T *)q, (const T *)k, (const T *)v, (T *)y, state, reverse, numer, gamma,
+                           (const T *)gate, H);
 }
 
 hipError_t launch_decode_step(const void *q, const void *k, const void *v, void *y, float *state,
                               int U, int dp, int dv, int dtype, int packed, int numerator_only,
-                              hipStream_t s)
+                              const float *gamma, const void *gate, int H, hipStream_t s)
 {
 #define CALL_LIN(DP_, DV_)                                                                        \
-    if (dtype == BASED_F32) step_pick<DP_, DV_, float>(q, k, v, y, state, U, packed, numerator_only, s); \
-    else step_pick<DP_, DV_, bf16_t>(q, k, v, y, state, U, packed, numerator_only, s)
+    if (dtype == BASED_F32) step_pick<DP_, DV_, float>(q, k, v, y, state, U, packed, numerator_only, gamma, gate, H, s); \
+    else step_pick<DP_, DV_, bf16_t>(q, k, v, y, state, U, packed, numerator_only, gamma, gate, H, s)
     if (dp == 8 || dp == 24) BASED_PICK2(dp, 8, 24, dv, 64, 128, CALL_LIN);
     else BASED_PICK2(dp, 16, 32, dv, 64, 128, CALL_LIN);
 #undef CALL_LIN

@@ -35,15 +35,23 @@ __host__ __device__ constexpr size_t ref_entry_floats(int dp)
     return ((size_t)feature_dim(dp) * 65 + 63) / 64 * 64;
 }
 
+// Decay variant (appendix paragraph on decay): a fixed rate per head multiplies the state at every token,
+// S_i = gamma S_{i-1} + phi(k_i) v_i^T, z likewise; an optional gate [B][N][H] scales row i of y.
+struct DecayArg {
+    const float *gamma;   // [H], device; null: no decay
+    const void *gate;     // [B][N][H] in the dtype of y, device; null: none
+    int H;
+};
+
 // INCREMENT: state increment of the segment only (no readout), written to workspace entry 1 + seg.
 // Otherwise: the full pass over the segment; with G > 1 it starts from workspace entry seg.
-template <int DP, int NT, typename T, bool INCREMENT>
+template <int DP, int NT, typename T, bool INCREMENT, bool DECAY>
 __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q,
                                                          const T *__restrict__ k,
                                                          const T *__restrict__ v,
                                                          T *__restrict__ y, float *state,
                                                          int has_init, int N, int dv, float *ws,
-                                                         int seg_len, int G)
+                                                         int seg_len, int G, DecayArg dk)
 {
     using C = RefCfg<DP, NT>;
     constexpr int D = C::D, RG = C::RG, FPT = C::FPT, DPAD = C::DPAD, TB = C::TB, ZPT = C::ZPT;
@@ -71,6 +79,9 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
     float *Su = state ? state + (size_t)u * state_stride(DP, dv) : nullptr;
     float *zu = Su ? Su + (size_t)D * dv : nullptr;
 
+    const float gm = DECAY ? dk.gamma[u % dk.H] : 1.f;
+    const T *gate = DECAY && dk.gate ? static_cast<const T *>(dk.gate) + (size_t)(u / dk.H) * N * dk.H + (u % dk.H)
+                                     : nullptr;
     float s[FPT], zreg[ZPT];
     if (!INCREMENT && G > 1) {
         // state at the start of this segment, prepared by the scan launch
@@ -136,12 +147,17 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
 #pragma unroll
         for (int t = 0; t < TB; ++t) {
             const float vt = vs[t][c];
+            // (a token past the end of the segment must leave the state as it is: no decay for it either)
+            const float gt = (DECAY && tok0 + t < tok_end) ? gm : 1.f;
             const float4 *pk4 = reinterpret_cast<const float4 *>(&phik[t][r * FPT]);
             const float4 *pq4 = reinterpret_cast<const float4 *>(&phiq[t][r * FPT]);
             float num = 0.f;
 #pragma unroll
             for (int i = 0; i < FPT / 4; ++i) {
                 const float4 a = pk4[i], b = pq4[i];
+                if (DECAY) {
+                    s[4 * i + 0] *= gt; s[4 * i + 1] *= gt; s[4 * i + 2] *= gt; s[4 * i + 3] *= gt;
+                }
                 s[4 * i + 0] = fmaf(a.x, vt, s[4 * i + 0]); num = fmaf(b.x, s[4 * i + 0], num);
                 s[4 * i + 1] = fmaf(a.y, vt, s[4 * i + 1]); num = fmaf(b.y, s[4 * i + 1], num);
                 s[4 * i + 2] = fmaf(a.z, vt, s[4 * i + 2]); num = fmaf(b.z, s[4 * i + 2], num);
@@ -154,7 +170,7 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
 #pragma unroll
                 for (int i = 0; i < ZPT; ++i) {
                     const int f = tid + NT * i;
-                    if (f < DPAD) zreg[i] += phik[t][f];
+                    if (f < DPAD) zreg[i] = (DECAY ? gt * zreg[i] : zreg[i]) + phik[t][f];
                 }
                 continue;
             }
@@ -164,7 +180,7 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
             for (int i = 0; i < ZPT; ++i) {
                 const int f = tid + NT * i;
                 if (f < DPAD) {
-                    zreg[i] += phik[t][f];
+                    zreg[i] = (DECAY ? gt * zreg[i] : zreg[i]) + phik[t][f];
                     dpart = fmaf(phiq[t][f], zreg[i], dpart);
                 }
             }
@@ -179,7 +195,9 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
                 float num = 0.f, den = 0.f;
 #pragma unroll
                 for (int g = 0; g < RG; ++g) { num += red[t][g][cc]; den += redd[t][g]; }
-                yu[(size_t)(tok0 + t) * dv + cc] = from_f32<T>(numerator_only ? num : num / den);
+                float o = numerator_only ? num : num / den;
+                if (DECAY && gate) o *= to_f32(gate[(size_t)(tok0 + t) * dk.H]);
+                yu[(size_t)(tok0 + t) * dv + cc] = from_f32<T>(o);
             }
         }
         __syncthreads();
@@ -213,10 +231,11 @@ __global__ __launch_bounds__(NT) void prefill_ref_kernel(const T *__restrict__ q
     }
 }
 
-// Entry 0 <- the caller's initial state (or zero); entry g <- entry g - 1 + increment g - 1.
+// Entry 0 <- the caller's initial state (or zero); entry g <- gamma^(tokens of segment g - 1) x entry g - 1 +
+// increment g - 1 (gamma = 1 without decay).
 // grid: (unit slices, blocks over the elements of an entry)
 __global__ void prefill_ref_scan_kernel(float *ws, const float *state, int has_init, int dp, int dv,
-                                        int G)
+                                        int G, int seg_len, DecayArg dk)
 {
     const int D = feature_dim(dp), slices = dv / 64;
     const int us = blockIdx.x, u = us / slices, col0 = (us % slices) * 64;
@@ -224,12 +243,13 @@ __global__ void prefill_ref_scan_kernel(float *ws, const float *state, int has_i
     float *e = ws + (size_t)us * G * E;
     const float *Su = state ? state + (size_t)u * state_stride(dp, dv) : nullptr;
     const int nS = D * 64;
+    const float gseg = dk.gamma ? powf(dk.gamma[u % dk.H], (float)seg_len) : 1.f;   // every segment but the last is seg_len long
     for (int i = blockIdx.y * blockDim.x + threadIdx.x; i < nS + D; i += gridDim.y * blockDim.x) {
         float acc = 0.f;
         if (has_init) acc = i < nS ? Su[(size_t)(i / 64) * dv + col0 + (i % 64)] : Su[(size_t)D * dv + (i - nS)];
         e[i] = acc;
         for (int g = 1; g < G; ++g) {
-            acc += e[(size_t)g * E + i];
+            acc = fmaf(acc, gseg, e[(size_t)g * E + i]);
             e[(size_t)g * E + i] = acc;
         }
     }
@@ -257,9 +277,9 @@ size_t prefill_ref_workspace_bytes(int U, int N, int dp, int dv)
     return G > 1 ? (size_t)U * (dv / 64) * G * ref_entry_floats(dp) * sizeof(float) : 0;
 }
 
-template <int DP, int NT, typename T>
+template <int DP, int NT, typename T, bool DECAY>
 static hipError_t launch_ref(const void *q, const void *k, const void *v, void *y, float *state,
-                             int has_init, void *workspace, int U, int N, int dv, hipStream_t s)
+                             int has_init, void *workspace, int U, int N, int dv, DecayArg dk, hipStream_t s)
 {
     const int groups = U * (dv / 64);
     int G = ref_segments(U, N, dv);
@@ -268,41 +288,49 @@ static hipError_t launch_ref(const void *q, const void *k, const void *v, void *
     float *ws = static_cast<float *>(workspace);
     hipError_t e;
     if (G > 1) {
-        hipLaunchKernelGGL((prefill_ref_kernel<DP, NT, T, true>), dim3((unsigned)(groups * (G - 1))), dim3(NT),
+        hipLaunchKernelGGL((prefill_ref_kernel<DP, NT, T, true, DECAY>), dim3((unsigned)(groups * (G - 1))), dim3(NT),
                            0, s, (const T *)q, (const T *)k, (const T *)v, (T *)y, state, has_init, N, dv, ws,
-                           seg_len, G);
+                           seg_len, G, dk);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_ref_scan_kernel, dim3((unsigned)groups, 32), dim3(256), 0, s, ws, state, has_init & 1,
-                           DP, dv, G);
+                           DP, dv, G, seg_len, dk);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((prefill_ref_kernel<DP, NT, T, false>), dim3((unsigned)(groups * G)), dim3(NT), 0, s,
-                       (const T *)q, (const T *)k, (const T *)v, (T *)y, state, has_init, N, dv, ws, seg_len, G);
+    hipLaunchKernelGGL((prefill_ref_kernel<DP, NT, T, false, DECAY>), dim3((unsigned)(groups * G)), dim3(NT), 0, s,
+                       (const T *)q, (const T *)k, (const T *)v, (T *)y, state, has_init, N, dv, ws, seg_len, G, dk);
     return hipGetLastError();
+}
+
+template <bool DECAY>
+static hipError_t launch_ref_any(const void *q, const void *k, const void *v, void *y, float *state, int has_init,
+                                 void *workspace, int U, int N, int dp, int dv, int dtype, DecayArg dk,
+                                 hipStream_t s)
+{
+#define REF_CASE(DP_, NT_)                                                                                      \
+    if (dp == DP_)                                                                                              \
+        return dtype == BASED_F32                                                                               \
+                   ? launch_ref<DP_, NT_, float, DECAY>(q, k, v, y, state, has_init, workspace, U, N, dv, dk, s) \
+                   : launch_ref<DP_, NT_, bf16_t, DECAY>(q, k, v, y, state, has_init, workspace, U, N, dv, dk, s)
+    REF_CASE(8, 256);
+    REF_CASE(16, 256);
+    REF_CASE(24, 512);
+    REF_CASE(32, 512);
+#undef REF_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_prefill_ref(const void *q, const void *k, const void *v, void *y, float *state,
                               int has_init, void *workspace, int U, int N, int dp, int dv, int dtype,
                               hipStream_t s)
 {
-    if (dp == 8) {
-        return dtype == BASED_F32
-                   ? launch_ref<8, 256, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
-                   : launch_ref<8, 256, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
-    }
-    if (dp == 16) {
-        return dtype == BASED_F32
-                   ? launch_ref<16, 256, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
-                   : launch_ref<16, 256, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
-    }
-    if (dp == 24) {
-        return dtype == BASED_F32
-                   ? launch_ref<24, 512, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
-                   : launch_ref<24, 512, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
-    }
-    return dtype == BASED_F32
-               ? launch_ref<32, 512, float>(q, k, v, y, state, has_init, workspace, U, N, dv, s)
-               : launch_ref<32, 512, bf16_t>(q, k, v, y, state, has_init, workspace, U, N, dv, s);
+    return launch_ref_any<false>(q, k, v, y, state, has_init, workspace, U, N, dp, dv, dtype, DecayArg{nullptr, nullptr, 1}, s);
+}
+
+hipError_t launch_prefill_ref_decay(const void *q, const void *k, const void *v, void *y, float *state,
+                                    int has_init, void *workspace, const float *gamma, const void *gate, int H,
+                                    int U, int N, int dp, int dv, int dtype, hipStream_t s)
+{
+    return launch_ref_any<true>(q, k, v, y, state, has_init, workspace, U, N, dp, dv, dtype, DecayArg{gamma, gate, H}, s);
 }
 
 }  // namespace based

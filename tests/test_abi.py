@@ -126,6 +126,12 @@ def test_bad_arguments_are_rejected_before_launch(based):
     assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 16, 64, p, p, p, p, p, null, 4, 1, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 16, 64, p, p, p, p, p, p, 4, 5, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_decode_fused_rotary(p, p, p, p, p, 0, 8, 64, p, p, p, p, p, p, 4, 1, null, 64, 64, 0.125, 1, 1, 1, st) == based.ERR_UNSUPPORTED
+    # decay variant
+    assert lib.based_prefill_decay(p, p, p, p, null, 0, null, null, null, 1, 1, 8, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill_decay(p, p, p, p, null, 0, null, p, null, 1, 1, 8, 20, 64, 1, st) == based.ERR_UNSUPPORTED
+    assert lib.based_decode_step_decay(p, p, p, p, p, null, null, 1, 1, 16, 64, 1, st) == based.ERR_INVALID_ARG
+    assert lib.based_prefill_decay_workspace_bytes(1, 1, 8, 16, 64, 1) == 0
+    assert lib.based_prefill_decay_workspace_bytes(1, 2, 4096, 16, 64, 1) > 0
     # BaseConv gate
     assert lib.based_short_conv_gate(null, p, p, p, p, null, p, null, 1, 4, 64, 1, st) == based.ERR_INVALID_ARG
     assert lib.based_short_conv_gate(p, p, p, p, p, null, p, null, 1, 0, 64, 1, st) == based.ERR_INVALID_ARG

@@ -271,6 +271,70 @@ def test_decode_steps_numerator_only(based, dtype, dp, dv):
 
 
 # ------------------------------------------------------------------------------------------------
+# decay variant
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dp,dv,N,N1,with_gate", [("f32", 16, 64, 300, 130, False), ("bf16", 16, 128, 300, 130, True),
+                                                         ("f32", 16, 64, 1400, 1100, True), ("bf16", 32, 64, 700, 64, False),
+                                                         ("f32", 8, 64, 1, 0, False)])
+def test_prefill_and_decode_with_decay(based, dtype, dp, dv, N, N1, with_gate):
+    """based_prefill_decay over a split sequence (second part from the state of the first; long enough to be
+    cut into segments in one case), then based_decode_step_decay token by token, against the oracle's decayed
+    recurrence; a per-head rate, heads cycling over the units."""
+    wl = make_wl("prefill_360m", d_feat=dp, d_v=dv, dtype=dtype)
+    B, H, T = 2, 3, 3
+    U = B * H
+    q, k, v = lin_case(wl, B, H, N + T)
+    gam_h = np.array([0.999, 0.97, 0.9], dtype=np.float32)
+    gamma_u = np.tile(gam_h.astype(np.float64), B)
+    gate = synth.round_to(synth.normal(4242, (B, N + T, H), 1.0), dtype) if with_gate else None
+    gate_u = None if gate is None else np.ascontiguousarray(gate.transpose(0, 2, 1)).reshape(U, N + T).astype(np.float64)
+    want, Sw, zw = oracle.linattn_decay(q, k, v, gamma_u, gate=gate_u)
+    tg = up(gam_h, "f32")
+
+    def part(a, lo, hi, d):
+        return up(a[:, lo:hi], dtype, (B, H, hi - lo, d))
+
+    def gpart(lo, hi):
+        return None if gate is None else up(gate[:, lo:hi], dtype)
+
+    state = based.alloc_state(B, H, dp, dv)
+    has = False
+    if N1 > 0:
+        y1 = based.prefill_decay(part(q, 0, N1, dp), part(k, 0, N1, dp), part(v, 0, N1, dv), tg, state=state, gate=gpart(0, N1))
+        check_close(rows(down(y1).reshape(U, N1, dv)), rows(want[:, :N1]), TOL[dtype], "decay prefill part 1")
+        has = True
+    y2 = based.prefill_decay(part(q, N1, N, dp), part(k, N1, N, dp), part(v, N1, N, dv), tg, state=state, has_init=has,
+                             gate=gpart(N1, N))
+    torch.cuda.synchronize()
+    check_close(rows(down(y2).reshape(U, N - N1, dv)), rows(want[:, N1:N]), TOL[dtype], "decay prefill part 2")
+    for t in range(N, N + T):
+        gt = None if gate is None else up(gate[:, t], dtype)
+        y = based.decode_step_decay(up(q[:, t], dtype, (B, H, dp)), up(k[:, t], dtype, (B, H, dp)),
+                                    up(v[:, t], dtype, (B, H, dv)), state, tg, gate=gt)
+        check_close(down(y).reshape(U, dv), want[:, t], TOL[dtype], f"decay decode token {t}")
+    Sg, zg = based.state_export(state, B, H, dp, dv)
+    check_close(down(Sg).reshape(Sw.shape), Sw, TOL[dtype], "decay final S")
+    check_close(down(zg).reshape(zw.shape), zw, TOL[dtype], "decay final z")
+
+
+def test_decay_of_one_is_the_plain_method(based):
+    """gamma = 1 and no gate: bit-identical to based_prefill on the fp32 path, and to based_decode_step."""
+    wl = make_wl("tiny")
+    B, H, N = 1, 2, 150
+    q, k, v = lin_case(wl, B, H, N + 1)
+    tq, tk, tv = (up(a[:, :N], "f32", (B, H, N, d)) for a, d in ((q, 16), (k, 16), (v, 64)))
+    ones = torch.ones((H,), dtype=torch.float32, device="cuda")
+    s1, s2 = based.alloc_state(B, H, 16, 64), based.alloc_state(B, H, 16, 64)
+    y1 = based.prefill(tq, tk, tv, state=s1)
+    y2 = based.prefill_decay(tq, tk, tv, ones, state=s2)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(s1, s2)
+    a = [up(x[:, N], "f32", (B, H, d)) for x, d in ((q, 16), (k, 16), (v, 64))]
+    assert torch.equal(based.decode_step(a[0], a[1], a[2], s1), based.decode_step_decay(a[0], a[1], a[2], s2, ones))
+    assert torch.equal(s1, s2)
+
+
+# ------------------------------------------------------------------------------------------------
 # sliding-window attention
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
