@@ -46,8 +46,8 @@ MEASURED_TRAFFIC = {
     ("based_prefill", "prefill_360m"): (110228369, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
     ("based_swa_prefill", "prefill_1p3b"): (545564752, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
     ("based_swa_prefill", "prefill_360m"): (142845731, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
-    ("based_decode_step", "decode_1p3b"): (579171327, ("decode.hip",), "6ccbc9b9aa4a"),
-    ("based_decode_step_packed", "decode_1p3b"): (325378674, ("decode.hip",), "6ccbc9b9aa4a"),
+    ("based_decode_step", "decode_1p3b"): (579192285, ("decode.hip",), "0e4b071cdd26"),
+    ("based_decode_step_packed", "decode_1p3b"): (325422966, ("decode.hip",), "0e4b071cdd26"),
 }
 
 
