@@ -19,6 +19,7 @@ SOURCES = [
     "linattn_prefill_mfma32.hip",
     "swa_prefill_ref.hip",
     "swa_prefill_mfma.hip",
+    "swa_prefill_mfma16.hip",
     "linear_mfma.hip",
     "baseconv.hip",
     "rotary.hip",

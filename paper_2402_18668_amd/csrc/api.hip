@@ -351,7 +351,10 @@ static int swa_prefill_any(const void *q, const void *k, const void *v, void *y,
     hipError_t e;
     // the matrix-core kernel takes the row maximum of the unscaled scores, which is the maximum of
     // the scaled ones only for a positive scale; anything else goes to the vector-ALU kernel
-    if (swa_prefill_mfma_supported(d_h, w, dtype, rot != nullptr) && scale > 0.f) {
+    if (!rot && swa_prefill_mfma16_supported(d_h, w, dtype) && scale > 0.f) {
+        // (the tiling of 16 queries to a wave, for the sizes where it is the faster one; fills the ring too)
+        e = launch_swa_prefill_mfma16(q, k, v, y, ring, U, N, d_h, w, scale, (hipStream_t)stream);
+    } else if (swa_prefill_mfma_supported(d_h, w, dtype, rot != nullptr) && scale > 0.f) {
         // this kernel also fills the ring
         e = launch_swa_prefill_mfma(q, k, v, y, ring, rot, U, N, d_h, w, scale, (hipStream_t)stream);
     } else {

@@ -120,6 +120,10 @@ hipError_t launch_swa_prefill_ref(const void *q, const void *k, const void *v, v
 bool swa_prefill_mfma_supported(int dh, int w, int dtype, int rotary);
 hipError_t launch_swa_prefill_mfma(const void *q, const void *k, const void *v, void *y, void *ring,
                                    const float *rot, int U, int N, int dh, int w, float scale, hipStream_t s);
+// the same with 16 queries to a wave (two workgroups per CU); no rotary variant
+bool swa_prefill_mfma16_supported(int dh, int w, int dtype);
+hipError_t launch_swa_prefill_mfma16(const void *q, const void *k, const void *v, void *y, void *ring, int U, int N,
+                                     int dh, int w, float scale, hipStream_t s);
 hipError_t launch_swa_ring_fill(const void *k, const void *v, void *ring, const float *rot, int U, int N, int dh,
                                 int w, int dtype, hipStream_t s);
 // Position of the decoded token: one value for every sequence, or (per_seq != NULL) one per batch

@@ -344,7 +344,12 @@ def test_decay_of_one_is_the_plain_method(based):
                                         # the small windows (the paper's 1.4B model uses 16)
                                         (64, 16, 2, 2, 300), (128, 16, 1, 2, 150), (64, 32, 1, 2, 333),
                                         (128, 32, 1, 1, 260), (64, 16, 1, 1, 1), (128, 16, 1, 2, 15),
-                                        (64, 16, 1, 1, 16), (64, 16, 1, 2, 17), (64, 32, 1, 1, 33)])
+                                        (64, 16, 1, 1, 16), (64, 16, 1, 2, 17), (64, 32, 1, 1, 33),
+                                        # d_h 128 with window 64 (bf16: 16 queries to a wave, steps of 64):
+                                        # one token, less than a tile, a step and one more, several
+                                        # segments with a ragged last step
+                                        (128, 64, 1, 1, 1), (128, 64, 1, 2, 17), (128, 64, 3, 1, 129),
+                                        (128, 64, 1, 1, 65), (128, 64, 2, 3, 1000)])
 def test_swa_prefill(based, dtype, dh, w, B, H, N):
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
     q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
