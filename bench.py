@@ -141,7 +141,7 @@ class StepRunner:
         based.decode_fused(s["dq"], s["dk"], s["dv"], s["state"], s["dsq"], s["dsk"], s["dsv"], s["ring"],
                            wl.N + 1, wl.w, self.scale, y_lin=s["yl"], y_swa=s["ys"])
 
-    def run(self, steps: int, warmup: int, ev_every: int = 2):
+    def run(self, steps: int, warmup: int, ev_every: int = 4):
         """Warm up, then time exactly `steps` steps; events bracket the two prefill calls on every
         ev_every-th timed step (an event is a marker between two launches that costs about 3 us of GPU
         time, which the step time includes)."""
