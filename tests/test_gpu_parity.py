@@ -679,7 +679,9 @@ def test_decode_state_beyond_the_cache(based):
 
 
 @pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100), (128, 16, 1300),
-                                    (64, 32, 1100)])
+                                    (64, 32, 1100),
+                                    # 16 queries to a wave: many short segments, a last step of 20 and of 63 queries
+                                    (128, 64, 1300), (128, 64, 2047)])
 def test_swa_prefill_segmented(based, dh, w, N):
     """Sequences long enough to be cut into segments (ragged last step), every element checked."""
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype="bf16")
