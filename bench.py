@@ -42,9 +42,9 @@ PEAK_HBM_GBS = 8000.0
 # of those sources is the one recorded here, and as null after any change to them.
 MEASURED_TRAFFIC = {
     # key: (entry point, workload) -> (bytes per launch, source files the kernel is built from, their hash)
-    ("based_prefill", "prefill_1p3b"): (338599323, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
+    ("based_prefill", "prefill_1p3b"): (338599539, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
     ("based_prefill", "prefill_360m"): (110228369, ("linattn_prefill_mfma.hip",), "a11fb2150fe2"),
-    ("based_swa_prefill", "prefill_1p3b"): (553816885, ("swa_prefill_mfma16.hip",), "4c82a433e981"),
+    ("based_swa_prefill", "prefill_1p3b"): (553817107, ("swa_prefill_mfma16.hip",), "6d81285cd196"),
     ("based_swa_prefill", "prefill_360m"): (142845731, ("swa_prefill_mfma.hip",), "268b1a0162b0"),
     ("based_decode_step", "decode_1p3b"): (579192285, ("decode.hip",), "0e4b071cdd26"),
     ("based_decode_step_packed", "decode_1p3b"): (325422966, ("decode.hip",), "0e4b071cdd26"),
@@ -185,7 +185,7 @@ class StepRunner:
         swa_bytes = 4 * dh * 2 * U * N
         gbs = swa_bytes / (swa_ms * 1e-3) / 1e9
         swa = {
-            "kernel": "based_swa_prefill (" + ("swa_prefill_mfma16_kernel: 16 queries to a wave" if (dh, wl.w) == (128, 64)
+            "kernel": "based_swa_prefill (" + ("swa_prefill_mfma16_kernel: 16 queries to a wave" if dh == 128 and wl.w in (32, 64)
                                                else "swa_prefill_mfma_kernel: 32 queries to a wave") + ")", "bound": "hbm", "achieved": round(gbs, 1),
             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_ms": round(swa_ms, 4),
             "algorithmic_bytes_per_launch": swa_bytes, "traffic": measured_traffic("based_swa_prefill", wl.name),

@@ -389,14 +389,16 @@ static hipError_t launch_swa_mfma16(const void *q, const void *k, const void *v,
 
 bool swa_prefill_mfma16_supported(int dh, int w, int dtype)
 {
-    // the one size where this tiling was measured to be the faster one (with d_h = 64 the 32-query kernel
-    // already holds two workgroups per CU and the two run alike)
-    return dtype == BASED_BF16 && dh == 128 && w == 64;
+    // the sizes where this tiling was measured to be the faster one: d_h = 128 with a ring that then fits a CU
+    // twice (with d_h = 64 the 32-query kernel already holds two workgroups per CU and the two run alike; with
+    // window 128 this one holds a single workgroup as well and is slower)
+    return dtype == BASED_BF16 && dh == 128 && (w == 32 || w == 64);
 }
 
 hipError_t launch_swa_prefill_mfma16(const void *q, const void *k, const void *v, void *y, void *ring, int U, int N,
                                      int dh, int w, float scale, hipStream_t s)
 {
+    if (dh == 128 && w == 32) return launch_swa_mfma16<128, 32>(q, k, v, y, ring, U, N, scale, s);
     if (dh == 128 && w == 64) return launch_swa_mfma16<128, 64>(q, k, v, y, ring, U, N, scale, s);
     return hipErrorInvalidValue;
 }

@@ -345,11 +345,12 @@ def test_decay_of_one_is_the_plain_method(based):
                                         (64, 16, 2, 2, 300), (128, 16, 1, 2, 150), (64, 32, 1, 2, 333),
                                         (128, 32, 1, 1, 260), (64, 16, 1, 1, 1), (128, 16, 1, 2, 15),
                                         (64, 16, 1, 1, 16), (64, 16, 1, 2, 17), (64, 32, 1, 1, 33),
-                                        # d_h 128 with window 64 (bf16: 16 queries to a wave, steps of 64):
+                                        # d_h 128 with window 64 or 32 (bf16: 16 queries to a wave, steps of 64):
                                         # one token, less than a tile, a step and one more, several
                                         # segments with a ragged last step
                                         (128, 64, 1, 1, 1), (128, 64, 1, 2, 17), (128, 64, 3, 1, 129),
-                                        (128, 64, 1, 1, 65), (128, 64, 2, 3, 1000)])
+                                        (128, 64, 1, 1, 65), (128, 64, 2, 3, 1000),
+                                        (128, 32, 1, 2, 17), (128, 32, 1, 1, 65), (128, 32, 2, 3, 1000)])
 def test_swa_prefill(based, dtype, dh, w, B, H, N):
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype=dtype)
     q, k, v = synth.swa_inputs(wl, units=B * H, N=N)
@@ -681,7 +682,7 @@ def test_decode_state_beyond_the_cache(based):
 @pytest.mark.parametrize("dh,w,N", [(64, 64, 1100), (128, 128, 1300), (64, 128, 2100), (128, 16, 1300),
                                     (64, 32, 1100),
                                     # 16 queries to a wave: many short segments, a last step of 20 and of 63 queries
-                                    (128, 64, 1300), (128, 64, 2047)])
+                                    (128, 64, 1300), (128, 64, 2047), (128, 32, 1300)])
 def test_swa_prefill_segmented(based, dh, w, N):
     """Sequences long enough to be cut into segments (ragged last step), every element checked."""
     wl = make_wl("prefill_360m", d_h=dh, w=w, dtype="bf16")
