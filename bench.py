@@ -476,7 +476,7 @@ def projection_leg(torch, based, dev, B: int, N: int, d_model: int, H: int, dp: 
         ms = a.elapsed_time(b) / R   # (includes the allocation of the outputs by the binding's caching allocator)
         tf = 2.0 * M * K * Nf / (ms * 1e-3) / 1e12
         res[name] = {"M": M, "K": K, "N": Nf, "ms": round(ms, 4),
-                     "roofline": {"kernel": f"{entry} (lin::linear_kernel)", "bound": "mfma", "achieved": round(tf, 1),
+                     "roofline": {"kernel": f"{entry} (lin::linear_wide_kernel, 256 x 256 tiles)", "bound": "mfma", "achieved": round(tf, 1),
                                   "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4)}}
     return res
 
