@@ -1201,6 +1201,47 @@ def test_project_qkv_and_out(based, B, N, dm, H, dp, dv):
         check_close(rows(down(out)), rows(oracle.project_out(yh, Wo)), TOL["bf16"], "project out")
 
 
+@pytest.mark.parametrize("K", [64, 128, 192, 1024])
+def test_linear_wide_tiles_sampled(based, K):
+    """The 256 x 256 tiling of the projections (taken when N is a multiple of 256 and there are at least 512
+    such tiles): a ragged last band of rows, one, two, three and many K steps (its loads run two steps ahead).
+    Sampled rows against the oracle, every output feature."""
+    M, N = 128 * 256 + 232, 1024          # 129 x 4 = 516 tiles
+    x, W = synth.linear_inputs(31, M, K, N)
+    y = based.linear(up(x, "bf16"), up(W, "bf16"))
+    torch.cuda.synchronize()
+    sample = np.array([0, 1, 31, 32, 127, 128, 255, 256, 257, 12345, 128 * 256 - 1, 128 * 256, M - 2, M - 1])
+    check_close(down(y)[sample], oracle.linear(x[sample], W), TOL["bf16"], f"wide tiles, K = {K}")
+
+
+def test_project_qkv_and_out_wide_tiles_sampled(based):
+    """based_project_qkv / based_project_out on the 256 x 256 tiling: the 1.3B-shaped head layout (16 heads,
+    d' 16, d_v 128) over 17 sequences of 2000 tokens (sequence ends inside tiles, a ragged last band), a short
+    d_model for the q / k / v projection.  Sampled (sequence, token) rows, every head and feature."""
+    B, N, dm, H, dp, dv = 17, 2000, 128, 16, 16, 128
+    Ntot = H * (2 * dp + dv)
+    x, W = synth.linear_inputs(32, B * N, dm, Ntot)
+    x = x.reshape(B, N, dm)
+    q, k, v = based.project_qkv(up(x, "bf16"), up(W, "bf16"), H, dp, dv)
+    torch.cuda.synchronize()
+    bs = np.array([0, 0, 0, 1, 7, 16, 16])
+    ts = np.array([0, 255, 1999, 0, 1234, 1998, 1999])
+    xs = x[bs, ts][:, None, :]                      # [samples, 1, d_model]: one-token sequences for the oracle
+    Wq, Wk, Wv = W[:H * dp], W[H * dp:2 * H * dp], W[2 * H * dp:]
+    for name, got, Wp in (("q", q, Wq), ("k", k, Wk), ("v", v, Wv)):
+        want = oracle.project_heads(xs, Wp, H)[:, :, 0, :]          # [samples, H, d]
+        check_close(rows(down(got)[bs, :, ts, :]), rows(want), TOL["bf16"], f"wide project {name}")
+    # the output projection reads the head-major mixer output: K = H d_v = 2048, N = 1792 (7 tiles wide)
+    dmo = 1792
+    yh = synth.linear_inputs(33, B * H * N, dv, 8)[0].reshape(B, H, N, dv)
+    Wo = synth.linear_inputs(34, 8, H * dv, dmo)[1]
+    out = based.project_out(up(yh, "bf16"), up(Wo, "bf16"))
+    torch.cuda.synchronize()
+    ys = np.stack([yh[b_, :, t_, :] for b_, t_ in zip(bs, ts)])[:, :, None, :]     # [samples, H, 1, d_v]
+    want = oracle.project_out(ys, Wo)[:, 0, :]
+    check_close(rows(down(out)[bs, ts]), rows(want), TOL["bf16"], "wide project out")
+
+
 def test_linear_attention_layer_chain(based):
     """A linear-attention layer end to end in the library's own layouts (project q, k, v -> prefill -> project
     out, no transposing pass in between) against the same chain in the oracle, each stage fed the GPU's
