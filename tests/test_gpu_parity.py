@@ -1203,14 +1203,14 @@ def test_project_qkv_and_out(based, B, N, dm, H, dp, dv):
 
 @pytest.mark.parametrize("K", [64, 128, 192, 1024])
 def test_linear_wide_tiles_sampled(based, K):
-    """The 256 x 256 tiling of the projections (taken when N is a multiple of 256 and there are at least 512
-    such tiles): a ragged last band of rows, one, two, three and many K steps (its loads run two steps ahead).
-    Sampled rows against the oracle, every output feature."""
-    M, N = 128 * 256 + 232, 1024          # 129 x 4 = 516 tiles
+    """The 256 x 256 tiling of the projections (taken when N is a multiple of 256 and the tiles fill whole
+    rounds of the chip well): a ragged last band of rows, one, two, three and many K steps (its loads run two
+    steps ahead).  Sampled rows against the oracle, every output feature."""
+    M, N = 127 * 256 + 232, 1024          # 128 x 4 = 512 tiles
     x, W = synth.linear_inputs(31, M, K, N)
     y = based.linear(up(x, "bf16"), up(W, "bf16"))
     torch.cuda.synchronize()
-    sample = np.array([0, 1, 31, 32, 127, 128, 255, 256, 257, 12345, 128 * 256 - 1, 128 * 256, M - 2, M - 1])
+    sample = np.array([0, 1, 31, 32, 127, 128, 255, 256, 257, 12345, 127 * 256 - 1, 127 * 256, M - 2, M - 1])
     check_close(down(y)[sample], oracle.linear(x[sample], W), TOL["bf16"], f"wide tiles, K = {K}")
 
 
